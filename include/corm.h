@@ -1,0 +1,150 @@
+/*
+ * corm.h -- C ABI of the MI355X (gfx950) decode hot path of CORM
+ * ("Cache Optimization with Recent Message", arXiv 2404.15949).
+ *
+ * One decode step, per layer, for every (sequence b, KV head h) "unit":
+ *   append  k_t, v_t                         (shapes of Algorithm 1: keys [l,d] include the current token)
+ *   attend  out = softmax(q K^T / sqrt(d)) V (Eq. 1) over the l LIVE keys of the unit only,
+ *           alpha_{t,i} the normalized scores (Eq. 2)
+ *   record  the scores of this query into row (t-1) mod w of a ring of the last w queries
+ *           (Section 4.2 "Approach": a recent window of size w records what each query finds important)
+ *   evict   a key survives iff some recorded query of the window (any query head of its group,
+ *           Section 5.3) gave it a score >= c/t_j (Def. 3.1, c = 1), or it is among the r newest
+ *           slots (Def. 4.1 and the recent-r protection of Section 4.2); nothing is evicted
+ *           while fewer than w rows are recorded (Algorithm 1)
+ *   compact K, V (and the per-key metadata) are gathered in ascending slot order
+ *           (the nonzero()/index step of Algorithm 1): a STABLE stream compaction.
+ *
+ * Conventions
+ * -----------
+ * Every pointer is a DEVICE pointer to caller-owned memory unless it says "host".  The library
+ * allocates and frees nothing; scratch lives in a caller-provided workspace.  Calls are
+ * asynchronous on `stream` (a hipStream_t passed as void*, NULL = the default stream) and never
+ * synchronize.  Every call returns 0 (CORM_OK) or a negative corm_status; argument errors are
+ * detected on the host before anything is launched.  Conditions only the device can see
+ * (a full unit, a step beyond the ring's columns) never fault: the kernel skips the offending
+ * write and ORs a bit into the optional `status` word.
+ *
+ * Layouts (row-major, sizes in elements)
+ *   q              [B, Hq, d]            kv_dtype        query of the current token per head
+ *   k_new, v_new   [B, Hkv, d]           kv_dtype        key/value of the current token
+ *   K, V           [B, Hkv, Lcap, d]     kv_dtype        slot i of a unit is one contiguous row; only
+ *                                                        slots < lens[b,h] are live; 16-byte aligned
+ *   lens           [B, Hkv]              int32           live keys per unit
+ *   pos            [B, Hkv, Lcap]        int32           absolute 0-based token position of each slot,
+ *                                                        strictly increasing within a unit
+ *   last_hit       [B, Hkv, Lcap]        int32           last step at which some head of the group found
+ *                                                        the key important; 0 = never
+ *   t              [B]                   int32           absolute 1-based step of the current query
+ *                                                        (tokens of the sequence so far, incl. this one)
+ *   t_first        [B]                   int32           step of the oldest row ever recorded in the ring;
+ *                                                        the window is full iff t - t_first + 1 >= w
+ *   score_ring     [B, Hq, w, Tcap]      score_dtype     row (tau-1) mod w holds the scores of step tau,
+ *                                                        column = ABSOLUTE position of the key, so rows
+ *                                                        never need compaction
+ *   out            [B, Hq, d]            float32
+ *   keep           [B, Hkv, Lcap]        uint8           1 = survives; entries >= lens are unspecified
+ *   kept_idx       [B, Hkv, Lcap]        int32           old slot of the j-th survivor, ascending
+ * Slots >= lens' after a compaction hold unspecified data.
+ *
+ * Arithmetic: logits and all accumulation in fp32; scores are rounded (nearest-even) to
+ * score_dtype when stored, and the importance test compares the STORED value, widened to fp32,
+ * against fp32(c) / fp32(t) (IEEE division) with >=.
+ */
+#ifndef CORM_H
+#define CORM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum corm_dtype { CORM_F32 = 0, CORM_BF16 = 1 };
+
+enum corm_status {
+  CORM_OK = 0,
+  CORM_EINVAL = -1,       /* null / misaligned pointer, bad shape, w < 1, r < 1, c < 0 ...      */
+  CORM_EUNSUPPORTED = -2, /* d not in {64,128}, group size not in {1,2,4,8}, unknown dtype      */
+  CORM_ECAPACITY = -3,    /* workspace too small (host); device: see CORM_DEV_* bits             */
+  CORM_EHIP = -4          /* a HIP call or launch failed                                         */
+};
+
+/* bits ORed into the optional device status word */
+enum corm_dev_status {
+  CORM_DEV_UNIT_FULL = 1, /* append skipped: lens == Lcap                                        */
+  CORM_DEV_BAD_STEP = 2,  /* t < 1 or t > Tcap or a position outside [0,Tcap): record skipped   */
+  CORM_DEV_BAD_LENS = 4   /* lens outside [0,Lcap]: clamped                                      */
+};
+
+typedef struct corm_desc {
+  int32_t B, Hq, Hkv, d; /* d in {64,128}; Hq % Hkv == 0; G = Hq/Hkv in {1,2,4,8}                */
+  int32_t Lcap;          /* slots per unit                                                        */
+  int32_t Tcap;          /* ring columns = largest absolute position + 1                          */
+  int32_t w, r;          /* recent-query window, protected newest slots; both >= 1                */
+  int32_t kv_dtype;      /* corm_dtype of q, K, V, k_new, v_new                                   */
+  int32_t score_dtype;   /* corm_dtype of score_ring                                              */
+  float thr_scale;       /* c in the threshold c/t; 1 = Def. 3.1; 0 = everything important        */
+  float sm_scale;        /* logit scale; 0 selects 1/sqrt(d) (Eq. 1)                              */
+} corm_desc;
+
+int corm_version(void);
+const char* corm_strerror(int status);
+
+/* Bytes of workspace the attend/step calls need for this descriptor (host call). */
+int corm_workspace_bytes(const corm_desc* desc, size_t* bytes);
+
+/* Zero the workspace's arrival counters.  Once after allocation (the calls leave them zero). */
+int corm_workspace_init(const corm_desc* desc, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Append (shapes of Algorithm 1): K[b,h,lens] = k_new, V likewise, pos = t-1, last_hit = 0, lens += 1.
+ * A full unit is left unchanged and flagged in *status (may be NULL). */
+int corm_append(const corm_desc* desc, void* K, void* V, int32_t* lens, int32_t* pos, int32_t* last_hit,
+                const void* k_new, const void* v_new, const int32_t* t, int32_t* status, void* stream);
+
+/* Attend + record (Eq. 1, Eq. 2, Def. 3.1): for every query head, exact softmax attention over the
+ * live keys of its unit -> out; the normalized scores are written to ring row (t-1) mod w at the
+ * keys' absolute positions, and last_hit[i] = t for keys some head of the group scores >= c/t.
+ * Reads K, V, lens, pos; writes out, score_ring, last_hit, workspace.  A unit with lens == 0
+ * yields out = 0 and records nothing. */
+int corm_decode_attend(const corm_desc* desc, const void* q, const void* K, const void* V,
+                       const int32_t* lens, const int32_t* pos, const int32_t* t, void* score_ring,
+                       int32_t* last_hit, float* out, void* workspace, size_t workspace_bytes,
+                       int32_t* status, void* stream);
+
+/* Eviction decision from the ring alone (Def. 4.1 + recent-r rule + Section 5.3 group rule),
+ * evaluated literally: keep[i] = OR over the recorded rows tau in [max(t_first, t-w+1), t] and the
+ * G heads of the group of (ring[tau][pos_i] >= c/tau), OR i >= lens - r.  If fewer than w rows are
+ * recorded every live key is kept (Algorithm 1). */
+int corm_evict_mask(const corm_desc* desc, const void* score_ring, const int32_t* lens, const int32_t* pos,
+                    const int32_t* t, const int32_t* t_first, uint8_t* keep, void* stream);
+
+/* The same decision from the per-key summary: keep[i] = last_hit[i] > t - w  OR  i >= lens - r
+ * (equal to corm_evict_mask when last_hit was maintained by corm_decode_attend over the window). */
+int corm_evict_mask_summary(const corm_desc* desc, const int32_t* last_hit, const int32_t* lens,
+                            const int32_t* t, const int32_t* t_first, uint8_t* keep, void* stream);
+
+/* Stable per-unit compaction (the gather of Algorithm 1), in place: survivors keep their order;
+ * K, V, pos, last_hit rows move to slot (number of survivors before them); lens = survivors.
+ * kept_idx (may be NULL) receives the old slot of each survivor. */
+int corm_compact(const corm_desc* desc, void* K, void* V, int32_t* pos, int32_t* last_hit, int32_t* lens,
+                 const uint8_t* keep, int32_t* kept_idx, void* stream);
+
+/* One fused decode step = append, attend, record, evict, compact, in Algorithm 1's order (the
+ * current query attends over ALL l keys, eviction takes effect from the next step).  Same bits
+ * as corm_append + corm_decode_attend + corm_evict_mask + corm_compact.  keep and kept_idx may
+ * be NULL; when given they describe the slots as they were after the append. */
+int corm_decode_step(const corm_desc* desc, const void* q, const void* k_new, const void* v_new,
+                     void* K, void* V, int32_t* lens, int32_t* pos, int32_t* last_hit,
+                     const int32_t* t, const int32_t* t_first, void* score_ring, float* out,
+                     uint8_t* keep, int32_t* kept_idx, void* workspace, size_t workspace_bytes,
+                     int32_t* status, void* stream);
+
+/* Diagnostic: thr[i] = fp32(c) / fp32(t[i]) exactly as the kernels compute it (Def. 3.1). */
+int corm_threshold(float c, const int32_t* t, int32_t n, float* thr, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CORM_H */

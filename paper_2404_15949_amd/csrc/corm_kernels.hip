@@ -1,0 +1,891 @@
+// HIP kernels (gfx950 / CDNA4, wave64) and C ABI of the CORM decode hot path.
+//
+// One launch handles one layer's step for all (sequence, KV head) units:
+//   grid = (splits, units); workgroup (split s, unit u) streams keys [s*CHUNK, (s+1)*CHUNK) of
+//   the unit once: q.k logits (Eq. 2 numerator), an online-softmax partial (max, sum, sum p*v)
+//   in fp32, raw logits to scratch.  The last workgroup of a unit to arrive (one atomic per
+//   workgroup, no spinning) merges the partials -> out (Eq. 1), turns the logits into normalized
+//   scores, writes the ring row, updates last_hit (Def. 3.1), decides keep (Def. 4.1 + recent r),
+//   and compacts the unit in place in ascending tile order (Algorithm 1's gather).
+//
+// Row geometry: a K/V row is d*sizeof(T) bytes (256 B for bf16 d=128 and fp32 d=64); each lane
+// owns 16 bytes of a row, so LPR = row_bytes/16 lanes share a row and one wave-wide 16-byte
+// load covers 64/LPR consecutive rows = 1 KiB of contiguous memory.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <math.h>
+#include <cmath>
+
+#include "corm.h"
+
+namespace {
+
+constexpr int WG = 256;          // threads per workgroup
+constexpr int WAVES = WG / 64;   // waves per workgroup
+constexpr int CHUNK = 512;       // keys per split
+constexpr int UNROLL = 4;        // 16-byte K loads (and V loads) in flight per lane and iteration
+constexpr float LOG2E = 1.4426950408889634f;
+
+struct Params {
+  const void* q;
+  const void* k_new;
+  const void* v_new;
+  void* K;
+  void* V;
+  int32_t* lens;
+  int32_t* pos;
+  int32_t* last_hit;
+  const int32_t* t;
+  const int32_t* t_first;
+  void* ring;
+  float* out;
+  uint8_t* keep_out;
+  int32_t* kept_idx;
+  int32_t* counters;
+  float* partials;
+  float* logits;
+  int32_t* status;
+  int32_t B, Hq, Hkv, Lcap, Tcap, w, r, nsplit;
+  float thr_scale, scale_log2;
+  int32_t do_append, do_evict, ring_bf16;
+};
+
+// ---------------------------------------------------------------- small device helpers
+
+__device__ __forceinline__ float bf16_lo(uint32_t x) { return __uint_as_float(x << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t x) { return __uint_as_float(x & 0xffff0000u); }
+
+// fp32 -> bf16 bits, round to nearest even (NaN stays NaN)
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c,
+                                         false);
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+
+// sum over the LPR lanes that share a row; every lane of the group gets the total
+template <int LPR>
+__device__ __forceinline__ float row_allreduce_sum(float v) {
+  v += dpp_f32<0xB1>(v);                    // quad_perm [1,0,3,2]
+  v += dpp_f32<0x4E>(v);                    // quad_perm [2,3,0,1]
+  v += dpp_f32<0x141>(v);                   // row_half_mirror: lanes 0..7 of each 16 are now equal
+  if (LPR >= 16) v += dpp_f32<0x140>(v);    // row_mirror
+  if (LPR >= 32) v += __shfl_xor(v, 16);
+  return v;
+}
+
+struct F32 {
+  static constexpr int EPL = 4;  // elements per 16-byte lane slice
+  static constexpr int ESZ = 4;
+  __device__ static __forceinline__ float dot(const uint4& k, const uint4& q) {
+    float s = __uint_as_float(k.x) * __uint_as_float(q.x);
+    s = fmaf(__uint_as_float(k.y), __uint_as_float(q.y), s);
+    s = fmaf(__uint_as_float(k.z), __uint_as_float(q.z), s);
+    s = fmaf(__uint_as_float(k.w), __uint_as_float(q.w), s);
+    return s;
+  }
+  __device__ static __forceinline__ void axpy(float* acc, float p, const uint4& v) {
+    acc[0] = fmaf(p, __uint_as_float(v.x), acc[0]);
+    acc[1] = fmaf(p, __uint_as_float(v.y), acc[1]);
+    acc[2] = fmaf(p, __uint_as_float(v.z), acc[2]);
+    acc[3] = fmaf(p, __uint_as_float(v.w), acc[3]);
+  }
+};
+
+struct BF16 {
+  static constexpr int EPL = 8;
+  static constexpr int ESZ = 2;
+  __device__ static __forceinline__ float dot(const uint4& k, const uint4& q) {
+    float s = dot2_bf16(k.x, q.x, 0.f);
+    s = dot2_bf16(k.y, q.y, s);
+    s = dot2_bf16(k.z, q.z, s);
+    s = dot2_bf16(k.w, q.w, s);
+    return s;
+  }
+  __device__ static __forceinline__ void axpy(float* acc, float p, const uint4& v) {
+    acc[0] = fmaf(p, bf16_lo(v.x), acc[0]);
+    acc[1] = fmaf(p, bf16_hi(v.x), acc[1]);
+    acc[2] = fmaf(p, bf16_lo(v.y), acc[2]);
+    acc[3] = fmaf(p, bf16_hi(v.y), acc[3]);
+    acc[4] = fmaf(p, bf16_lo(v.z), acc[4]);
+    acc[5] = fmaf(p, bf16_hi(v.z), acc[5]);
+    acc[6] = fmaf(p, bf16_lo(v.w), acc[6]);
+    acc[7] = fmaf(p, bf16_hi(v.w), acc[7]);
+  }
+};
+
+__device__ __forceinline__ float neg_inf() { return -__builtin_inff(); }
+
+// Def. 3.1 threshold: IEEE fp32 quotient c / t
+__device__ __forceinline__ float importance_threshold(float c, int32_t t) { return __fdiv_rn(c, (float)t); }
+
+// vmcnt(0), expcnt and lgkmcnt left at their maxima (gfx9 encoding)
+__device__ __forceinline__ void wait_vm_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
+// ---------------------------------------------------------------- stable in-place compaction of one unit
+//
+// Called by all WG threads of ONE workgroup.  Tiles of WG slots in ascending order; for each tile:
+// keep flags -> exclusive scan (ballot + popcount per wave, LDS across waves, running base across
+// tiles) -> metadata moves -> cooperative row moves of K and V.  Because every destination is <=
+// its source and tiles ascend, a tile's writes can only land on slots whose contents were already
+// read; inside a tile all reads complete (explicit wait + barrier) before any write.
+
+struct CompactShared {
+  int32_t wave_count[WAVES];
+  int32_t src_of[WG];
+};
+
+template <int ROWB>
+__device__ __forceinline__ void move_rows(char* Kb, char* Vb, const int32_t* src_of, int n_rows, int dst_base) {
+  constexpr int LPR = ROWB / 16;
+  constexpr int RPP = WG / LPR;  // rows per pass of the workgroup
+  const int tid = threadIdx.x;
+  const int sub = tid / LPR;
+  const size_t col = (size_t)(tid % LPR) * 16;
+  // four passes are in flight together (named registers: an indexed array would be demoted to scratch)
+  for (int base = 0; base < n_rows; base += RPP * 4) {
+    const int j0 = base + sub, j1 = j0 + RPP, j2 = j1 + RPP, j3 = j2 + RPP;
+    const int last = n_rows - 1;
+    // clamped row numbers: every load reads a valid row, stores are predicated
+    const size_t o0 = (size_t)src_of[min(j0, last)] * ROWB + col;
+    const size_t o1 = (size_t)src_of[min(j1, last)] * ROWB + col;
+    const size_t o2 = (size_t)src_of[min(j2, last)] * ROWB + col;
+    const size_t o3 = (size_t)src_of[min(j3, last)] * ROWB + col;
+    const uint4 k0 = *reinterpret_cast<const uint4*>(Kb + o0);
+    const uint4 k1 = *reinterpret_cast<const uint4*>(Kb + o1);
+    const uint4 k2 = *reinterpret_cast<const uint4*>(Kb + o2);
+    const uint4 k3 = *reinterpret_cast<const uint4*>(Kb + o3);
+    const uint4 v0 = *reinterpret_cast<const uint4*>(Vb + o0);
+    const uint4 v1 = *reinterpret_cast<const uint4*>(Vb + o1);
+    const uint4 v2 = *reinterpret_cast<const uint4*>(Vb + o2);
+    const uint4 v3 = *reinterpret_cast<const uint4*>(Vb + o3);
+    wait_vm_loads();
+    __syncthreads();
+    if (j0 < n_rows) {
+      const size_t d = (size_t)(dst_base + j0) * ROWB + col;
+      *reinterpret_cast<uint4*>(Kb + d) = k0;
+      *reinterpret_cast<uint4*>(Vb + d) = v0;
+    }
+    if (j1 < n_rows) {
+      const size_t d = (size_t)(dst_base + j1) * ROWB + col;
+      *reinterpret_cast<uint4*>(Kb + d) = k1;
+      *reinterpret_cast<uint4*>(Vb + d) = v1;
+    }
+    if (j2 < n_rows) {
+      const size_t d = (size_t)(dst_base + j2) * ROWB + col;
+      *reinterpret_cast<uint4*>(Kb + d) = k2;
+      *reinterpret_cast<uint4*>(Vb + d) = v2;
+    }
+    if (j3 < n_rows) {
+      const size_t d = (size_t)(dst_base + j3) * ROWB + col;
+      *reinterpret_cast<uint4*>(Kb + d) = k3;
+      *reinterpret_cast<uint4*>(Vb + d) = v3;
+    }
+  }
+}
+
+// One tile step of the scan.  keep: this thread's flag (0 for slots >= L).  Returns this thread's
+// rank among the tile's survivors and the tile's survivor count (via *tile_kept).
+__device__ __forceinline__ int tile_scan(bool keep, CompactShared& sh, int* tile_kept) {
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  unsigned long long bal = __ballot(keep);
+  int rank = __popcll(bal & ((1ull << lane) - 1ull));
+  if (lane == 0) sh.wave_count[wv] = __popcll(bal);
+  __syncthreads();
+  int before = 0, total = 0;
+#pragma unroll
+  for (int i = 0; i < WAVES; ++i) {
+    int c = sh.wave_count[i];
+    if (i < wv) before += c;
+    total += c;
+  }
+  *tile_kept = total;
+  return before + rank;
+}
+
+// ---------------------------------------------------------------- the fused step kernel
+
+template <typename DT, int D, int G>
+__global__ __launch_bounds__(WG) void corm_step_kernel(const Params p) {
+  constexpr int EPL = DT::EPL;
+  constexpr int ROWB = D * DT::ESZ;
+  constexpr int LPR = ROWB / 16;    // lanes per row
+  constexpr int RPL = 64 / LPR;     // rows per wave-wide load
+  constexpr int U = UNROLL;
+  static_assert(U <= LPR, "logit store uses one lane per unrolled load");
+
+  const int split = blockIdx.x;
+  const int unit = blockIdx.y;
+  const int b = unit / p.Hkv;
+  const int hkv = unit - b * p.Hkv;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wv = tid >> 6;
+  const int sub = lane / LPR, cl = lane % LPR;
+
+  __shared__ float sh_m[G][WAVES];
+  __shared__ float sh_z[G][WAVES];
+  __shared__ float sh_acc[G][WAVES][D];
+  __shared__ float sh_M[G], sh_Z[G];
+  __shared__ int sh_flag;
+  __shared__ CompactShared sh_c;
+
+  // ---- unit geometry
+  int L0 = p.lens[unit];
+  if (L0 < 0 || L0 > p.Lcap) {
+    if (tid == 0 && split == 0 && p.status) atomicOr(p.status, CORM_DEV_BAD_LENS);
+    L0 = L0 < 0 ? 0 : p.Lcap;
+  }
+  int L = L0;
+  bool appended = false;
+  if (p.do_append) {
+    if (L0 < p.Lcap) {
+      L = L0 + 1;
+      appended = true;
+    } else if (tid == 0 && split == 0 && p.status) {
+      atomicOr(p.status, CORM_DEV_UNIT_FULL);
+    }
+  }
+  // splits that hold live keys; the others only take part in the arrival count, so that nobody
+  // reads lens[unit] after the finalizing workgroup has rewritten it
+  const int nlive = (L + CHUNK - 1) / CHUNK;
+  const int tcur = p.t[b];
+
+  char* Kb = reinterpret_cast<char*>(p.K) + (size_t)unit * p.Lcap * ROWB;
+  char* Vb = reinterpret_cast<char*>(p.V) + (size_t)unit * p.Lcap * ROWB;
+  const char* knew = reinterpret_cast<const char*>(p.k_new) + (size_t)unit * ROWB;
+  const char* vnew = reinterpret_cast<const char*>(p.v_new) + (size_t)unit * ROWB;
+  int32_t* posb = p.pos + (size_t)unit * p.Lcap;
+  int32_t* lhb = p.last_hit + (size_t)unit * p.Lcap;
+  const int hq0 = hkv * G;
+
+  // ---- this lane's slice of the G queries
+  uint4 qreg[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+    qreg[g] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(p.q) +
+                                              ((size_t)(b * p.Hq + hq0 + g) * ROWB + (size_t)cl * 16));
+
+  const int cbeg = split * CHUNK;
+  const int cend = min(cbeg + CHUNK, L);
+  constexpr int PSTRIDE = D + 2;  // partial of one split and head: [max, sum, acc[D]]
+  float* logit_u = p.logits + (size_t)(b * p.Hq + hq0) * p.Lcap;
+
+  if (split < nlive) {
+
+  // the appended row: the owner of its chunk writes it into the cache (one wave) ...
+  if (appended && L0 >= cbeg && L0 < cend && wv == 0) {
+    if (lane < LPR) {
+      uint4 kx = *reinterpret_cast<const uint4*>(knew + (size_t)lane * 16);
+      uint4 vx = *reinterpret_cast<const uint4*>(vnew + (size_t)lane * 16);
+      *reinterpret_cast<uint4*>(Kb + (size_t)L0 * ROWB + (size_t)lane * 16) = kx;
+      *reinterpret_cast<uint4*>(Vb + (size_t)L0 * ROWB + (size_t)lane * 16) = vx;
+    }
+    if (lane == 0) {
+      posb[L0] = tcur - 1;
+      lhb[L0] = 0;
+    }
+  }
+
+  float m_run[G], z_run[G], acc[G][EPL];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    m_run[g] = neg_inf();
+    z_run[g] = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+  }
+
+  for (int it = cbeg; it < cend; it += WAVES * RPL * U) {
+    uint4 kreg[U], vreg[U];
+    int row[U];
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+      row[j] = it + (j * WAVES + wv) * RPL + sub;
+      int rc = min(row[j], cend - 1);
+      // ... and everybody reads that row from the step's input, not from the cache
+      const char* kp = (appended && rc == L0) ? knew : Kb + (size_t)rc * ROWB;
+      kreg[j] = *reinterpret_cast<const uint4*>(kp + (size_t)cl * 16);
+    }
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+      int rc = min(row[j], cend - 1);
+      const char* vp = (appended && rc == L0) ? vnew : Vb + (size_t)rc * ROWB;
+      vreg[j] = *reinterpret_cast<const uint4*>(vp + (size_t)cl * 16);
+    }
+
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float s[U];
+      float my_logit = 0.f;
+      int my_row = -1;
+#pragma unroll
+      for (int j = 0; j < U; ++j) {
+        float part = DT::dot(kreg[j], qreg[g]);
+        float tot = row_allreduce_sum<LPR>(part) * p.scale_log2;
+        s[j] = row[j] < cend ? tot : neg_inf();
+        if (cl == j && row[j] < cend) {
+          my_logit = tot;
+          my_row = row[j];
+        }
+      }
+      if (my_row >= 0) logit_u[(size_t)g * p.Lcap + my_row] = my_logit;
+
+      float mnew = m_run[g];
+#pragma unroll
+      for (int j = 0; j < U; ++j) mnew = fmaxf(mnew, s[j]);
+      const float msafe = mnew == neg_inf() ? 0.f : mnew;
+      const float a = exp2f(m_run[g] - msafe);
+      float pj[U];
+      float zs = 0.f;
+#pragma unroll
+      for (int j = 0; j < U; ++j) {
+        pj[j] = exp2f(s[j] - msafe);
+        zs += pj[j];
+      }
+      z_run[g] = fmaf(z_run[g], a, zs);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[g][e] *= a;
+#pragma unroll
+      for (int j = 0; j < U; ++j) DT::axpy(acc[g], pj[j], vreg[j]);
+      m_run[g] = mnew;
+    }
+  }
+
+  // ---- merge the RPL row groups of the wave (lanes differing in bits >= log2(LPR)), then the waves
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) {
+      float mo = __shfl_xor(m_run[g], off);
+      float zo = __shfl_xor(z_run[g], off);
+      float mn = fmaxf(m_run[g], mo);
+      float ms = mn == neg_inf() ? 0.f : mn;
+      float a0 = exp2f(m_run[g] - ms), a1 = exp2f(mo - ms);
+      z_run[g] = z_run[g] * a0 + zo * a1;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) {
+        float ao = __shfl_xor(acc[g][e], off);
+        acc[g][e] = acc[g][e] * a0 + ao * a1;
+      }
+      m_run[g] = mn;
+    }
+    if (sub == 0) {
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) sh_acc[g][wv][cl * EPL + e] = acc[g][e];
+      if (cl == 0) {
+        sh_m[g][wv] = m_run[g];
+        sh_z[g][wv] = z_run[g];
+      }
+    }
+  }
+  __syncthreads();
+
+  // partial of this split: [m, z, acc[D]] per query head
+  for (int idx = tid; idx < G * D; idx += WG) {
+    const int g = idx / D, c = idx - g * D;
+    float mw[WAVES];
+    float mx = neg_inf();
+#pragma unroll
+    for (int i = 0; i < WAVES; ++i) {
+      mw[i] = sh_m[g][i];
+      mx = fmaxf(mx, mw[i]);
+    }
+    const float ms = mx == neg_inf() ? 0.f : mx;
+    float zt = 0.f, at = 0.f;
+#pragma unroll
+    for (int i = 0; i < WAVES; ++i) {
+      float a = exp2f(mw[i] - ms);
+      zt = fmaf(sh_z[g][i], a, zt);
+      at = fmaf(sh_acc[g][i][c], a, at);
+    }
+    float* part = p.partials + ((size_t)(b * p.Hq + hq0 + g) * p.nsplit + split) * PSTRIDE;
+    part[2 + c] = at;
+    if (c == 0) {
+      part[0] = mx;
+      part[1] = zt;
+    }
+  }
+
+  }  // split < nlive
+
+  // ---- arrival: the last workgroup of the unit finalizes it
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    int old = atomicAdd(&p.counters[unit], 1);
+    int last = (old == (int)gridDim.x - 1);
+    if (last) p.counters[unit] = 0;  // leave the counter ready for the next launch
+    sh_flag = last;
+  }
+  __syncthreads();
+  if (!sh_flag) return;
+  __threadfence();
+
+  // ---- merge the split partials -> out (Eq. 1), and the global max / sum of Eq. 2
+  for (int g = 0; g < G; ++g) {
+    const float* part0 = p.partials + (size_t)(b * p.Hq + hq0 + g) * p.nsplit * PSTRIDE;
+    float mx = neg_inf();
+    for (int s = 0; s < nlive; ++s) mx = fmaxf(mx, part0[(size_t)s * PSTRIDE]);
+    const float ms = mx == neg_inf() ? 0.f : mx;
+    if (tid < D) {
+      float zt = 0.f, at = 0.f;
+      for (int s = 0; s < nlive; ++s) {
+        const float* ps = part0 + (size_t)s * PSTRIDE;
+        float a = exp2f(ps[0] - ms);
+        zt = fmaf(ps[1], a, zt);
+        at = fmaf(ps[2 + tid], a, at);
+      }
+      p.out[(size_t)(b * p.Hq + hq0 + g) * D + tid] = L > 0 ? at / zt : 0.f;
+      if (tid == 0) {
+        sh_M[g] = ms;
+        sh_Z[g] = zt;
+      }
+    }
+  }
+  __syncthreads();
+  if (L == 0) {
+    return;
+  }
+
+  // ---- record (Def. 3.1), decide (Def. 4.1 + recent r), compact (Algorithm 1's gather)
+  const bool step_ok = tcur >= 1 && tcur <= p.Tcap;
+  if (!step_ok && tid == 0 && p.status) atomicOr(p.status, CORM_DEV_BAD_STEP);
+  const int slot = step_ok ? (tcur - 1) % p.w : 0;
+  const float thr = importance_threshold(p.thr_scale, step_ok ? tcur : 1);
+  const bool full = p.do_evict && step_ok && (tcur - p.t_first[b] + 1 >= p.w);
+  uint8_t* keepb = p.keep_out ? p.keep_out + (size_t)unit * p.Lcap : nullptr;
+  int32_t* idxb = p.kept_idx ? p.kept_idx + (size_t)unit * p.Lcap : nullptr;
+
+  int dst_base = 0;  // survivors before the current tile
+  for (int tile = 0; tile < L; tile += WG) {
+    const int i = tile + tid;
+    const bool live = i < L;
+    bool keep = false;
+    int my_pos = 0, my_lh = 0;
+    bool hit = false;
+    if (live) {
+      my_pos = posb[i];
+      my_lh = lhb[i];
+      const bool pos_ok = my_pos >= 0 && my_pos < p.Tcap;
+      if (!pos_ok && p.status) atomicOr(p.status, CORM_DEV_BAD_STEP);
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float lg = logit_u[(size_t)g * p.Lcap + i];
+        float sc = exp2f(lg - sh_M[g]) / sh_Z[g];
+        float stored;
+        size_t ri = ((size_t)(b * p.Hq + hq0 + g) * p.w + slot) * p.Tcap + (size_t)my_pos;
+        if (p.ring_bf16) {
+          uint16_t hb = f32_to_bf16_rne(sc);
+          stored = __uint_as_float((uint32_t)hb << 16);
+          if (step_ok && pos_ok) reinterpret_cast<uint16_t*>(p.ring)[ri] = hb;
+        } else {
+          stored = sc;
+          if (step_ok && pos_ok) reinterpret_cast<float*>(p.ring)[ri] = sc;
+        }
+        hit |= (stored >= thr);
+      }
+      if (hit && step_ok) my_lh = tcur;
+      keep = !full || (my_lh > tcur - p.w) || (i >= L - p.r);
+    }
+    if (!p.do_evict) {
+      if (live && hit && step_ok) lhb[i] = my_lh;
+      continue;
+    }
+    int tile_kept;
+    const int rank = tile_scan(keep, sh_c, &tile_kept);
+    const int dst = dst_base + rank;
+    if (live && keepb) keepb[i] = keep ? 1 : 0;
+    if (keep) {
+      sh_c.src_of[rank] = i;
+      if (idxb) idxb[dst] = i;
+      if (dst != i) {
+        posb[dst] = my_pos;
+        lhb[dst] = my_lh;
+      } else if (hit) {
+        lhb[i] = my_lh;
+      }
+    }
+    __syncthreads();
+    const int tile_n = min(WG, L - tile);
+    if (!(dst_base == tile && tile_kept == tile_n)) move_rows<ROWB>(Kb, Vb, sh_c.src_of, tile_kept, dst_base);
+    dst_base += tile_kept;
+    __syncthreads();
+  }
+  if (tid == 0 && (p.do_evict || p.do_append)) p.lens[unit] = p.do_evict ? dst_base : L;
+}
+
+// ---------------------------------------------------------------- standalone kernels
+
+__global__ __launch_bounds__(64) void corm_append_kernel(char* K, char* V, int32_t* lens, int32_t* pos,
+                                                         int32_t* last_hit, const char* k_new, const char* v_new,
+                                                         const int32_t* t, int32_t* status, int Hkv, int Lcap,
+                                                         int rowb) {
+  const int unit = blockIdx.x;
+  const int b = unit / Hkv;
+  const int L0 = lens[unit];
+  if (L0 < 0 || L0 >= Lcap) {
+    if (threadIdx.x == 0 && status) atomicOr(status, L0 == Lcap ? CORM_DEV_UNIT_FULL : CORM_DEV_BAD_LENS);
+    return;
+  }
+  const int lane = threadIdx.x;
+  if (lane * 16 < rowb) {
+    size_t dst = ((size_t)unit * Lcap + L0) * rowb + (size_t)lane * 16;
+    size_t src = (size_t)unit * rowb + (size_t)lane * 16;
+    *reinterpret_cast<uint4*>(K + dst) = *reinterpret_cast<const uint4*>(k_new + src);
+    *reinterpret_cast<uint4*>(V + dst) = *reinterpret_cast<const uint4*>(v_new + src);
+  }
+  if (lane == 0) {
+    pos[(size_t)unit * Lcap + L0] = t[b] - 1;
+    last_hit[(size_t)unit * Lcap + L0] = 0;
+    lens[unit] = L0 + 1;
+  }
+}
+
+// literal windowed OR over the ring (Def. 4.1 + recent r + group rule)
+__global__ __launch_bounds__(WG) void corm_evict_mask_kernel(const void* ring, int ring_bf16, const int32_t* lens,
+                                                             const int32_t* pos, const int32_t* t,
+                                                             const int32_t* t_first, uint8_t* keep, int Hq, int Hkv,
+                                                             int Lcap, int Tcap, int w, int r, float c) {
+  const int unit = blockIdx.y;
+  const int b = unit / Hkv, hkv = unit - b * Hkv;
+  const int G = Hq / Hkv;
+  int L = lens[unit];
+  L = L < 0 ? 0 : (L > Lcap ? Lcap : L);
+  const int i = blockIdx.x * WG + threadIdx.x;
+  if (i >= L) return;
+  const int tcur = t[b];
+  const int tf = t_first[b];
+  bool k = i >= L - r;
+  const bool full = tcur - tf + 1 >= w;
+  if (!full) k = true;
+  const int pi = pos[(size_t)unit * Lcap + i];
+  if (!k && pi >= 0 && pi < Tcap) {
+    const int lo = max(max(tf, tcur - w + 1), 1);
+    for (int tau = tcur; tau >= lo && !k; --tau) {
+      if (pi > tau - 1) break;  // the key did not exist at step tau (nor earlier): minor there
+      const float thr = importance_threshold(c, tau);
+      const int slot = (tau - 1) % w;
+      for (int g = 0; g < G; ++g) {
+        size_t ri = ((size_t)(b * Hq + hkv * G + g) * w + slot) * Tcap + (size_t)pi;
+        float v = ring_bf16 ? __uint_as_float((uint32_t) reinterpret_cast<const uint16_t*>(ring)[ri] << 16)
+                            : reinterpret_cast<const float*>(ring)[ri];
+        k |= (v >= thr);
+      }
+    }
+  }
+  keep[(size_t)unit * Lcap + i] = k ? 1 : 0;
+}
+
+__global__ __launch_bounds__(WG) void corm_evict_mask_summary_kernel(const int32_t* last_hit, const int32_t* lens,
+                                                                     const int32_t* t, const int32_t* t_first,
+                                                                     uint8_t* keep, int Hkv, int Lcap, int w, int r) {
+  const int unit = blockIdx.y;
+  const int b = unit / Hkv;
+  int L = lens[unit];
+  L = L < 0 ? 0 : (L > Lcap ? Lcap : L);
+  const int i = blockIdx.x * WG + threadIdx.x;
+  if (i >= L) return;
+  const int tcur = t[b];
+  const bool full = tcur - t_first[b] + 1 >= w;
+  const bool k = !full || last_hit[(size_t)unit * Lcap + i] > tcur - w || i >= L - r;
+  keep[(size_t)unit * Lcap + i] = k ? 1 : 0;
+}
+
+template <int ROWB>
+__global__ __launch_bounds__(WG) void corm_compact_kernel(char* K, char* V, int32_t* pos, int32_t* last_hit,
+                                                          int32_t* lens, const uint8_t* keep, int32_t* kept_idx,
+                                                          int Lcap) {
+  __shared__ CompactShared sh_c;
+  const int unit = blockIdx.x;
+  const int tid = threadIdx.x;
+  int L = lens[unit];
+  L = L < 0 ? 0 : (L > Lcap ? Lcap : L);
+  char* Kb = K + (size_t)unit * Lcap * ROWB;
+  char* Vb = V + (size_t)unit * Lcap * ROWB;
+  int32_t* posb = pos + (size_t)unit * Lcap;
+  int32_t* lhb = last_hit + (size_t)unit * Lcap;
+  const uint8_t* keepb = keep + (size_t)unit * Lcap;
+  int32_t* idxb = kept_idx ? kept_idx + (size_t)unit * Lcap : nullptr;
+  int dst_base = 0;
+  for (int tile = 0; tile < L; tile += WG) {
+    const int i = tile + tid;
+    const bool live = i < L;
+    const bool kp = live && keepb[i] != 0;
+    int my_pos = 0, my_lh = 0;
+    if (kp) {
+      my_pos = posb[i];
+      my_lh = lhb[i];
+    }
+    wait_vm_loads();
+    int tile_kept;
+    const int rank = tile_scan(kp, sh_c, &tile_kept);
+    const int dst = dst_base + rank;
+    if (kp) {
+      sh_c.src_of[rank] = i;
+      if (idxb) idxb[dst] = i;
+      if (dst != i) {
+        posb[dst] = my_pos;
+        lhb[dst] = my_lh;
+      }
+    }
+    __syncthreads();
+    const int tile_n = min(WG, L - tile);
+    if (!(dst_base == tile && tile_kept == tile_n)) move_rows<ROWB>(Kb, Vb, sh_c.src_of, tile_kept, dst_base);
+    dst_base += tile_kept;
+    __syncthreads();
+  }
+  if (tid == 0) lens[unit] = dst_base;
+}
+
+__global__ void corm_threshold_kernel(float c, const int32_t* t, int n, float* thr) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) thr[i] = importance_threshold(c, t[i]);
+}
+
+__global__ void corm_fill_i32_kernel(int32_t* p, size_t n, int32_t v) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// ---------------------------------------------------------------- host side
+
+struct WorkspaceLayout {
+  size_t counters_off, partials_off, logits_off, total;
+  int nsplit;
+};
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+WorkspaceLayout workspace_layout(const corm_desc& d) {
+  WorkspaceLayout w;
+  w.nsplit = (d.Lcap + CHUNK - 1) / CHUNK;
+  w.counters_off = 0;
+  size_t counters = (size_t)d.B * d.Hkv * sizeof(int32_t);
+  w.partials_off = align_up(counters, 256);
+  size_t partials = (size_t)d.B * d.Hq * w.nsplit * (d.d + 2) * sizeof(float);
+  w.logits_off = align_up(w.partials_off + partials, 256);
+  size_t logits = (size_t)d.B * d.Hq * d.Lcap * sizeof(float);
+  w.total = align_up(w.logits_off + logits, 256);
+  return w;
+}
+
+int validate_desc(const corm_desc* d) {
+  if (!d) return CORM_EINVAL;
+  if (d->B < 1 || d->Hq < 1 || d->Hkv < 1 || d->Lcap < 1 || d->Tcap < 1 || d->w < 1 || d->r < 1) return CORM_EINVAL;
+  if (d->Hq % d->Hkv != 0) return CORM_EINVAL;
+  if (!(d->thr_scale >= 0.f) || !std::isfinite(d->thr_scale)) return CORM_EINVAL;
+  if (!(d->sm_scale >= 0.f) || !std::isfinite(d->sm_scale)) return CORM_EINVAL;
+  if ((long long)d->B * d->Hkv > 2147483647LL / 2 || (long long)d->B * d->Hq > 2147483647LL / 2) return CORM_EINVAL;
+  if (d->B * d->Hkv > 65535) return CORM_EUNSUPPORTED;  // grid.y limit
+  if (d->kv_dtype != CORM_F32 && d->kv_dtype != CORM_BF16) return CORM_EUNSUPPORTED;
+  if (d->score_dtype != CORM_F32 && d->score_dtype != CORM_BF16) return CORM_EUNSUPPORTED;
+  if (d->d != 64 && d->d != 128) return CORM_EUNSUPPORTED;
+  const int G = d->Hq / d->Hkv;
+  if (G != 1 && G != 2 && G != 4 && G != 8) return CORM_EUNSUPPORTED;
+  return CORM_OK;
+}
+
+bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+bool misaligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) != 0; }
+
+int row_bytes(const corm_desc* d) { return d->d * (d->kv_dtype == CORM_F32 ? 4 : 2); }
+
+int launch_status() { return hipGetLastError() == hipSuccess ? CORM_OK : CORM_EHIP; }
+
+template <typename DT, int D>
+int launch_step_g(const Params& p, int G, dim3 grid, hipStream_t s) {
+  switch (G) {
+    case 1: hipLaunchKernelGGL((corm_step_kernel<DT, D, 1>), grid, dim3(WG), 0, s, p); break;
+    case 2: hipLaunchKernelGGL((corm_step_kernel<DT, D, 2>), grid, dim3(WG), 0, s, p); break;
+    case 4: hipLaunchKernelGGL((corm_step_kernel<DT, D, 4>), grid, dim3(WG), 0, s, p); break;
+    case 8: hipLaunchKernelGGL((corm_step_kernel<DT, D, 8>), grid, dim3(WG), 0, s, p); break;
+    default: return CORM_EUNSUPPORTED;
+  }
+  return launch_status();
+}
+
+int launch_step(const corm_desc* d, Params& p, void* workspace, size_t workspace_bytes, hipStream_t s) {
+  WorkspaceLayout wl = workspace_layout(*d);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return CORM_EINVAL;
+  if (workspace_bytes < wl.total) return CORM_ECAPACITY;
+  char* ws = reinterpret_cast<char*>(workspace);
+  p.counters = reinterpret_cast<int32_t*>(ws + wl.counters_off);
+  p.partials = reinterpret_cast<float*>(ws + wl.partials_off);
+  p.logits = reinterpret_cast<float*>(ws + wl.logits_off);
+  p.B = d->B; p.Hq = d->Hq; p.Hkv = d->Hkv; p.Lcap = d->Lcap; p.Tcap = d->Tcap; p.w = d->w; p.r = d->r;
+  p.nsplit = wl.nsplit;
+  p.thr_scale = d->thr_scale;
+  const float sm = d->sm_scale > 0.f ? d->sm_scale : 1.0f / sqrtf((float)d->d);
+  p.scale_log2 = sm * LOG2E;
+  p.ring_bf16 = d->score_dtype == CORM_BF16;
+  const int G = d->Hq / d->Hkv;
+  dim3 grid(wl.nsplit, d->B * d->Hkv);
+  if (d->kv_dtype == CORM_F32) {
+    return d->d == 64 ? launch_step_g<F32, 64>(p, G, grid, s) : launch_step_g<F32, 128>(p, G, grid, s);
+  }
+  return d->d == 64 ? launch_step_g<BF16, 64>(p, G, grid, s) : launch_step_g<BF16, 128>(p, G, grid, s);
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------- C ABI
+
+extern "C" {
+
+int corm_version(void) { return 100; }
+
+const char* corm_strerror(int status) {
+  switch (status) {
+    case CORM_OK: return "ok";
+    case CORM_EINVAL: return "invalid argument (null or misaligned pointer, bad shape, w < 1, r < 1, c < 0)";
+    case CORM_EUNSUPPORTED: return "unsupported configuration (d not in {64,128}, group size not in {1,2,4,8}, dtype)";
+    case CORM_ECAPACITY: return "capacity exceeded (workspace too small)";
+    case CORM_EHIP: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+int corm_workspace_bytes(const corm_desc* desc, size_t* bytes) {
+  int rc = validate_desc(desc);
+  if (rc) return rc;
+  if (!bytes) return CORM_EINVAL;
+  *bytes = workspace_layout(*desc).total;
+  return CORM_OK;
+}
+
+int corm_workspace_init(const corm_desc* desc, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc = validate_desc(desc);
+  if (rc) return rc;
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return CORM_EINVAL;
+  WorkspaceLayout wl = workspace_layout(*desc);
+  if (workspace_bytes < wl.total) return CORM_ECAPACITY;
+  size_t n = (size_t)desc->B * desc->Hkv;
+  hipLaunchKernelGGL(corm_fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                     reinterpret_cast<int32_t*>(workspace), n, 0);
+  return launch_status();
+}
+
+int corm_append(const corm_desc* desc, void* K, void* V, int32_t* lens, int32_t* pos, int32_t* last_hit,
+                const void* k_new, const void* v_new, const int32_t* t, int32_t* status, void* stream) {
+  int rc = validate_desc(desc);
+  if (rc) return rc;
+  if (!K || !V || !lens || !pos || !last_hit || !k_new || !v_new || !t) return CORM_EINVAL;
+  if (misaligned16(K) || misaligned16(V) || misaligned16(k_new) || misaligned16(v_new)) return CORM_EINVAL;
+  if (misaligned4(lens) || misaligned4(pos) || misaligned4(last_hit) || misaligned4(t) || misaligned4(status))
+    return CORM_EINVAL;
+  hipLaunchKernelGGL(corm_append_kernel, dim3(desc->B * desc->Hkv), dim3(64), 0, (hipStream_t)stream,
+                     reinterpret_cast<char*>(K), reinterpret_cast<char*>(V), lens, pos, last_hit,
+                     reinterpret_cast<const char*>(k_new), reinterpret_cast<const char*>(v_new), t, status, desc->Hkv,
+                     desc->Lcap, row_bytes(desc));
+  return launch_status();
+}
+
+int corm_decode_attend(const corm_desc* desc, const void* q, const void* K, const void* V, const int32_t* lens,
+                       const int32_t* pos, const int32_t* t, void* score_ring, int32_t* last_hit, float* out,
+                       void* workspace, size_t workspace_bytes, int32_t* status, void* stream) {
+  int rc = validate_desc(desc);
+  if (rc) return rc;
+  if (!q || !K || !V || !lens || !pos || !t || !score_ring || !last_hit || !out) return CORM_EINVAL;
+  if (misaligned16(q) || misaligned16(K) || misaligned16(V) || misaligned4(out) || misaligned4(score_ring))
+    return CORM_EINVAL;
+  if (misaligned4(lens) || misaligned4(pos) || misaligned4(last_hit) || misaligned4(t) || misaligned4(status))
+    return CORM_EINVAL;
+  Params p = {};
+  p.q = q; p.k_new = K; p.v_new = V;  // k_new/v_new unused without append; kept non-null
+  p.K = const_cast<void*>(K); p.V = const_cast<void*>(V);
+  p.lens = const_cast<int32_t*>(lens); p.pos = const_cast<int32_t*>(pos); p.last_hit = last_hit;
+  p.t = t; p.t_first = t; p.ring = score_ring; p.out = out; p.status = status;
+  p.do_append = 0; p.do_evict = 0;
+  return launch_step(desc, p, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+int corm_evict_mask(const corm_desc* desc, const void* score_ring, const int32_t* lens, const int32_t* pos,
+                    const int32_t* t, const int32_t* t_first, uint8_t* keep, void* stream) {
+  int rc = validate_desc(desc);
+  if (rc) return rc;
+  if (!score_ring || !lens || !pos || !t || !t_first || !keep) return CORM_EINVAL;
+  if (misaligned4(score_ring) || misaligned4(lens) || misaligned4(pos) || misaligned4(t) || misaligned4(t_first))
+    return CORM_EINVAL;
+  dim3 grid((desc->Lcap + WG - 1) / WG, desc->B * desc->Hkv);
+  hipLaunchKernelGGL(corm_evict_mask_kernel, grid, dim3(WG), 0, (hipStream_t)stream, score_ring,
+                     (int)(desc->score_dtype == CORM_BF16), lens, pos, t, t_first, keep, desc->Hq, desc->Hkv,
+                     desc->Lcap, desc->Tcap, desc->w, desc->r, desc->thr_scale);
+  return launch_status();
+}
+
+int corm_evict_mask_summary(const corm_desc* desc, const int32_t* last_hit, const int32_t* lens, const int32_t* t,
+                            const int32_t* t_first, uint8_t* keep, void* stream) {
+  int rc = validate_desc(desc);
+  if (rc) return rc;
+  if (!last_hit || !lens || !t || !t_first || !keep) return CORM_EINVAL;
+  if (misaligned4(last_hit) || misaligned4(lens) || misaligned4(t) || misaligned4(t_first)) return CORM_EINVAL;
+  dim3 grid((desc->Lcap + WG - 1) / WG, desc->B * desc->Hkv);
+  hipLaunchKernelGGL(corm_evict_mask_summary_kernel, grid, dim3(WG), 0, (hipStream_t)stream, last_hit, lens, t,
+                     t_first, keep, desc->Hkv, desc->Lcap, desc->w, desc->r);
+  return launch_status();
+}
+
+int corm_compact(const corm_desc* desc, void* K, void* V, int32_t* pos, int32_t* last_hit, int32_t* lens,
+                 const uint8_t* keep, int32_t* kept_idx, void* stream) {
+  int rc = validate_desc(desc);
+  if (rc) return rc;
+  if (!K || !V || !pos || !last_hit || !lens || !keep) return CORM_EINVAL;
+  if (misaligned16(K) || misaligned16(V) || misaligned4(pos) || misaligned4(last_hit) || misaligned4(lens) ||
+      misaligned4(kept_idx))
+    return CORM_EINVAL;
+  const int rb = row_bytes(desc);
+  dim3 grid(desc->B * desc->Hkv);
+  char* Kc = reinterpret_cast<char*>(K);
+  char* Vc = reinterpret_cast<char*>(V);
+  hipStream_t s = (hipStream_t)stream;
+  switch (rb) {
+    case 128: hipLaunchKernelGGL((corm_compact_kernel<128>), grid, dim3(WG), 0, s, Kc, Vc, pos, last_hit, lens, keep, kept_idx, desc->Lcap); break;
+    case 256: hipLaunchKernelGGL((corm_compact_kernel<256>), grid, dim3(WG), 0, s, Kc, Vc, pos, last_hit, lens, keep, kept_idx, desc->Lcap); break;
+    case 512: hipLaunchKernelGGL((corm_compact_kernel<512>), grid, dim3(WG), 0, s, Kc, Vc, pos, last_hit, lens, keep, kept_idx, desc->Lcap); break;
+    default: return CORM_EUNSUPPORTED;
+  }
+  return launch_status();
+}
+
+int corm_decode_step(const corm_desc* desc, const void* q, const void* k_new, const void* v_new, void* K, void* V,
+                     int32_t* lens, int32_t* pos, int32_t* last_hit, const int32_t* t, const int32_t* t_first,
+                     void* score_ring, float* out, uint8_t* keep, int32_t* kept_idx, void* workspace,
+                     size_t workspace_bytes, int32_t* status, void* stream) {
+  int rc = validate_desc(desc);
+  if (rc) return rc;
+  if (!q || !k_new || !v_new || !K || !V || !lens || !pos || !last_hit || !t || !t_first || !score_ring || !out)
+    return CORM_EINVAL;
+  if (misaligned16(q) || misaligned16(k_new) || misaligned16(v_new) || misaligned16(K) || misaligned16(V) ||
+      misaligned4(out) || misaligned4(score_ring))
+    return CORM_EINVAL;
+  if (misaligned4(lens) || misaligned4(pos) || misaligned4(last_hit) || misaligned4(t) || misaligned4(t_first) ||
+      misaligned4(kept_idx) || misaligned4(status))
+    return CORM_EINVAL;
+  Params p = {};
+  p.q = q; p.k_new = k_new; p.v_new = v_new; p.K = K; p.V = V; p.lens = lens; p.pos = pos; p.last_hit = last_hit;
+  p.t = t; p.t_first = t_first; p.ring = score_ring; p.out = out; p.keep_out = keep; p.kept_idx = kept_idx;
+  p.status = status;
+  p.do_append = 1; p.do_evict = 1;
+  return launch_step(desc, p, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+int corm_threshold(float c, const int32_t* t, int32_t n, float* thr, void* stream) {
+  if (!t || !thr || n < 0 || !(c >= 0.f)) return CORM_EINVAL;
+  if (n == 0) return CORM_OK;
+  hipLaunchKernelGGL(corm_threshold_kernel, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)stream, c, t, n, thr);
+  return launch_status();
+}
+
+}  // extern "C"

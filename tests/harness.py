@@ -1,0 +1,175 @@
+"""Parity harness: drives the HIP library through its C ABI and the CPU oracle side by side.
+
+Slaved trajectory: the oracle replays the whole sequence itself, but the record / evict /
+compact part of each step is fed the scores the device recorded in its ring, so both caches
+stay identical and keep / indices / K' / V' / lens' are compared bit for bit at every step,
+while `out` and the oracle's own fp64 scores are compared within tolerance.
+
+Snapshot step: the oracle is rebuilt from a copy of the device state of a few units (cache
+rows, positions and the ring window), computes one step, and is compared the same way.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+from oracle import corm_oracle as O
+from paper_2404_15949_amd import corm, inputs
+
+OUT_TOL = {"f32": 1e-5, "bf16": 2e-3}          # max_c |delta| / max_c |ref| per output row
+# recorded score vs the oracle's fp64 score: fp32 arithmetic error, plus bf16 storage rounding (2^-9 relative)
+SCORE_RTOL = {"f32": 2e-5, "bf16": 2.0 ** -8}
+SCORE_ATOL_OF_MAX = {"f32": 2e-6, "bf16": 1e-5}
+
+
+def out_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+def make_state(wl: inputs.Workload, device, Lcap=None, Tcap=None, thr_scale=1.0, want_masks=True,
+               workspace=None) -> corm.LayerState:
+    n_replay = min(wl.w, wl.P)
+    Lcap = wl.P + wl.D if Lcap is None else Lcap
+    Tcap = wl.P + wl.D if Tcap is None else Tcap
+    return corm.LayerState(wl.B, wl.Hq, wl.Hkv, wl.d, Lcap, Tcap, wl.w, wl.r, wl.dtype, thr_scale=thr_scale,
+                           device=device, workspace=workspace, want_masks=want_masks)
+
+
+def step_inputs(wl: inputs.Workload, x: Dict[str, torch.Tensor], j: int, n_replay: int):
+    """q, k_new, v_new ([B,H,d], contiguous) and the absolute step t of trajectory step j."""
+    P = wl.P
+    if j < n_replay:
+        p = P - n_replay + j
+        k = x["K0"][:, :, p].contiguous()
+        v = x["V0"][:, :, p].contiguous()
+    else:
+        p = P + (j - n_replay)
+        k = x["Kn"][j - n_replay].contiguous()
+        v = x["Vn"][j - n_replay].contiguous()
+    return x["Q"][j].contiguous(), k, v, p + 1
+
+
+def _f32(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy()
+
+
+def check_unit_state(st: corm.LayerState, b: int, h: int, u: O.UnitCache, t: int) -> None:
+    """Device cache of unit (b,h) == the oracle's, bit for bit (rows, order, positions, lens)."""
+    l = int(st.lens[b, h].item())
+    assert l == u.l, (b, h, l, u.l)
+    assert np.array_equal(st.pos[b, h, :l].cpu().numpy().astype(np.int64), u.positions), (b, h)
+    Kd = _f32(st.K[b, h, :l]).astype(np.float64)
+    Vd = _f32(st.V[b, h, :l]).astype(np.float64)
+    assert np.array_equal(Kd, u.keys), (b, h, "K rows")
+    assert np.array_equal(Vd, u.values), (b, h, "V rows")
+    # last_hit summary vs the oracle's message window
+    lh = st.last_hit[b, h, :l].cpu().numpy()
+    m = u.message.shape[0]
+    steps = np.asarray(u.row_steps[-m:], dtype=np.int64) if m else np.zeros((0,), dtype=np.int64)
+    hit_any = u.message.any(axis=1) if m else np.zeros((0, l), dtype=bool)       # [m, l]
+    last = np.where(hit_any, steps[:, None], 0).max(axis=0) if m else np.zeros(l, dtype=np.int64)
+    lo = t - st.w  # hits at steps <= t-w are outside the window
+    assert np.array_equal(np.where(lh > lo, lh, 0), last), (b, h, "last_hit")
+
+
+def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_scale=1.0, check_state_every=1,
+                          units: Optional[Sequence[Tuple[int, int]]] = None, steps: Optional[int] = None,
+                          use_split_calls=False) -> Dict:
+    """Run replay + decode on the device, slaving one oracle per checked unit.  Returns a report."""
+    x_cpu = inputs.make_layer(wl, layer, device="cpu")
+    x = {k: v.to(device) for k, v in x_cpu.items() if k != "sinks"}
+    n_replay = min(wl.w, wl.P)
+    n_steps = n_replay + wl.D if steps is None else steps
+    st = make_state(wl, device, thr_scale=thr_scale)
+    G = wl.G
+    pre = wl.P - n_replay
+    st.preload(x["K0"][:, :, :pre], x["V0"][:, :, :pre])
+    units = [(b, h) for b in range(wl.B) for h in range(wl.Hkv)] if units is None else list(units)
+    oracles = {}
+    for (b, h) in units:
+        u = O.UnitCache(wl.d, G, wl.w, wl.r, thr_scale, score_dtype=wl.dtype)
+        u.preload(_f32(x_cpu["K0"][b, h, :pre]), _f32(x_cpu["V0"][b, h, :pre]))
+        oracles[(b, h)] = u
+    t_first = torch.full((wl.B,), pre + 1, dtype=torch.int32, device=device)
+    tol = OUT_TOL[wl.dtype]
+    worst_out = 0.0
+    worst_score = 0.0
+    flips = 0
+    evicted_total = 0
+    for j in range(n_steps):
+        q, k, v, t = step_inputs(wl, x, j, n_replay)
+        t_dev = torch.full((wl.B,), t, dtype=torch.int32, device=device)
+        if use_split_calls:
+            corm.corm_append(st.desc, st.K, st.V, st.lens, st.pos, st.last_hit, k, v, t_dev, st.status)
+            corm.corm_decode_attend(st.desc, q, st.K, st.V, st.lens, st.pos, t_dev, st.ring, st.last_hit, st.out,
+                                    st.workspace, status=st.status)
+            corm.corm_evict_mask(st.desc, st.ring, st.lens, st.pos, t_dev, t_first, st.keep)
+            keep_lit = st.keep.clone()
+            corm.corm_evict_mask_summary(st.desc, st.last_hit, st.lens, t_dev, t_first, st.keep)
+            lens_before = st.lens.cpu().numpy()
+            for (b, h) in units:
+                lb = int(lens_before[b, h])
+                assert torch.equal(keep_lit[b, h, :lb], st.keep[b, h, :lb]), ("literal vs summary mask", j, b, h)
+            corm.corm_compact(st.desc, st.K, st.V, st.pos, st.last_hit, st.lens, st.keep, st.kept_idx)
+        else:
+            st.step(q, k, v, t_dev, t_first)
+        torch.cuda.synchronize()
+        assert int(st.status.item()) == 0, ("device status", int(st.status.item()), j)
+        slot = (t - 1) % wl.w
+        ring_row = _f32(st.ring[:, :, slot])                  # [B, Hq, Tcap]
+        out = st.out.cpu().numpy()
+        keep_d = st.keep.cpu().numpy()
+        idx_d = st.kept_idx.cpu().numpy()
+        lens_d = st.lens.cpu().numpy()
+        qc, kc, vc = _f32(q), _f32(k), _f32(v)
+        for (b, h) in units:
+            u = oracles[(b, h)]
+            live_pos = np.concatenate([u.positions, [t - 1]])
+            recorded = ring_row[b, h * G:(h + 1) * G][:, live_pos]
+            res = u.step(qc[b, h * G:(h + 1) * G], kc[b, h], vc[b, h], t, recorded=recorded)
+            l = len(live_pos)
+            assert np.array_equal(keep_d[b, h, :l].astype(bool), res["keep"]), ("keep", j, b, h)
+            assert int(lens_d[b, h]) == u.l, ("lens", j, b, h, int(lens_d[b, h]), u.l)
+            assert np.array_equal(idx_d[b, h, :u.l].astype(np.int64), res["indices"]), ("kept_idx", j, b, h)
+            evicted_total += l - u.l
+            for g in range(G):
+                e = out_rel_err(out[b, h * G + g].astype(np.float64), res["out"][g])
+                worst_out = max(worst_out, e)
+                assert e <= tol, ("out", j, b, h, g, e)
+                a = res["alpha"][g]
+                err = np.abs(recorded[g].astype(np.float64) - a)
+                bound = SCORE_RTOL[wl.dtype] * a + SCORE_ATOL_OF_MAX[wl.dtype] * a.max()
+                worst_score = max(worst_score, float((err / bound).max()))
+                assert (err <= bound).all(), ("recorded score", j, b, h, g, float((err / bound).max()))
+            own = O.important(O.round_to_storage(res["alpha"], wl.dtype), t, thr_scale)
+            flips += int((own != O.important(recorded, t, thr_scale)).sum())
+            if check_state_every and ((j + 1) % check_state_every == 0 or j == n_steps - 1):
+                check_unit_state(st, b, h, u, t)
+    return {"steps": n_steps, "units": len(units), "worst_out_rel_err": worst_out,
+            "worst_score_err_over_bound": worst_score, "importance_flips_vs_fp64": flips,
+            "evicted_total": evicted_total, "final_lens": st.lens.cpu().numpy().tolist()}
+
+
+# ------------------------------------------------------------------ snapshot mode
+
+def oracle_from_snapshot(st: corm.LayerState, b: int, h: int, t_prev: int, t_first: int, dtype: str,
+                         thr_scale: float) -> O.UnitCache:
+    """Rebuild the oracle state of unit (b,h) from device memory as it stands after step t_prev."""
+    G = st.Hq // st.Hkv
+    u = O.UnitCache(st.d, G, st.w, st.r, thr_scale, score_dtype=dtype)
+    l = int(st.lens[b, h].item())
+    u.keys = _f32(st.K[b, h, :l]).astype(np.float64)
+    u.values = _f32(st.V[b, h, :l]).astype(np.float64)
+    u.positions = st.pos[b, h, :l].cpu().numpy().astype(np.int64)
+    rows = list(range(max(t_first, t_prev - st.w + 1), t_prev + 1))
+    pos_t = torch.from_numpy(u.positions).to(st.ring.device)
+    msg = np.zeros((len(rows), G, l), dtype=bool)
+    for a, tau in enumerate(rows):
+        sc = _f32(st.ring[b, h * G:(h + 1) * G, (tau - 1) % st.w][:, pos_t])      # [G, l]
+        born = u.positions <= tau - 1
+        msg[a] = O.important(sc, tau, thr_scale) & born[None, :]
+    u.message = msg
+    u.row_steps = rows
+    return u

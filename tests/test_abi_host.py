@@ -1,0 +1,97 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the header declares,
+and rejects bad arguments on the host before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2404_15949_amd import corm
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "corm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(corm_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared()
+    assert set(names) == set(corm.EXPORTS), (names, corm.EXPORTS)
+    raw = ctypes.CDLL(corm.LIB_PATH)
+    for n in names:
+        assert hasattr(raw, n), n
+    assert corm.corm_version() >= 100
+    assert "invalid" in corm.strerror(corm.CORM_EINVAL)
+
+
+def _desc(**kw):
+    base = dict(B=2, Hq=8, Hkv=2, d=128, Lcap=1024, Tcap=1024, w=16, r=16, kv_dtype="bf16")
+    base.update(kw)
+    return corm.make_desc(**base)
+
+
+def test_desc_layout_matches_header():
+    assert ctypes.sizeof(corm.corm_desc) == 12 * 4
+    assert [f[0] for f in corm.corm_desc._fields_] == ["B", "Hq", "Hkv", "d", "Lcap", "Tcap", "w", "r", "kv_dtype",
+                                                       "score_dtype", "thr_scale", "sm_scale"]
+
+
+def test_workspace_size_formula():
+    d = _desc()
+    n = corm.corm_workspace_bytes(d)
+    nsplit = (1024 + 511) // 512
+    need = 2 * 2 * 4 + 2 * 8 * nsplit * 130 * 4 + 2 * 8 * 1024 * 4
+    assert need <= n <= need + 3 * 256
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(d=96), corm.CORM_EUNSUPPORTED),
+    (dict(Hq=6, Hkv=2), corm.CORM_EUNSUPPORTED),      # group of 3
+    (dict(Hq=8, Hkv=3), corm.CORM_EINVAL),            # not divisible
+    (dict(w=0), corm.CORM_EINVAL),
+    (dict(r=0), corm.CORM_EINVAL),
+    (dict(thr_scale=-1.0), corm.CORM_EINVAL),
+    (dict(thr_scale=float("nan")), corm.CORM_EINVAL),
+    (dict(Lcap=0), corm.CORM_EINVAL),
+    (dict(B=0), corm.CORM_EINVAL),
+    (dict(kv_dtype=7), corm.CORM_EUNSUPPORTED),
+])
+def test_bad_descriptors_are_rejected(kw, code):
+    kv = kw.pop("kv_dtype", "bf16")
+    d = _desc(**kw)
+    if kv == 7:
+        d.kv_dtype = 7
+    assert corm.corm_workspace_bytes(d, check=False) == code
+
+
+def test_null_and_misaligned_pointers_are_rejected_on_the_host():
+    d = _desc()
+    a = 4096  # a plausible aligned address; never dereferenced because validation fails first
+    args = dict(q=a, k_new=a, v_new=a, K=a, V=a, lens=a, pos=a, last_hit=a, t=a, t_first=a, score_ring=a, out=a)
+    order = ["q", "k_new", "v_new", "K", "V", "lens", "pos", "last_hit", "t", "t_first", "score_ring", "out"]
+    for missing in order:
+        v = dict(args); v[missing] = None
+        rc = corm.corm_decode_step(d, *[v[k] for k in order], workspace=a, workspace_bytes=1 << 30, check=False)
+        assert rc == corm.CORM_EINVAL, missing
+    v = dict(args); v["K"] = a + 8
+    rc = corm.corm_decode_step(d, *[v[k] for k in order], workspace=a, workspace_bytes=1 << 30, check=False)
+    assert rc == corm.CORM_EINVAL
+    # workspace too small / missing
+    rc = corm.corm_decode_step(d, *[args[k] for k in order], workspace=a, workspace_bytes=16, check=False)
+    assert rc == corm.CORM_ECAPACITY
+    rc = corm.corm_decode_step(d, *[args[k] for k in order], workspace=None, workspace_bytes=0, check=False)
+    assert rc == corm.CORM_EINVAL
+    assert corm.corm_compact(d, None, a, a, a, a, a, check=False) == corm.CORM_EINVAL
+    assert corm.corm_evict_mask(d, a, a, a, a, None, a, check=False) == corm.CORM_EINVAL
+    assert corm.corm_append(d, a, a, a, a, a, a + 4, a, a, check=False) == corm.CORM_EINVAL
+    assert corm.corm_threshold(-1.0, a, 4, a, check=False) == corm.CORM_EINVAL
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(corm, "_lib", None)
+    monkeypatch.setattr(corm, "LIB_PATH", "/nonexistent/libcorm.so")
+    with pytest.raises(RuntimeError, match="no fallback"):
+        corm.lib()

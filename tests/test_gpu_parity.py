@@ -1,0 +1,271 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import corm_oracle as O
+from paper_2404_15949_amd import corm, inputs
+from tests import harness
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+W = inputs.WORKLOADS
+
+
+def say(*a):
+    print("[case]", *a, flush=True)
+    sys.stdout.flush()
+
+
+# ------------------------------------------------------------------ whole trajectories, every unit, every step
+
+TRAJ = {
+    # the tiny fp32 workload exactly as defined (4 heads, d 64, P 512, D 64, w 32)
+    "tiny_f32": (W["tiny_f32"], 1),
+    # bf16 d128 MHA, L crosses one 512-key split boundary with a ragged tail
+    "bf16_mha": (W["llama7b_1layer"].replace(B=2, Hq=4, Hkv=4, P=700, D=60, w=48, r=48), 6),
+    # grouped queries on bf16: G = 4 and G = 2, G = 8
+    "bf16_gqa4": (W["gqa_llama3"].replace(B=2, Hq=8, Hkv=2, P=600, D=40, w=40, r=40), 8),
+    "bf16_gqa2": (W["gqa_llama3"].replace(B=1, Hq=4, Hkv=2, P=300, D=30, w=24, r=24), 8),
+    "bf16_gqa8": (W["gqa_llama3"].replace(B=1, Hq=8, Hkv=1, P=530, D=20, w=24, r=24), 8),
+    # other row geometries: fp32 d128 (512-byte rows), bf16 d64 (128-byte rows)
+    "f32_d128": (W["tiny_f32"].replace(d=128, Hq=2, Hkv=2, P=540, D=30, w=24, r=24), 6),
+    "bf16_d64": (W["llama7b_1layer"].replace(B=1, Hq=2, Hkv=2, d=64, P=520, D=30, w=24, r=24), 6),
+    "f32_gqa4": (W["tiny_f32"].replace(Hq=4, Hkv=1, P=200, D=30, w=16, r=16), 6),
+    # r < w: keys may be evicted while younger than the window; r > w
+    "r_lt_w": (W["tiny_f32"].replace(P=128, D=40, w=24, r=3), 1),
+    "r_gt_w": (W["tiny_f32"].replace(P=128, D=40, w=8, r=40), 1),
+    # key-norm mixes of the other workloads at reduced size
+    "sparse_layer": (W["llama7b_b16"].replace(layers=3, B=2, Hq=2, Hkv=2, P=600, D=30, w=32, r=32), 6),
+    "odd_head_x2": (W["long32k"].replace(B=1, Hq=4, Hkv=4, P=1100, D=30, w=64, r=64), 10),
+    # structured queries: heads diverge in length
+    "structured": (W["llama7b_1layer"].replace(B=1, Hq=4, Hkv=4, P=1200, D=40, w=96, r=96,
+                                               q_mean_scales=inputs.STRUCTURED_Q_MEAN), 10),
+}
+
+
+@pytest.mark.parametrize("name", list(TRAJ))
+def test_slaved_trajectory(name):
+    wl, every = TRAJ[name]
+    layer = 2 if name == "sparse_layer" else 0
+    say("trajectory", name, wl)
+    rep = harness.run_slaved_trajectory(wl, DEV, layer=layer, check_state_every=every)
+    say("report", name, {k: v for k, v in rep.items() if k != "final_lens"})
+    if name not in ("r_gt_w",):
+        assert rep["evicted_total"] > 0, "nothing was evicted: compaction not exercised"
+
+
+def test_split_calls_equal_the_fused_step():
+    """append + decode_attend + evict_mask (literal, also == summary) + compact: the same bits
+    as the fused step, checked against the same oracle."""
+    wl = W["gqa_llama3"].replace(B=2, Hq=4, Hkv=2, P=560, D=30, w=24, r=24)
+    say("split calls", wl)
+    a = harness.run_slaved_trajectory(wl, DEV, check_state_every=5, use_split_calls=True)
+    b = harness.run_slaved_trajectory(wl, DEV, check_state_every=5, use_split_calls=False)
+    assert a["final_lens"] == b["final_lens"] and a["evicted_total"] == b["evicted_total"] > 0
+
+
+@pytest.mark.parametrize("c,expect", [(0.0, "none"), (1e9, "window")])
+def test_threshold_extremes(c, expect):
+    wl = W["tiny_f32"].replace(P=96, D=30, w=8, r=5)
+    say("threshold extreme", c)
+    rep = harness.run_slaved_trajectory(wl, DEV, thr_scale=c, check_state_every=1)
+    lens = np.array(rep["final_lens"])
+    if expect == "none":
+        assert (lens == wl.P + wl.D).all() and rep["evicted_total"] == 0
+    else:
+        assert (lens == wl.r).all()
+
+
+def test_w1_r1():
+    wl = W["tiny_f32"].replace(P=40, D=30, w=1, r=1)
+    say("w=1 r=1")
+    harness.run_slaved_trajectory(wl, DEV, check_state_every=1)
+
+
+# ------------------------------------------------------------------ the threshold arithmetic
+
+def test_device_threshold_is_the_ieee_quotient():
+    ts = np.unique(np.concatenate([np.arange(1, 70000), np.random.default_rng(0).integers(1, 2 ** 24, 50000)]))
+    t = torch.from_numpy(ts.astype(np.int32)).to(DEV)
+    thr = torch.empty(len(ts), dtype=torch.float32, device=DEV)
+    for c in (1.0, 0.5, 3.0, 0.0):
+        corm.corm_threshold(c, t, len(ts), thr)
+        want = np.float32(c) / ts.astype(np.float32)
+        assert np.array_equal(thr.cpu().numpy().view(np.uint32), want.astype(np.float32).view(np.uint32)), c
+
+
+# ------------------------------------------------------------------ standalone calls on arbitrary inputs
+
+def _rand_state(B, Hq, Hkv, d, Lcap, Tcap, w, r, dtype, lens, seed=0):
+    st = corm.LayerState(B, Hq, Hkv, d, Lcap, Tcap, w, r, dtype, device=DEV, want_masks=True)
+    g = torch.Generator(device="cpu"); g.manual_seed(seed)
+    st.K.copy_(torch.randn(B, Hkv, Lcap, d, generator=g).to(st.dtype))
+    st.V.copy_(torch.randn(B, Hkv, Lcap, d, generator=g).to(st.dtype))
+    st.lens.copy_(torch.tensor(lens, dtype=torch.int32).view(B, Hkv))
+    return st, g
+
+
+def test_compact_standalone_random_masks():
+    """corm_compact on arbitrary keep masks == stable gather; edge lens 0, 1, tile and split boundaries."""
+    lens = [0, 1, 255, 256, 257, 512, 513, 1000]
+    B, Hkv, Lcap, d = 2, 4, 1000, 128
+    st, g = _rand_state(B, Hkv, Hkv, d, Lcap, Lcap, 4, 4, "bf16", lens)
+    pos = torch.stack([torch.sort(torch.randperm(5000, generator=g)[:Lcap]).values for _ in range(B * Hkv)])
+    st.pos.copy_(pos.view(B, Hkv, Lcap).int())
+    st.last_hit.copy_(torch.randint(0, 999, (B, Hkv, Lcap), generator=g).int())
+    for trial, pkeep in enumerate([0.5, 0.97, 0.03, 1.0, 0.0]):
+        say("compact trial", trial, pkeep)
+        keep = (torch.rand(B, Hkv, Lcap, generator=g) < pkeep).to(torch.uint8)
+        K0, V0 = st.K.clone(), st.V.clone()
+        pos0, lh0, lens0 = st.pos.clone(), st.last_hit.clone(), st.lens.clone()
+        st.keep.copy_(keep)
+        corm.corm_compact(st.desc, st.K, st.V, st.pos, st.last_hit, st.lens, st.keep, st.kept_idx)
+        torch.cuda.synchronize()
+        for b in range(B):
+            for h in range(Hkv):
+                l = int(lens0[b, h])
+                idx = O.stable_compact(keep[b, h, :l].numpy())
+                n = len(idx)
+                assert int(st.lens[b, h]) == n
+                it = torch.from_numpy(idx).to(DEV)
+                assert torch.equal(st.kept_idx[b, h, :n].long(), it)
+                assert torch.equal(st.K[b, h, :n], K0[b, h][it]) and torch.equal(st.V[b, h, :n], V0[b, h][it])
+                assert torch.equal(st.pos[b, h, :n], pos0[b, h][it]) and torch.equal(st.last_hit[b, h, :n], lh0[b, h][it])
+        # idempotence: compacting again with an all-ones mask changes nothing
+        K1, lens1 = st.K.clone(), st.lens.clone()
+        st.keep.fill_(1)
+        corm.corm_compact(st.desc, st.K, st.V, st.pos, st.last_hit, st.lens, st.keep, None)
+        torch.cuda.synchronize()
+        assert torch.equal(st.lens, lens1)
+        for b in range(B):
+            for h in range(Hkv):
+                n = int(lens1[b, h])
+                assert torch.equal(st.K[b, h, :n], K1[b, h, :n])
+        # restore full units for the next trial
+        st.K.copy_(K0); st.V.copy_(V0); st.pos.copy_(pos0); st.last_hit.copy_(lh0); st.lens.copy_(lens0)
+
+
+def test_evict_mask_standalone_random_ring():
+    """corm_evict_mask on an arbitrary ring == the oracle's windowed rule on the same stored scores."""
+    B, Hq, Hkv, d, Lcap, Tcap, w, r = 2, 4, 2, 64, 300, 400, 6, 4
+    lens = [0, 3, 300, 257]
+    for dtype in ("f32", "bf16"):
+        st, g = _rand_state(B, Hq, Hkv, d, Lcap, Tcap, w, r, dtype, lens, seed=3)
+        G = Hq // Hkv
+        pos = torch.stack([torch.sort(torch.randperm(340, generator=g)[:Lcap]).values for _ in range(B * Hkv)])
+        st.pos.copy_(pos.view(B, Hkv, Lcap).int())
+        ring = (torch.rand(B, Hq, w, Tcap, generator=g) ** 6 * 0.02).to(st.dtype)
+        st.ring.copy_(ring)
+        for (tcur, tfirst) in [(345, 1), (345, 341), (345, 340), (350, 300)]:
+            say("evict_mask", dtype, tcur, tfirst)
+            t = torch.full((B,), tcur, dtype=torch.int32, device=DEV)
+            tf = torch.full((B,), tfirst, dtype=torch.int32, device=DEV)
+            st.keep.fill_(7)
+            corm.corm_evict_mask(st.desc, st.ring, st.lens, st.pos, t, tf, st.keep)
+            torch.cuda.synchronize()
+            rows = list(range(max(tfirst, tcur - w + 1), tcur + 1))
+            for b in range(B):
+                for h in range(Hkv):
+                    l = lens[b * Hkv + h]
+                    if l == 0:
+                        continue
+                    p = pos.view(B, Hkv, Lcap)[b, h, :l].numpy()
+                    sc = np.zeros((len(rows), G, l), dtype=np.float32)
+                    for a, tau in enumerate(rows):
+                        row = ring[b, h * G:(h + 1) * G, (tau - 1) % w].float().numpy()[:, p]
+                        sc[a] = np.where(p[None, :] <= tau - 1, row, 0.0)
+                    want = O.keep_from_score_window(sc, rows, w, r)
+                    got = st.keep[b, h, :l].cpu().numpy().astype(bool)
+                    assert np.array_equal(got, want), (dtype, tcur, tfirst, b, h)
+                    if len(rows) >= w:
+                        assert not want.all()
+
+
+def test_attend_edge_lengths_and_status_flags():
+    """decode_attend on lens 0 / 1 / split boundaries, and the device status bits (no faults)."""
+    B, Hq, Hkv, d, Lcap, Tcap, w, r = 1, 6, 6, 128, 1100, 1100, 8, 8
+    lens = [0, 1, 511, 512, 513, 1100]
+    st, g = _rand_state(B, Hq, Hkv, d, Lcap, Tcap, w, r, "bf16", lens, seed=5)
+    st.pos.copy_(torch.arange(Lcap, dtype=torch.int32).expand(B, Hkv, Lcap))
+    q = torch.randn(B, Hq, d, generator=g).to(torch.bfloat16).to(DEV)
+    t = torch.full((B,), Lcap, dtype=torch.int32, device=DEV)
+    say("attend edge lengths")
+    corm.corm_decode_attend(st.desc, q, st.K, st.V, st.lens, st.pos, t, st.ring, st.last_hit, st.out, st.workspace,
+                            status=st.status)
+    torch.cuda.synchronize()
+    assert int(st.status.item()) == 0
+    slot = (Lcap - 1) % w
+    for h, l in enumerate(lens):
+        if l == 0:
+            assert torch.count_nonzero(st.out[0, h]) == 0
+            continue
+        K = st.K[0, h, :l].float().cpu().numpy(); V = st.V[0, h, :l].float().cpu().numpy()
+        a = O.attention_scores(q[0, h].float().cpu().numpy(), K)
+        ref = O.attention_output(a, V)
+        assert harness.out_rel_err(st.out[0, h].cpu().numpy().astype(np.float64), ref) <= 2e-3
+        rec = st.ring[0, h, slot, :l].float().cpu().numpy()
+        assert (np.abs(rec - a) <= 2.0 ** -8 * a + 1e-5 * a.max()).all()
+        lh = st.last_hit[0, h, :l].cpu().numpy()
+        assert np.array_equal(lh == Lcap, O.important(rec, Lcap))
+    assert torch.equal(st.lens.cpu().view(-1), torch.tensor(lens, dtype=torch.int32))   # attend leaves lens alone
+    # a full unit cannot take an append; a step beyond the ring's columns is not recorded
+    say("status: unit full")
+    k = torch.randn(B, Hkv, d, generator=g).to(torch.bfloat16).to(DEV)
+    K_before = st.K.clone()
+    tf = torch.ones(B, dtype=torch.int32, device=DEV)
+    st.step(q, k, k, t, tf)
+    torch.cuda.synchronize()
+    assert int(st.status.item()) & corm.CORM_DEV_UNIT_FULL
+    assert torch.equal(st.K[0, 5], K_before[0, 5])
+    st.status.zero_()
+    rc = corm.corm_append(st.desc, st.K, st.V, st.lens, st.pos, st.last_hit, k, k, t, st.status)
+    torch.cuda.synchronize()
+    assert int(st.status.item()) & corm.CORM_DEV_UNIT_FULL
+    say("status: step beyond Tcap")
+    st.status.zero_()
+    st.lens.fill_(4)
+    ring_before = st.ring.clone()
+    t_bad = torch.full((B,), Tcap + 1, dtype=torch.int32, device=DEV)
+    corm.corm_decode_attend(st.desc, q, st.K, st.V, st.lens, st.pos, t_bad, st.ring, st.last_hit, st.out,
+                            st.workspace, status=st.status)
+    torch.cuda.synchronize()
+    assert int(st.status.item()) & corm.CORM_DEV_BAD_STEP
+    assert torch.equal(st.ring, ring_before)
+    say("status: lens out of range is clamped")
+    st.status.zero_()
+    st.lens.fill_(Lcap + 5)
+    corm.corm_decode_attend(st.desc, q, st.K, st.V, st.lens, st.pos, t, st.ring, st.last_hit, st.out,
+                            st.workspace, status=st.status)
+    torch.cuda.synchronize()
+    assert int(st.status.item()) & corm.CORM_DEV_BAD_LENS
+
+
+def test_repeat_run_is_bit_identical():
+    """Same inputs twice -> identical state (no race in the split arrival or the in-place compaction)."""
+    wl = W["llama7b_1layer"].replace(B=2, Hq=4, Hkv=4, P=1300, D=24, w=64, r=64,
+                                     q_mean_scales=inputs.STRUCTURED_Q_MEAN)
+    say("repeatability", wl)
+    x = {k: v.to(DEV) for k, v in inputs.make_layer(wl, 0).items() if k != "sinks"}
+    n_replay = wl.w
+    snaps = []
+    for rep in range(2):
+        st = harness.make_state(wl, DEV)
+        pre = wl.P - n_replay
+        st.preload(x["K0"][:, :, :pre], x["V0"][:, :, :pre])
+        tf = torch.full((wl.B,), pre + 1, dtype=torch.int32, device=DEV)
+        outs = []
+        for j in range(n_replay + wl.D):
+            q, k, v, t = harness.step_inputs(wl, x, j, n_replay)
+            st.step(q, k, v, torch.full((wl.B,), t, dtype=torch.int32, device=DEV), tf)
+            outs.append(st.out.clone())
+        torch.cuda.synchronize()
+        lens = st.lens.cpu()
+        live = torch.arange(st.Lcap).view(1, 1, -1) < lens.unsqueeze(-1)
+        snaps.append((torch.stack(outs).cpu(), lens, (st.K.cpu() * live.unsqueeze(-1)), st.pos.cpu() * live,
+                      st.ring.cpu()))
+    for a, b in zip(*snaps):
+        assert torch.equal(a, b)
+    assert snaps[0][1].min() < wl.P
