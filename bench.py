@@ -1,0 +1,261 @@
+#!/usr/bin/env python3
+"""Benchmark of the CORM decode hot path on one MI355X.
+
+A "step" is one decode step of the whole stack: for every layer one fused launch that appends
+the token's key/value, attends over every unit's live keys, records the scores, decides the
+evictions and compacts the caches.  Default workload: the LLaMA-2-7B-shaped full stack
+(32 layers x 32 heads, d 128, bf16, batch 16, prompt 4096, w = r = 1024) on seeded synthetic
+inputs.  Inputs are resident in HBM before the timed region; the prompt is untimed set-up.
+
+Prints ONE JSON line (the last line of stdout).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
+
+
+def log(*a):
+    print("[bench]", *a, file=sys.stderr, flush=True)
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="llama7b_b16")
+    ap.add_argument("--layers", type=int, default=None, help="override the number of layers (development only)")
+    ap.add_argument("--structured", action="store_true",
+                    help="supplementary variant: per-head query means so that eviction happens at w >= 256")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-units", type=int, default=24)
+    ap.add_argument("--cpu-steps", type=int, default=6)
+    return ap.parse_args()
+
+
+def algorithmic_bytes(lens_before, wl, esz, ssz):
+    """Bytes one launch must move for units whose live lengths (before the append) are lens_before:
+    K and V rows read once, the ring row written, pos and last_hit read; q/k_new/v_new/out per head.
+    (Rows moved by the compaction and the logits scratch are NOT counted.)"""
+    L = lens_before.double() + 1.0
+    per_key = 2 * wl.d * esz + wl.G * ssz + 8
+    per_unit = (2 * wl.G + 2) * wl.d * esz + wl.G * wl.d * 4
+    return float((L * per_key).sum().item() + L.numel() * per_unit)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (units are independent; no collective exists in the path); "
+              "--gpus N with N > 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2404_15949_amd import corm, inputs
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    corm.lib()  # fail loudly now if the HIP library is missing
+
+    wl = inputs.WORKLOADS[args.workload]
+    if args.structured:
+        wl = wl.replace(q_mean_scales=inputs.STRUCTURED_Q_MEAN)
+    layers = wl.layers if args.layers is None else args.layers
+    K_steps, W_steps = args.steps, args.warmup
+    n_dec = W_steps + K_steps
+    n_replay = min(wl.w, wl.P)
+    Lcap = Tcap = wl.P + n_dec
+    esz = 2 if wl.dtype == "bf16" else 4
+    B, Hq, Hkv, d = wl.B, wl.Hq, wl.Hkv, wl.d
+
+    # ---------------- set-up (untimed): allocate, generate, feed the prompt
+    t0 = time.time()
+    desc = corm.make_desc(B, Hq, Hkv, d, Lcap, Tcap, wl.w, wl.r, wl.dtype)
+    ws = torch.empty(corm.corm_workspace_bytes(desc), dtype=torch.uint8, device=dev)
+    corm.corm_workspace_init(desc, ws)
+    lens_all = torch.zeros(layers, B, Hkv, dtype=torch.int32, device=dev)
+    states, Qs, Kns, Vns = [], [], [], []
+    pre = wl.P - n_replay
+    t_all = (torch.arange(n_replay + n_dec, dtype=torch.int32, device=dev) + (pre + 1)).view(-1, 1).repeat(1, B)
+    t_first = torch.full((B,), pre + 1, dtype=torch.int32, device=dev)
+    for l in range(layers):
+        st = corm.LayerState(B, Hq, Hkv, d, Lcap, Tcap, wl.w, wl.r, wl.dtype, device=dev, workspace=ws)
+        st.lens = lens_all[l]
+        x = inputs.make_layer(wl, l, device=dev, n_decode=n_dec, n_replay=n_replay)
+        st.preload(x["K0"][:, :, :pre], x["V0"][:, :, :pre])
+        # keys/values of the replayed prompt tail in step-major layout, then the decode tokens
+        Kt = x["K0"][:, :, pre:].permute(2, 0, 1, 3).contiguous()
+        Vt = x["V0"][:, :, pre:].permute(2, 0, 1, 3).contiguous()
+        Kns.append(torch.cat([Kt, x["Kn"]], dim=0))
+        Vns.append(torch.cat([Vt, x["Vn"]], dim=0))
+        Qs.append(x["Q"])
+        states.append(st)
+        del x, Kt, Vt
+    torch.cuda.synchronize()
+    log(f"allocated + generated {layers} layers in {time.time() - t0:.1f}s; "
+        f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB resident")
+
+    def run_step(j):
+        tj = t_all[j]
+        for l in range(layers):
+            states[l].step(Qs[l][j], Kns[l][j], Vns[l][j], tj, t_first)
+
+    t0 = time.time()
+    for j in range(n_replay):          # prompt tail: seeds the recent-query window; bulk eviction at its end
+        run_step(j)
+    torch.cuda.synchronize()
+    log(f"prompt replay ({n_replay} positions) {time.time() - t0:.1f}s; "
+        f"live fraction after the prompt {lens_all.float().mean().item() / wl.P:.4f}")
+    assert all(int(s.status.item()) == 0 for s in states)
+
+    # ---------------- CPU baseline: the oracle, timed on a bounded sample of the same workload
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        cpu_baseline = cpu_baseline_leg(args, wl, states, Qs, Kns, Vns, n_replay, pre, layers)
+
+    # ---------------- warm-up, then the timed region
+    for j in range(n_replay, n_replay + W_steps):
+        run_step(j)
+    lens_hist = torch.empty(K_steps + 1, layers, B, Hkv, dtype=torch.int32, device=dev)
+    lens_hist[0].copy_(lens_all)
+    # HIP events around the attend kernel of ONE launch per step (layer k mod layers), recorded by the
+    # library on the stream it launches on: the dominant kernel's duration, measured inside the timed region
+    hip = HipEvents()
+    pairs = [(hip.create(), hip.create()) for _ in range(K_steps)]
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for k in range(K_steps):
+        j = n_replay + W_steps + k
+        tj = t_all[j]
+        probe = k % layers
+        for l in range(layers):
+            if l == probe:
+                corm.corm_profile_attend(pairs[k][0], pairs[k][1])
+            states[l].step(Qs[l][j], Kns[l][j], Vns[l][j], tj, t_first)
+        lens_hist[k + 1].copy_(lens_all)   # one tiny copy per step: the live lengths the next step starts from
+    ev1.record()
+    torch.cuda.synchronize()
+    ms_total = ev0.elapsed_time(ev1)
+    assert all(int(s.status.item()) == 0 for s in states)
+
+    ms_per_step = ms_total / K_steps
+    n_launch = K_steps * layers
+    ssz = esz
+    # the dominant kernel (attend): algorithmic bytes of the probed launches / their measured durations
+    probe_ms = [hip.elapsed_ms(a, b_) for (a, b_) in pairs]
+    probe_bytes = [algorithmic_bytes(lens_hist[k][k % layers], wl, esz, ssz) for k in range(K_steps)]
+    avg_attend_ms = sum(probe_ms) / len(probe_ms)
+    bytes_per_launch = sum(probe_bytes) / len(probe_bytes)
+    achieved = bytes_per_launch / (avg_attend_ms * 1e-3) / 1e9
+    # the whole step (attend + record + compact of every layer) against the same algorithmic bytes
+    total_bytes = sum(algorithmic_bytes(lens_hist[k], wl, esz, ssz) for k in range(K_steps))
+    step_gbs = total_bytes / (ms_total * 1e-3) / 1e9
+    live_end = lens_hist[-1].float().mean().item() / (wl.P + n_dec)
+    evicted = int((lens_hist[:-1].long() + 1 - lens_hist[1:].long()).sum().item())
+
+    result = {
+        "metric": "decode steps/sec and achieved HBM GB/s (% of peak), attend+evict+compact",
+        "value": 1000.0 / ms_per_step,
+        "unit": "decode steps/s",
+        "n_gpus": 1, "steps": K_steps, "warmup": W_steps, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name + ("+structured_queries" if args.structured else ""),
+                   "layers": layers, "batch": B, "q_heads": Hq, "kv_heads": Hkv, "head_dim": d,
+                   "prompt": wl.P, "w": wl.w, "r": wl.r, "tokens_per_step": B,
+                   "live_fraction_end": live_end, "keys_evicted_in_timed_region": evicted},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "corm_attend_kernel", "bytes_per_launch": bytes_per_launch,
+                     "avg_launch_ms": avg_attend_ms, "launches_probed": len(probe_ms),
+                     "launches": n_launch},
+        "whole_step": {"achieved": step_gbs, "unit": "GB/s", "frac": step_gbs / HBM_PEAK_GBS,
+                       "avg_layer_step_ms": ms_total / n_launch,
+                       "note": "algorithmic bytes of all launches / wall time of the timed region "
+                               "(attend + record + compact kernels and launch gaps)"},
+        "cpu_baseline": cpu_baseline,
+    }
+    if cpu_baseline:
+        result["gpu_over_cpu"] = result["value"] / cpu_baseline["value"]
+    print(json.dumps(result), flush=True)
+
+
+class HipEvents:
+    """Raw hipEvent_t handles through the HIP runtime that torch already loaded (plumbing only)."""
+
+    def __init__(self):
+        import ctypes
+        self.ct = ctypes
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+
+    def create(self) -> int:
+        ev = self.ct.c_void_p()
+        rc = self.hip.hipEventCreate(self.ct.byref(ev))
+        assert rc == 0, f"hipEventCreate failed: {rc}"
+        return ev.value
+
+    def elapsed_ms(self, a: int, b: int) -> float:
+        ms = self.ct.c_float()
+        rc = self.hip.hipEventElapsedTime(self.ct.byref(ms), a, b)
+        assert rc == 0, f"hipEventElapsedTime failed: {rc}"
+        return ms.value
+
+
+def cpu_baseline_leg(args, wl, states, Qs, Kns, Vns, n_replay, pre, layers):
+    """Time the oracle (as it stands) on a sample of units of the workload's first decode steps, starting
+    from copies of the device state after the prompt.  The device state is not touched."""
+    import numpy as np
+    import torch
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle.snapshot import unit_from_device_arrays
+
+    rng = np.random.default_rng(0)
+    n_units, n_steps = args.cpu_units, args.cpu_steps
+    G = wl.G
+    picks = [(int(rng.integers(layers)), int(rng.integers(wl.B)), int(rng.integers(wl.Hkv))) for _ in range(n_units)]
+    t_prev = wl.P
+    work = []
+    for (l, b, h) in picks:
+        st = states[l]
+        u = unit_from_device_arrays(st.K, st.V, st.pos, st.lens, st.ring, b, h, G, wl.w, wl.r, t_prev, pre + 1,
+                                    wl.dtype, 1.0)
+        q = Qs[l][n_replay:n_replay + n_steps, b, h * G:(h + 1) * G].float().cpu().numpy()
+        k = Kns[l][n_replay:n_replay + n_steps, b, h].float().cpu().numpy()
+        v = Vns[l][n_replay:n_replay + n_steps, b, h].float().cpu().numpy()
+        work.append((u, q, k, v))
+    cores = min(os.cpu_count() or 1, 16)
+
+    def run(item):
+        u, q, k, v = item
+        for s in range(n_steps):
+            u.step(q[s], k[s], v[s], t_prev + 1 + s)
+        return u.l
+
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=cores) as ex:
+        list(ex.map(run, work))
+    dt = time.perf_counter() - t0
+    unit_steps_per_s = n_units * n_steps / dt
+    units_per_step = layers * wl.B * wl.Hkv
+    log(f"cpu baseline: {n_units} units x {n_steps} steps in {dt:.1f}s on {cores} threads")
+    return {"value": unit_steps_per_s / units_per_step, "unit": "decode steps/s", "cores": cores, "kind": "oracle",
+            "sample": f"{n_units} random (layer, sequence, head) units x {n_steps} decode steps from the state after "
+                      f"the prompt, {dt:.1f} s wall; extrapolated to the {units_per_step} units of a full step"}
+
+
+if __name__ == "__main__":
+    main()

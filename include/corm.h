@@ -95,7 +95,8 @@ const char* corm_strerror(int status);
 /* Bytes of workspace the attend/step calls need for this descriptor (host call). */
 int corm_workspace_bytes(const corm_desc* desc, size_t* bytes);
 
-/* Zero the workspace's arrival counters.  Once after allocation (the calls leave them zero). */
+/* Prepare a freshly allocated workspace (clears its per-split survivor counts).  Optional: every
+ * call writes what it later reads. */
 int corm_workspace_init(const corm_desc* desc, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Append (shapes of Algorithm 1): K[b,h,lens] = k_new, V likewise, pos = t-1, last_hit = 0, lens += 1.
@@ -140,6 +141,13 @@ int corm_decode_step(const corm_desc* desc, const void* q, const void* k_new, co
                      const int32_t* t, const int32_t* t_first, void* score_ring, float* out,
                      uint8_t* keep, int32_t* kept_idx, void* workspace, size_t workspace_bytes,
                      int32_t* status, void* stream);
+
+/* Measurement hook (host call, not thread safe): the NEXT corm_decode_attend / corm_decode_step call
+ * records start_event immediately before and stop_event immediately after its attend launch, on
+ * that call's stream, then forgets them.  Both are hipEvent_t handles passed as void*; both NULL
+ * cancels.  The attend kernel streams K and V (the step's dominant traffic); this is how its
+ * duration is measured in place, without instrumenting any other call. */
+int corm_profile_attend(void* start_event, void* stop_event);
 
 /* Diagnostic: thr[i] = fp32(c) / fp32(t[i]) exactly as the kernels compute it (Def. 3.1). */
 int corm_threshold(float c, const int32_t* t, int32_t n, float* thr, void* stream);

@@ -1,0 +1,44 @@
+"""Rebuild an oracle unit from copies of plain state arrays.  TEST INFRASTRUCTURE ONLY.
+
+Used for snapshot parity (the oracle resumes from a copy of the cache and of the recorded score
+window and must reproduce the next step) and by the benchmark's CPU-baseline leg.  Takes torch
+tensors in the layouts the C header documents and only reads them; imports nothing of the
+device path.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import corm_oracle as O
+
+
+def _f32(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy()
+
+
+def unit_from_device_arrays(K, V, pos, lens, ring, b: int, h: int, G: int, w: int, r: int, t_prev: int,
+                            t_first: int, dtype: str, thr_scale: float = 1.0) -> O.UnitCache:
+    """State of unit (b, h) after step t_prev.
+
+    K, V [B,Hkv,Lcap,d]; pos [B,Hkv,Lcap]; lens [B,Hkv]; ring [B,Hq,w,Tcap] with the row of step
+    tau in slot (tau-1) mod w and columns indexed by absolute position.  The boolean message of
+    Algorithm 1 is rebuilt by thresholding each recorded row with its own c/tau (Def. 3.1);
+    keys that did not exist at step tau count as minor in that row.
+    """
+    d = K.shape[-1]
+    u = O.UnitCache(d, G, w, r, thr_scale, score_dtype=dtype)
+    l = int(lens[b, h].item())
+    u.keys = _f32(K[b, h, :l]).astype(np.float64)
+    u.values = _f32(V[b, h, :l]).astype(np.float64)
+    u.positions = pos[b, h, :l].cpu().numpy().astype(np.int64)
+    rows = list(range(max(t_first, t_prev - w + 1), t_prev + 1))
+    pos_t = torch.from_numpy(u.positions).to(ring.device)
+    sc_all = _f32(ring[b, h * G:(h + 1) * G].index_select(2, pos_t))        # [G, w, l]
+    msg = np.zeros((len(rows), G, l), dtype=bool)
+    for a, tau in enumerate(rows):
+        born = u.positions <= tau - 1
+        msg[a] = O.important(sc_all[:, (tau - 1) % w], tau, thr_scale) & born[None, :]
+    u.message = msg
+    u.row_steps = rows
+    return u

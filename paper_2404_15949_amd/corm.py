@@ -22,7 +22,7 @@ CORM_DEV_UNIT_FULL, CORM_DEV_BAD_STEP, CORM_DEV_BAD_LENS = 1, 2, 4
 
 EXPORTS = ("corm_version", "corm_strerror", "corm_workspace_bytes", "corm_workspace_init", "corm_append",
            "corm_decode_attend", "corm_evict_mask", "corm_evict_mask_summary", "corm_compact",
-           "corm_decode_step", "corm_threshold")
+           "corm_decode_step", "corm_profile_attend", "corm_threshold")
 
 
 class corm_desc(ctypes.Structure):
@@ -65,6 +65,7 @@ def lib() -> ctypes.CDLL:
         L.corm_decode_step.argtypes = [dp, vp, vp, vp, vp, vp, i32p, i32p, i32p, i32p, i32p, vp, vp, vp, i32p,
                                        vp, sz, i32p, vp]
         L.corm_threshold.argtypes = [ctypes.c_float, i32p, ctypes.c_int32, vp, vp]
+        L.corm_profile_attend.argtypes = [vp, vp]
         for name in EXPORTS:
             if name not in ("corm_version", "corm_strerror"):
                 getattr(L, name).restype = ctypes.c_int
@@ -172,6 +173,12 @@ def corm_decode_step(desc, q, k_new, v_new, K, V, lens, pos, last_hit, t, t_firs
                                 _ptr(pos), _ptr(last_hit), _ptr(t), _ptr(t_first), _ptr(score_ring), _ptr(out),
                                 _ptr(keep), _ptr(kept_idx), _ptr(workspace), nbytes, _ptr(status), _stream(stream))
     return _check(rc, "corm_decode_step") if check else rc
+
+
+def corm_profile_attend(start_event, stop_event, check=True) -> int:
+    """start_event / stop_event: raw hipEvent_t handles (ints) or None."""
+    rc = lib().corm_profile_attend(start_event, stop_event)
+    return _check(rc, "corm_profile_attend") if check else rc
 
 
 def corm_threshold(c: float, t, n: int, thr, stream=None, check=True) -> int:

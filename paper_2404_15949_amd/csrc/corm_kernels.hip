@@ -1,12 +1,19 @@
 // HIP kernels (gfx950 / CDNA4, wave64) and C ABI of the CORM decode hot path.
 //
-// One launch handles one layer's step for all (sequence, KV head) units:
-//   grid = (splits, units); workgroup (split s, unit u) streams keys [s*CHUNK, (s+1)*CHUNK) of
-//   the unit once: q.k logits (Eq. 2 numerator), an online-softmax partial (max, sum, sum p*v)
-//   in fp32, raw logits to scratch.  The last workgroup of a unit to arrive (one atomic per
-//   workgroup, no spinning) merges the partials -> out (Eq. 1), turns the logits into normalized
-//   scores, writes the ring row, updates last_hit (Def. 3.1), decides keep (Def. 4.1 + recent r),
-//   and compacts the unit in place in ascending tile order (Algorithm 1's gather).
+// One decode step of one layer is three launches on one stream (kernel boundaries are the only
+// cross-workgroup synchronization: no fences, atomics or spinning inside the kernels):
+//
+//   attend   grid (splits, units).  Workgroup (s, u) streams keys [s*CHUNK, (s+1)*CHUNK) of unit u
+//            once: q.k logits (numerator of Eq. 2), an online-softmax partial (max, sum, sum p*v) in
+//            fp32, raw logits to scratch.  The owner of the chunk that holds slot lens[u] also
+//            writes the step's new key/value row into the cache (the append).
+//   record   grid (splits, units).  Merges the split partials (every workgroup recomputes the few
+//            numbers it needs) -> out (Eq. 1, by split 0); turns its chunk's logits into normalized
+//            scores (Eq. 2), writes them to the ring row of this step, updates last_hit (Def. 3.1)
+//            and, when evicting, the keep flag of every key (Def. 4.1 + recent r) and the number of
+//            survivors of the chunk.
+//   compact  grid (units).  If the unit lost no key: lens = l, done.  Otherwise a stable in-place
+//            compaction in ascending tile order (the gather of Algorithm 1).
 //
 // Row geometry: a K/V row is d*sizeof(T) bytes (256 B for bf16 d=128 and fp32 d=64); each lane
 // owns 16 bytes of a row, so LPR = row_bytes/16 lanes share a row and one wave-wide 16-byte
@@ -23,7 +30,7 @@ namespace {
 constexpr int WG = 256;          // threads per workgroup
 constexpr int WAVES = WG / 64;   // waves per workgroup
 constexpr int CHUNK = 512;       // keys per split
-constexpr int UNROLL = 4;        // 16-byte K loads (and V loads) in flight per lane and iteration
+constexpr int UNROLL = 4;        // 16-byte K loads (and V loads) per lane and pipeline stage
 constexpr float LOG2E = 1.4426950408889634f;
 
 struct Params {
@@ -39,11 +46,11 @@ struct Params {
   const int32_t* t_first;
   void* ring;
   float* out;
-  uint8_t* keep_out;
-  int32_t* kept_idx;
-  int32_t* counters;
-  float* partials;
-  float* logits;
+  uint8_t* keep;       // keep flags [B,Hkv,Lcap] (caller's array or workspace)
+  int32_t* kept_idx;   // optional
+  int32_t* counts;     // survivors per (unit, split)
+  float* partials;     // [B*Hq, nsplit, d+2]
+  float* logits;       // [B*Hq, Lcap], log2 domain
   int32_t* status;
   int32_t B, Hq, Hkv, Lcap, Tcap, w, r, nsplit;
   float thr_scale, scale_log2;
@@ -134,13 +141,379 @@ __device__ __forceinline__ float importance_threshold(float c, int32_t t) { retu
 // vmcnt(0), expcnt and lgkmcnt left at their maxima (gfx9 encoding)
 __device__ __forceinline__ void wait_vm_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
+// Live length of a unit for this launch: lens clamped to [0, Lcap], plus one if a row is appended.
+struct UnitLen {
+  int L0;         // live keys before the step
+  int L;          // keys the step attends over
+  bool appended;
+  int flags;      // CORM_DEV_* conditions seen
+};
+
+__device__ __forceinline__ UnitLen unit_len(const Params& p, int unit) {
+  UnitLen u;
+  u.flags = 0;
+  int L0 = p.lens[unit];
+  if (L0 < 0 || L0 > p.Lcap) {
+    u.flags |= CORM_DEV_BAD_LENS;
+    L0 = L0 < 0 ? 0 : p.Lcap;
+  }
+  u.L0 = L0;
+  u.L = L0;
+  u.appended = false;
+  if (p.do_append) {
+    if (L0 < p.Lcap) {
+      u.L = L0 + 1;
+      u.appended = true;
+    } else {
+      u.flags |= CORM_DEV_UNIT_FULL;
+    }
+  }
+  return u;
+}
+
+// ---------------------------------------------------------------- attend
+
+template <typename DT, int D, int G>
+struct Attend {
+  static constexpr int EPL = DT::EPL;
+  static constexpr int ROWB = D * DT::ESZ;
+  static constexpr int LPR = ROWB / 16;   // lanes per row
+  static constexpr int RPL = 64 / LPR;    // rows per wave-wide load
+  static constexpr int U = UNROLL;
+  static constexpr int STAGE_ROWS = WAVES * RPL * U;  // rows one pipeline stage of the workgroup covers
+  static_assert(U <= LPR, "logit store uses one lane per unrolled load");
+
+  struct Stage {
+    uint4 k[U];
+    uint4 v[U];
+  };
+
+  // rows of a stage: the workgroup reads WAVES*RPL consecutive rows per unrolled load
+  __device__ static __forceinline__ int row_of(int it, int j, int wv, int sub) { return it + (j * WAVES + wv) * RPL + sub; }
+
+  __device__ static __forceinline__ void load(Stage& st, int it, int cend, int wv, int sub, int cl, const char* Kb,
+                                              const char* Vb, const char* knew, const char* vnew, int new_slot) {
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+      const int rc = min(row_of(it, j, wv, sub), cend - 1);   // clamped: always a live row
+      // the appended row is read from the step's input, not from the cache
+      const char* kp = rc == new_slot ? knew : Kb + (size_t)rc * ROWB;
+      st.k[j] = *reinterpret_cast<const uint4*>(kp + (size_t)cl * 16);
+    }
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+      const int rc = min(row_of(it, j, wv, sub), cend - 1);
+      const char* vp = rc == new_slot ? vnew : Vb + (size_t)rc * ROWB;
+      st.v[j] = *reinterpret_cast<const uint4*>(vp + (size_t)cl * 16);
+    }
+  }
+
+  __device__ static __forceinline__ void compute(const Stage& st, int it, int cend, int wv, int sub, int cl,
+                                                 const uint4 (&qreg)[G], float scale_log2, float* logit_u, int Lcap,
+                                                 float (&m_run)[G], float (&z_run)[G], float (&acc)[G][EPL]) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float s[U];
+      float my_logit = 0.f;
+      int my_row = -1;
+#pragma unroll
+      for (int j = 0; j < U; ++j) {
+        const int row = row_of(it, j, wv, sub);
+        const float part = DT::dot(st.k[j], qreg[g]);
+        const float tot = row_allreduce_sum<LPR>(part) * scale_log2;
+        s[j] = row < cend ? tot : neg_inf();
+        if (cl == j && row < cend) {
+          my_logit = tot;
+          my_row = row;
+        }
+      }
+      if (my_row >= 0) logit_u[(size_t)g * Lcap + my_row] = my_logit;
+
+      float mnew = m_run[g];
+#pragma unroll
+      for (int j = 0; j < U; ++j) mnew = fmaxf(mnew, s[j]);
+      const float msafe = mnew == neg_inf() ? 0.f : mnew;
+      const float a = exp2f(m_run[g] - msafe);
+      float pj[U];
+      float zs = 0.f;
+#pragma unroll
+      for (int j = 0; j < U; ++j) {
+        pj[j] = exp2f(s[j] - msafe);
+        zs += pj[j];
+      }
+      z_run[g] = fmaf(z_run[g], a, zs);
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[g][e] *= a;
+#pragma unroll
+      for (int j = 0; j < U; ++j) DT::axpy(acc[g], pj[j], st.v[j]);
+      m_run[g] = mnew;
+    }
+  }
+};
+
+template <typename DT, int D, int G>
+__global__ __launch_bounds__(WG) void corm_attend_kernel(const Params p) {
+  using A = Attend<DT, D, G>;
+  constexpr int EPL = A::EPL, ROWB = A::ROWB, LPR = A::LPR;
+
+  const int split = blockIdx.x;
+  const int unit = blockIdx.y;
+  const UnitLen ul = unit_len(p, unit);
+  const int L = ul.L;
+  if (split * CHUNK >= L) return;   // no live key in this split
+
+  const int b = unit / p.Hkv;
+  const int hkv = unit - b * p.Hkv;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wv = tid >> 6;
+  const int sub = lane / LPR, cl = lane % LPR;
+
+  __shared__ float sh_m[G][WAVES];
+  __shared__ float sh_z[G][WAVES];
+  __shared__ float sh_acc[G][WAVES][D];
+
+  char* Kb = reinterpret_cast<char*>(p.K) + (size_t)unit * p.Lcap * ROWB;
+  char* Vb = reinterpret_cast<char*>(p.V) + (size_t)unit * p.Lcap * ROWB;
+  const char* knew = reinterpret_cast<const char*>(p.k_new) + (size_t)unit * ROWB;
+  const char* vnew = reinterpret_cast<const char*>(p.v_new) + (size_t)unit * ROWB;
+  const int hq0 = hkv * G;
+  const int new_slot = ul.appended ? ul.L0 : -1;
+
+  // this lane's slice of the G queries
+  uint4 qreg[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+    qreg[g] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(p.q) +
+                                              ((size_t)(b * p.Hq + hq0 + g) * ROWB + (size_t)cl * 16));
+
+  const int cbeg = split * CHUNK;
+  const int cend = min(cbeg + CHUNK, L);
+
+  // the append: the owner of the chunk that holds the new slot writes the row and its metadata
+  if (new_slot >= cbeg && new_slot < cend && wv == 0) {
+    if (lane < LPR) {
+      const uint4 kx = *reinterpret_cast<const uint4*>(knew + (size_t)lane * 16);
+      const uint4 vx = *reinterpret_cast<const uint4*>(vnew + (size_t)lane * 16);
+      *reinterpret_cast<uint4*>(Kb + (size_t)new_slot * ROWB + (size_t)lane * 16) = kx;
+      *reinterpret_cast<uint4*>(Vb + (size_t)new_slot * ROWB + (size_t)lane * 16) = vx;
+    }
+    if (lane == 0) {
+      p.pos[(size_t)unit * p.Lcap + new_slot] = p.t[b] - 1;
+      p.last_hit[(size_t)unit * p.Lcap + new_slot] = 0;
+    }
+  }
+
+  float m_run[G], z_run[G], acc[G][EPL];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    m_run[g] = neg_inf();
+    z_run[g] = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+  }
+  float* logit_u = p.logits + (size_t)(b * p.Hq + hq0) * p.Lcap;
+
+  // two register stages: the loads of the next stage are in flight while this one is consumed
+  typename A::Stage s0, s1;
+  int it = cbeg;
+  A::load(s0, it, cend, wv, sub, cl, Kb, Vb, knew, vnew, new_slot);
+  while (true) {
+    const bool more1 = it + A::STAGE_ROWS < cend;
+    if (more1) A::load(s1, it + A::STAGE_ROWS, cend, wv, sub, cl, Kb, Vb, knew, vnew, new_slot);
+    A::compute(s0, it, cend, wv, sub, cl, qreg, p.scale_log2, logit_u, p.Lcap, m_run, z_run, acc);
+    if (!more1) break;
+    it += A::STAGE_ROWS;
+    const bool more0 = it + A::STAGE_ROWS < cend;
+    if (more0) A::load(s0, it + A::STAGE_ROWS, cend, wv, sub, cl, Kb, Vb, knew, vnew, new_slot);
+    A::compute(s1, it, cend, wv, sub, cl, qreg, p.scale_log2, logit_u, p.Lcap, m_run, z_run, acc);
+    if (!more0) break;
+    it += A::STAGE_ROWS;
+  }
+
+  // merge the row groups of the wave (lanes differing in bits >= log2(LPR)), then the waves
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+#pragma unroll
+    for (int off = LPR; off < 64; off <<= 1) {
+      const float mo = __shfl_xor(m_run[g], off);
+      const float zo = __shfl_xor(z_run[g], off);
+      const float mn = fmaxf(m_run[g], mo);
+      const float ms = mn == neg_inf() ? 0.f : mn;
+      const float a0 = exp2f(m_run[g] - ms), a1 = exp2f(mo - ms);
+      z_run[g] = z_run[g] * a0 + zo * a1;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) {
+        const float ao = __shfl_xor(acc[g][e], off);
+        acc[g][e] = acc[g][e] * a0 + ao * a1;
+      }
+      m_run[g] = mn;
+    }
+    if (sub == 0) {
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) sh_acc[g][wv][cl * EPL + e] = acc[g][e];
+      if (cl == 0) {
+        sh_m[g][wv] = m_run[g];
+        sh_z[g][wv] = z_run[g];
+      }
+    }
+  }
+  __syncthreads();
+
+  // partial of this split: [max, sum, acc[D]] per query head
+  constexpr int PSTRIDE = D + 2;
+  for (int idx = tid; idx < G * D; idx += WG) {
+    const int g = idx / D, c = idx - g * D;
+    float mw[WAVES];
+    float mx = neg_inf();
+#pragma unroll
+    for (int i = 0; i < WAVES; ++i) {
+      mw[i] = sh_m[g][i];
+      mx = fmaxf(mx, mw[i]);
+    }
+    const float ms = mx == neg_inf() ? 0.f : mx;
+    float zt = 0.f, at = 0.f;
+#pragma unroll
+    for (int i = 0; i < WAVES; ++i) {
+      const float a = exp2f(mw[i] - ms);
+      zt = fmaf(sh_z[g][i], a, zt);
+      at = fmaf(sh_acc[g][i][c], a, at);
+    }
+    float* part = p.partials + ((size_t)(b * p.Hq + hq0 + g) * p.nsplit + split) * PSTRIDE;
+    part[2 + c] = at;
+    if (c == 0) {
+      part[0] = mx;
+      part[1] = zt;
+    }
+  }
+}
+
+// ---------------------------------------------------------------- record (+ keep flags)
+
+template <int G>
+__global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const int D) {
+  const int split = blockIdx.x;
+  const int unit = blockIdx.y;
+  const UnitLen ul = unit_len(p, unit);
+  const int L = ul.L;
+  const int tid = threadIdx.x;
+  if (split == 0 && tid == 0 && ul.flags && p.status) atomicOr(p.status, ul.flags);
+  const int nlive = (L + CHUNK - 1) / CHUNK;
+  if (split >= nlive && split != 0) return;
+
+  const int b = unit / p.Hkv;
+  const int hkv = unit - b * p.Hkv;
+  const int hq0 = hkv * G;
+  const int lane = tid & 63, wv = tid >> 6;
+  const int PSTRIDE = D + 2;
+
+  __shared__ float sh_M[G], sh_Z[G];
+  __shared__ int sh_cnt[WAVES];
+
+  // global max and sum of Eq. 2 from the split partials (wave g handles head g, g + WAVES, ...)
+  for (int g = wv; g < G; g += WAVES) {
+    const float* part0 = p.partials + (size_t)(b * p.Hq + hq0 + g) * p.nsplit * PSTRIDE;
+    float mx = neg_inf();
+    for (int s = lane; s < nlive; s += 64) mx = fmaxf(mx, part0[(size_t)s * PSTRIDE]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+    const float ms = mx == neg_inf() ? 0.f : mx;
+    float zt = 0.f;
+    for (int s = lane; s < nlive; s += 64) {
+      const float* ps = part0 + (size_t)s * PSTRIDE;
+      zt = fmaf(ps[1], exp2f(ps[0] - ms), zt);
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) zt += __shfl_xor(zt, off);
+    if (lane == 0) {
+      sh_M[g] = ms;
+      sh_Z[g] = zt;
+    }
+  }
+  __syncthreads();
+
+  // out (Eq. 1): split 0 merges the accumulators
+  if (split == 0) {
+    for (int idx = tid; idx < G * D; idx += WG) {
+      const int g = idx / D, c = idx - g * D;
+      const float* part0 = p.partials + (size_t)(b * p.Hq + hq0 + g) * p.nsplit * PSTRIDE;
+      const float ms = sh_M[g];
+      float at = 0.f;
+      for (int s = 0; s < nlive; ++s) {
+        const float* ps = part0 + (size_t)s * PSTRIDE;
+        at = fmaf(ps[2 + c], exp2f(ps[0] - ms), at);
+      }
+      p.out[(size_t)(b * p.Hq + hq0 + g) * D + c] = L > 0 ? at / sh_Z[g] : 0.f;
+    }
+  }
+  if (split >= nlive) return;  // an empty unit: nothing to record
+
+  // record (Def. 3.1) and decide (Def. 4.1 + recent r) for the keys of this chunk
+  const int tcur = p.t[b];
+  const bool step_ok = tcur >= 1 && tcur <= p.Tcap;
+  if (!step_ok && split == 0 && tid == 0 && p.status) atomicOr(p.status, CORM_DEV_BAD_STEP);
+  const int slot = step_ok ? (tcur - 1) % p.w : 0;
+  const float thr = importance_threshold(p.thr_scale, step_ok ? tcur : 1);
+  const bool full = p.do_evict && step_ok && (tcur - p.t_first[b] + 1 >= p.w);
+  const int32_t* posb = p.pos + (size_t)unit * p.Lcap;
+  int32_t* lhb = p.last_hit + (size_t)unit * p.Lcap;
+  const float* logit_u = p.logits + (size_t)(b * p.Hq + hq0) * p.Lcap;
+  uint8_t* keepb = p.keep ? p.keep + (size_t)unit * p.Lcap : nullptr;
+
+  const int cbeg = split * CHUNK;
+  const int cend = min(cbeg + CHUNK, L);
+  int kept = 0;
+  for (int i = cbeg + tid; i < cbeg + CHUNK; i += WG) {
+    const bool live = i < cend;
+    bool keep = false;
+    if (live) {
+      const int my_pos = posb[i];
+      int my_lh = lhb[i];
+      const bool pos_ok = my_pos >= 0 && my_pos < p.Tcap;
+      if (!pos_ok && p.status) atomicOr(p.status, CORM_DEV_BAD_STEP);
+      bool hit = false;
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float sc = exp2f(logit_u[(size_t)g * p.Lcap + i] - sh_M[g]) / sh_Z[g];
+        float stored;
+        const size_t ri = ((size_t)(b * p.Hq + hq0 + g) * p.w + slot) * p.Tcap + (size_t)my_pos;
+        if (p.ring_bf16) {
+          const uint16_t hb = f32_to_bf16_rne(sc);
+          stored = __uint_as_float((uint32_t)hb << 16);
+          if (step_ok && pos_ok) reinterpret_cast<uint16_t*>(p.ring)[ri] = hb;
+        } else {
+          stored = sc;
+          if (step_ok && pos_ok) reinterpret_cast<float*>(p.ring)[ri] = sc;
+        }
+        hit |= (stored >= thr);
+      }
+      if (hit && step_ok) {
+        my_lh = tcur;
+        lhb[i] = tcur;
+      }
+      keep = !full || (my_lh > tcur - p.w) || (i >= L - p.r);
+      if (p.do_evict && keepb) keepb[i] = keep ? 1 : 0;
+    }
+    kept += __popcll(__ballot(keep));
+  }
+  if (p.do_evict) {
+    if (lane == 0) sh_cnt[wv] = kept;
+    __syncthreads();
+    if (tid == 0) {
+      int tot = 0;
+#pragma unroll
+      for (int i = 0; i < WAVES; ++i) tot += sh_cnt[i];
+      p.counts[(size_t)unit * p.nsplit + split] = tot;
+    }
+  }
+}
+
 // ---------------------------------------------------------------- stable in-place compaction of one unit
 //
-// Called by all WG threads of ONE workgroup.  Tiles of WG slots in ascending order; for each tile:
-// keep flags -> exclusive scan (ballot + popcount per wave, LDS across waves, running base across
-// tiles) -> metadata moves -> cooperative row moves of K and V.  Because every destination is <=
-// its source and tiles ascend, a tile's writes can only land on slots whose contents were already
-// read; inside a tile all reads complete (explicit wait + barrier) before any write.
+// One workgroup per unit.  Tiles of WG slots in ascending order; for each tile: keep flags ->
+// exclusive scan (ballot + popcount per wave, LDS across waves, running base across tiles) ->
+// metadata moves -> cooperative row moves of K and V.  Every destination is <= its source and
+// tiles ascend, so a tile's writes only land on slots whose contents were already read; inside a
+// tile all reads complete (explicit wait + barrier) before any write.
 
 struct CompactShared {
   int32_t wave_count[WAVES];
@@ -200,14 +573,14 @@ __device__ __forceinline__ void move_rows(char* Kb, char* Vb, const int32_t* src
 // rank among the tile's survivors and the tile's survivor count (via *tile_kept).
 __device__ __forceinline__ int tile_scan(bool keep, CompactShared& sh, int* tile_kept) {
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  unsigned long long bal = __ballot(keep);
-  int rank = __popcll(bal & ((1ull << lane) - 1ull));
+  const unsigned long long bal = __ballot(keep);
+  const int rank = __popcll(bal & ((1ull << lane) - 1ull));
   if (lane == 0) sh.wave_count[wv] = __popcll(bal);
   __syncthreads();
   int before = 0, total = 0;
 #pragma unroll
   for (int i = 0; i < WAVES; ++i) {
-    int c = sh.wave_count[i];
+    const int c = sh.wave_count[i];
     if (i < wv) before += c;
     total += c;
   }
@@ -215,306 +588,56 @@ __device__ __forceinline__ int tile_scan(bool keep, CompactShared& sh, int* tile
   return before + rank;
 }
 
-// ---------------------------------------------------------------- the fused step kernel
-
-template <typename DT, int D, int G>
-__global__ __launch_bounds__(WG) void corm_step_kernel(const Params p) {
-  constexpr int EPL = DT::EPL;
-  constexpr int ROWB = D * DT::ESZ;
-  constexpr int LPR = ROWB / 16;    // lanes per row
-  constexpr int RPL = 64 / LPR;     // rows per wave-wide load
-  constexpr int U = UNROLL;
-  static_assert(U <= LPR, "logit store uses one lane per unrolled load");
-
-  const int split = blockIdx.x;
-  const int unit = blockIdx.y;
-  const int b = unit / p.Hkv;
-  const int hkv = unit - b * p.Hkv;
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wv = tid >> 6;
-  const int sub = lane / LPR, cl = lane % LPR;
-
-  __shared__ float sh_m[G][WAVES];
-  __shared__ float sh_z[G][WAVES];
-  __shared__ float sh_acc[G][WAVES][D];
-  __shared__ float sh_M[G], sh_Z[G];
-  __shared__ int sh_flag;
+// counts != nullptr: the record kernel's per-split survivor counts allow an early exit when the
+// unit lost nothing.  do_append: lens still holds the length before the step's append.
+template <int ROWB>
+__global__ __launch_bounds__(WG) void corm_compact_kernel(char* K, char* V, int32_t* pos, int32_t* last_hit,
+                                                          int32_t* lens, const uint8_t* keep, int32_t* kept_idx,
+                                                          const int32_t* counts, int nsplit, int Lcap,
+                                                          int do_append) {
   __shared__ CompactShared sh_c;
-
-  // ---- unit geometry
-  int L0 = p.lens[unit];
-  if (L0 < 0 || L0 > p.Lcap) {
-    if (tid == 0 && split == 0 && p.status) atomicOr(p.status, CORM_DEV_BAD_LENS);
-    L0 = L0 < 0 ? 0 : p.Lcap;
-  }
-  int L = L0;
-  bool appended = false;
-  if (p.do_append) {
-    if (L0 < p.Lcap) {
-      L = L0 + 1;
-      appended = true;
-    } else if (tid == 0 && split == 0 && p.status) {
-      atomicOr(p.status, CORM_DEV_UNIT_FULL);
+  const int unit = blockIdx.x;
+  const int tid = threadIdx.x;
+  int L = lens[unit];
+  L = L < 0 ? 0 : (L > Lcap ? Lcap : L);
+  if (do_append && L < Lcap) L += 1;
+  int32_t* idxb = kept_idx ? kept_idx + (size_t)unit * Lcap : nullptr;
+  if (counts) {
+    const int nlive = (L + CHUNK - 1) / CHUNK;
+    int tot = 0;
+    for (int s = 0; s < nlive; ++s) tot += counts[(size_t)unit * nsplit + s];
+    if (tot == L) {  // nothing evicted: the cache is already compact
+      if (idxb)
+        for (int i = tid; i < L; i += WG) idxb[i] = i;
+      if (tid == 0) lens[unit] = L;
+      return;
     }
   }
-  // splits that hold live keys; the others only take part in the arrival count, so that nobody
-  // reads lens[unit] after the finalizing workgroup has rewritten it
-  const int nlive = (L + CHUNK - 1) / CHUNK;
-  const int tcur = p.t[b];
-
-  char* Kb = reinterpret_cast<char*>(p.K) + (size_t)unit * p.Lcap * ROWB;
-  char* Vb = reinterpret_cast<char*>(p.V) + (size_t)unit * p.Lcap * ROWB;
-  const char* knew = reinterpret_cast<const char*>(p.k_new) + (size_t)unit * ROWB;
-  const char* vnew = reinterpret_cast<const char*>(p.v_new) + (size_t)unit * ROWB;
-  int32_t* posb = p.pos + (size_t)unit * p.Lcap;
-  int32_t* lhb = p.last_hit + (size_t)unit * p.Lcap;
-  const int hq0 = hkv * G;
-
-  // ---- this lane's slice of the G queries
-  uint4 qreg[G];
-#pragma unroll
-  for (int g = 0; g < G; ++g)
-    qreg[g] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(p.q) +
-                                              ((size_t)(b * p.Hq + hq0 + g) * ROWB + (size_t)cl * 16));
-
-  const int cbeg = split * CHUNK;
-  const int cend = min(cbeg + CHUNK, L);
-  constexpr int PSTRIDE = D + 2;  // partial of one split and head: [max, sum, acc[D]]
-  float* logit_u = p.logits + (size_t)(b * p.Hq + hq0) * p.Lcap;
-
-  if (split < nlive) {
-
-  // the appended row: the owner of its chunk writes it into the cache (one wave) ...
-  if (appended && L0 >= cbeg && L0 < cend && wv == 0) {
-    if (lane < LPR) {
-      uint4 kx = *reinterpret_cast<const uint4*>(knew + (size_t)lane * 16);
-      uint4 vx = *reinterpret_cast<const uint4*>(vnew + (size_t)lane * 16);
-      *reinterpret_cast<uint4*>(Kb + (size_t)L0 * ROWB + (size_t)lane * 16) = kx;
-      *reinterpret_cast<uint4*>(Vb + (size_t)L0 * ROWB + (size_t)lane * 16) = vx;
-    }
-    if (lane == 0) {
-      posb[L0] = tcur - 1;
-      lhb[L0] = 0;
-    }
-  }
-
-  float m_run[G], z_run[G], acc[G][EPL];
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    m_run[g] = neg_inf();
-    z_run[g] = 0.f;
-#pragma unroll
-    for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
-  }
-
-  for (int it = cbeg; it < cend; it += WAVES * RPL * U) {
-    uint4 kreg[U], vreg[U];
-    int row[U];
-#pragma unroll
-    for (int j = 0; j < U; ++j) {
-      row[j] = it + (j * WAVES + wv) * RPL + sub;
-      int rc = min(row[j], cend - 1);
-      // ... and everybody reads that row from the step's input, not from the cache
-      const char* kp = (appended && rc == L0) ? knew : Kb + (size_t)rc * ROWB;
-      kreg[j] = *reinterpret_cast<const uint4*>(kp + (size_t)cl * 16);
-    }
-#pragma unroll
-    for (int j = 0; j < U; ++j) {
-      int rc = min(row[j], cend - 1);
-      const char* vp = (appended && rc == L0) ? vnew : Vb + (size_t)rc * ROWB;
-      vreg[j] = *reinterpret_cast<const uint4*>(vp + (size_t)cl * 16);
-    }
-
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float s[U];
-      float my_logit = 0.f;
-      int my_row = -1;
-#pragma unroll
-      for (int j = 0; j < U; ++j) {
-        float part = DT::dot(kreg[j], qreg[g]);
-        float tot = row_allreduce_sum<LPR>(part) * p.scale_log2;
-        s[j] = row[j] < cend ? tot : neg_inf();
-        if (cl == j && row[j] < cend) {
-          my_logit = tot;
-          my_row = row[j];
-        }
-      }
-      if (my_row >= 0) logit_u[(size_t)g * p.Lcap + my_row] = my_logit;
-
-      float mnew = m_run[g];
-#pragma unroll
-      for (int j = 0; j < U; ++j) mnew = fmaxf(mnew, s[j]);
-      const float msafe = mnew == neg_inf() ? 0.f : mnew;
-      const float a = exp2f(m_run[g] - msafe);
-      float pj[U];
-      float zs = 0.f;
-#pragma unroll
-      for (int j = 0; j < U; ++j) {
-        pj[j] = exp2f(s[j] - msafe);
-        zs += pj[j];
-      }
-      z_run[g] = fmaf(z_run[g], a, zs);
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) acc[g][e] *= a;
-#pragma unroll
-      for (int j = 0; j < U; ++j) DT::axpy(acc[g], pj[j], vreg[j]);
-      m_run[g] = mnew;
-    }
-  }
-
-  // ---- merge the RPL row groups of the wave (lanes differing in bits >= log2(LPR)), then the waves
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-#pragma unroll
-    for (int off = LPR; off < 64; off <<= 1) {
-      float mo = __shfl_xor(m_run[g], off);
-      float zo = __shfl_xor(z_run[g], off);
-      float mn = fmaxf(m_run[g], mo);
-      float ms = mn == neg_inf() ? 0.f : mn;
-      float a0 = exp2f(m_run[g] - ms), a1 = exp2f(mo - ms);
-      z_run[g] = z_run[g] * a0 + zo * a1;
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) {
-        float ao = __shfl_xor(acc[g][e], off);
-        acc[g][e] = acc[g][e] * a0 + ao * a1;
-      }
-      m_run[g] = mn;
-    }
-    if (sub == 0) {
-#pragma unroll
-      for (int e = 0; e < EPL; ++e) sh_acc[g][wv][cl * EPL + e] = acc[g][e];
-      if (cl == 0) {
-        sh_m[g][wv] = m_run[g];
-        sh_z[g][wv] = z_run[g];
-      }
-    }
-  }
-  __syncthreads();
-
-  // partial of this split: [m, z, acc[D]] per query head
-  for (int idx = tid; idx < G * D; idx += WG) {
-    const int g = idx / D, c = idx - g * D;
-    float mw[WAVES];
-    float mx = neg_inf();
-#pragma unroll
-    for (int i = 0; i < WAVES; ++i) {
-      mw[i] = sh_m[g][i];
-      mx = fmaxf(mx, mw[i]);
-    }
-    const float ms = mx == neg_inf() ? 0.f : mx;
-    float zt = 0.f, at = 0.f;
-#pragma unroll
-    for (int i = 0; i < WAVES; ++i) {
-      float a = exp2f(mw[i] - ms);
-      zt = fmaf(sh_z[g][i], a, zt);
-      at = fmaf(sh_acc[g][i][c], a, at);
-    }
-    float* part = p.partials + ((size_t)(b * p.Hq + hq0 + g) * p.nsplit + split) * PSTRIDE;
-    part[2 + c] = at;
-    if (c == 0) {
-      part[0] = mx;
-      part[1] = zt;
-    }
-  }
-
-  }  // split < nlive
-
-  // ---- arrival: the last workgroup of the unit finalizes it
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) {
-    int old = atomicAdd(&p.counters[unit], 1);
-    int last = (old == (int)gridDim.x - 1);
-    if (last) p.counters[unit] = 0;  // leave the counter ready for the next launch
-    sh_flag = last;
-  }
-  __syncthreads();
-  if (!sh_flag) return;
-  __threadfence();
-
-  // ---- merge the split partials -> out (Eq. 1), and the global max / sum of Eq. 2
-  for (int g = 0; g < G; ++g) {
-    const float* part0 = p.partials + (size_t)(b * p.Hq + hq0 + g) * p.nsplit * PSTRIDE;
-    float mx = neg_inf();
-    for (int s = 0; s < nlive; ++s) mx = fmaxf(mx, part0[(size_t)s * PSTRIDE]);
-    const float ms = mx == neg_inf() ? 0.f : mx;
-    if (tid < D) {
-      float zt = 0.f, at = 0.f;
-      for (int s = 0; s < nlive; ++s) {
-        const float* ps = part0 + (size_t)s * PSTRIDE;
-        float a = exp2f(ps[0] - ms);
-        zt = fmaf(ps[1], a, zt);
-        at = fmaf(ps[2 + tid], a, at);
-      }
-      p.out[(size_t)(b * p.Hq + hq0 + g) * D + tid] = L > 0 ? at / zt : 0.f;
-      if (tid == 0) {
-        sh_M[g] = ms;
-        sh_Z[g] = zt;
-      }
-    }
-  }
-  __syncthreads();
-  if (L == 0) {
-    return;
-  }
-
-  // ---- record (Def. 3.1), decide (Def. 4.1 + recent r), compact (Algorithm 1's gather)
-  const bool step_ok = tcur >= 1 && tcur <= p.Tcap;
-  if (!step_ok && tid == 0 && p.status) atomicOr(p.status, CORM_DEV_BAD_STEP);
-  const int slot = step_ok ? (tcur - 1) % p.w : 0;
-  const float thr = importance_threshold(p.thr_scale, step_ok ? tcur : 1);
-  const bool full = p.do_evict && step_ok && (tcur - p.t_first[b] + 1 >= p.w);
-  uint8_t* keepb = p.keep_out ? p.keep_out + (size_t)unit * p.Lcap : nullptr;
-  int32_t* idxb = p.kept_idx ? p.kept_idx + (size_t)unit * p.Lcap : nullptr;
-
-  int dst_base = 0;  // survivors before the current tile
+  char* Kb = K + (size_t)unit * Lcap * ROWB;
+  char* Vb = V + (size_t)unit * Lcap * ROWB;
+  int32_t* posb = pos + (size_t)unit * Lcap;
+  int32_t* lhb = last_hit + (size_t)unit * Lcap;
+  const uint8_t* keepb = keep + (size_t)unit * Lcap;
+  int dst_base = 0;
   for (int tile = 0; tile < L; tile += WG) {
     const int i = tile + tid;
     const bool live = i < L;
-    bool keep = false;
+    const bool kp = live && keepb[i] != 0;
     int my_pos = 0, my_lh = 0;
-    bool hit = false;
-    if (live) {
+    if (kp) {
       my_pos = posb[i];
       my_lh = lhb[i];
-      const bool pos_ok = my_pos >= 0 && my_pos < p.Tcap;
-      if (!pos_ok && p.status) atomicOr(p.status, CORM_DEV_BAD_STEP);
-#pragma unroll
-      for (int g = 0; g < G; ++g) {
-        float lg = logit_u[(size_t)g * p.Lcap + i];
-        float sc = exp2f(lg - sh_M[g]) / sh_Z[g];
-        float stored;
-        size_t ri = ((size_t)(b * p.Hq + hq0 + g) * p.w + slot) * p.Tcap + (size_t)my_pos;
-        if (p.ring_bf16) {
-          uint16_t hb = f32_to_bf16_rne(sc);
-          stored = __uint_as_float((uint32_t)hb << 16);
-          if (step_ok && pos_ok) reinterpret_cast<uint16_t*>(p.ring)[ri] = hb;
-        } else {
-          stored = sc;
-          if (step_ok && pos_ok) reinterpret_cast<float*>(p.ring)[ri] = sc;
-        }
-        hit |= (stored >= thr);
-      }
-      if (hit && step_ok) my_lh = tcur;
-      keep = !full || (my_lh > tcur - p.w) || (i >= L - p.r);
     }
-    if (!p.do_evict) {
-      if (live && hit && step_ok) lhb[i] = my_lh;
-      continue;
-    }
+    wait_vm_loads();
     int tile_kept;
-    const int rank = tile_scan(keep, sh_c, &tile_kept);
+    const int rank = tile_scan(kp, sh_c, &tile_kept);
     const int dst = dst_base + rank;
-    if (live && keepb) keepb[i] = keep ? 1 : 0;
-    if (keep) {
+    if (kp) {
       sh_c.src_of[rank] = i;
       if (idxb) idxb[dst] = i;
       if (dst != i) {
         posb[dst] = my_pos;
         lhb[dst] = my_lh;
-      } else if (hit) {
-        lhb[i] = my_lh;
       }
     }
     __syncthreads();
@@ -523,7 +646,7 @@ __global__ __launch_bounds__(WG) void corm_step_kernel(const Params p) {
     dst_base += tile_kept;
     __syncthreads();
   }
-  if (tid == 0 && (p.do_evict || p.do_append)) p.lens[unit] = p.do_evict ? dst_base : L;
+  if (tid == 0) lens[unit] = dst_base;
 }
 
 // ---------------------------------------------------------------- standalone kernels
@@ -603,52 +726,6 @@ __global__ __launch_bounds__(WG) void corm_evict_mask_summary_kernel(const int32
   keep[(size_t)unit * Lcap + i] = k ? 1 : 0;
 }
 
-template <int ROWB>
-__global__ __launch_bounds__(WG) void corm_compact_kernel(char* K, char* V, int32_t* pos, int32_t* last_hit,
-                                                          int32_t* lens, const uint8_t* keep, int32_t* kept_idx,
-                                                          int Lcap) {
-  __shared__ CompactShared sh_c;
-  const int unit = blockIdx.x;
-  const int tid = threadIdx.x;
-  int L = lens[unit];
-  L = L < 0 ? 0 : (L > Lcap ? Lcap : L);
-  char* Kb = K + (size_t)unit * Lcap * ROWB;
-  char* Vb = V + (size_t)unit * Lcap * ROWB;
-  int32_t* posb = pos + (size_t)unit * Lcap;
-  int32_t* lhb = last_hit + (size_t)unit * Lcap;
-  const uint8_t* keepb = keep + (size_t)unit * Lcap;
-  int32_t* idxb = kept_idx ? kept_idx + (size_t)unit * Lcap : nullptr;
-  int dst_base = 0;
-  for (int tile = 0; tile < L; tile += WG) {
-    const int i = tile + tid;
-    const bool live = i < L;
-    const bool kp = live && keepb[i] != 0;
-    int my_pos = 0, my_lh = 0;
-    if (kp) {
-      my_pos = posb[i];
-      my_lh = lhb[i];
-    }
-    wait_vm_loads();
-    int tile_kept;
-    const int rank = tile_scan(kp, sh_c, &tile_kept);
-    const int dst = dst_base + rank;
-    if (kp) {
-      sh_c.src_of[rank] = i;
-      if (idxb) idxb[dst] = i;
-      if (dst != i) {
-        posb[dst] = my_pos;
-        lhb[dst] = my_lh;
-      }
-    }
-    __syncthreads();
-    const int tile_n = min(WG, L - tile);
-    if (!(dst_base == tile && tile_kept == tile_n)) move_rows<ROWB>(Kb, Vb, sh_c.src_of, tile_kept, dst_base);
-    dst_base += tile_kept;
-    __syncthreads();
-  }
-  if (tid == 0) lens[unit] = dst_base;
-}
-
 __global__ void corm_threshold_kernel(float c, const int32_t* t, int n, float* thr) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) thr[i] = importance_threshold(c, t[i]);
@@ -662,7 +739,7 @@ __global__ void corm_fill_i32_kernel(int32_t* p, size_t n, int32_t v) {
 // ---------------------------------------------------------------- host side
 
 struct WorkspaceLayout {
-  size_t counters_off, partials_off, logits_off, total;
+  size_t counts_off, keep_off, partials_off, logits_off, total;
   int nsplit;
 };
 
@@ -671,13 +748,12 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 WorkspaceLayout workspace_layout(const corm_desc& d) {
   WorkspaceLayout w;
   w.nsplit = (d.Lcap + CHUNK - 1) / CHUNK;
-  w.counters_off = 0;
-  size_t counters = (size_t)d.B * d.Hkv * sizeof(int32_t);
-  w.partials_off = align_up(counters, 256);
-  size_t partials = (size_t)d.B * d.Hq * w.nsplit * (d.d + 2) * sizeof(float);
-  w.logits_off = align_up(w.partials_off + partials, 256);
-  size_t logits = (size_t)d.B * d.Hq * d.Lcap * sizeof(float);
-  w.total = align_up(w.logits_off + logits, 256);
+  const size_t units = (size_t)d.B * d.Hkv, heads = (size_t)d.B * d.Hq;
+  w.counts_off = 0;
+  w.keep_off = align_up(units * w.nsplit * sizeof(int32_t), 256);
+  w.partials_off = align_up(w.keep_off + units * d.Lcap, 256);
+  w.logits_off = align_up(w.partials_off + heads * w.nsplit * (d.d + 2) * sizeof(float), 256);
+  w.total = align_up(w.logits_off + heads * d.Lcap * sizeof(float), 256);
   return w;
 }
 
@@ -704,24 +780,53 @@ int row_bytes(const corm_desc* d) { return d->d * (d->kv_dtype == CORM_F32 ? 4 :
 
 int launch_status() { return hipGetLastError() == hipSuccess ? CORM_OK : CORM_EHIP; }
 
+// optional events recorded around the attend launch of the next step call (corm_profile_attend)
+hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
+
 template <typename DT, int D>
-int launch_step_g(const Params& p, int G, dim3 grid, hipStream_t s) {
+int launch_attend_g(const Params& p, int G, dim3 grid, hipStream_t s) {
   switch (G) {
-    case 1: hipLaunchKernelGGL((corm_step_kernel<DT, D, 1>), grid, dim3(WG), 0, s, p); break;
-    case 2: hipLaunchKernelGGL((corm_step_kernel<DT, D, 2>), grid, dim3(WG), 0, s, p); break;
-    case 4: hipLaunchKernelGGL((corm_step_kernel<DT, D, 4>), grid, dim3(WG), 0, s, p); break;
-    case 8: hipLaunchKernelGGL((corm_step_kernel<DT, D, 8>), grid, dim3(WG), 0, s, p); break;
+    case 1: hipLaunchKernelGGL((corm_attend_kernel<DT, D, 1>), grid, dim3(WG), 0, s, p); break;
+    case 2: hipLaunchKernelGGL((corm_attend_kernel<DT, D, 2>), grid, dim3(WG), 0, s, p); break;
+    case 4: hipLaunchKernelGGL((corm_attend_kernel<DT, D, 4>), grid, dim3(WG), 0, s, p); break;
+    case 8: hipLaunchKernelGGL((corm_attend_kernel<DT, D, 8>), grid, dim3(WG), 0, s, p); break;
     default: return CORM_EUNSUPPORTED;
   }
   return launch_status();
 }
 
+int launch_record(const Params& p, int G, int D, dim3 grid, hipStream_t s) {
+  switch (G) {
+    case 1: hipLaunchKernelGGL((corm_record_kernel<1>), grid, dim3(WG), 0, s, p, D); break;
+    case 2: hipLaunchKernelGGL((corm_record_kernel<2>), grid, dim3(WG), 0, s, p, D); break;
+    case 4: hipLaunchKernelGGL((corm_record_kernel<4>), grid, dim3(WG), 0, s, p, D); break;
+    case 8: hipLaunchKernelGGL((corm_record_kernel<8>), grid, dim3(WG), 0, s, p, D); break;
+    default: return CORM_EUNSUPPORTED;
+  }
+  return launch_status();
+}
+
+int launch_compact(const corm_desc* d, char* K, char* V, int32_t* pos, int32_t* last_hit, int32_t* lens,
+                   const uint8_t* keep, int32_t* kept_idx, const int32_t* counts, int nsplit, int do_append,
+                   hipStream_t s) {
+  dim3 grid(d->B * d->Hkv);
+  switch (row_bytes(d)) {
+    case 128: hipLaunchKernelGGL((corm_compact_kernel<128>), grid, dim3(WG), 0, s, K, V, pos, last_hit, lens, keep, kept_idx, counts, nsplit, d->Lcap, do_append); break;
+    case 256: hipLaunchKernelGGL((corm_compact_kernel<256>), grid, dim3(WG), 0, s, K, V, pos, last_hit, lens, keep, kept_idx, counts, nsplit, d->Lcap, do_append); break;
+    case 512: hipLaunchKernelGGL((corm_compact_kernel<512>), grid, dim3(WG), 0, s, K, V, pos, last_hit, lens, keep, kept_idx, counts, nsplit, d->Lcap, do_append); break;
+    default: return CORM_EUNSUPPORTED;
+  }
+  return launch_status();
+}
+
+// attend + record (+ compact when evicting), all on stream s
 int launch_step(const corm_desc* d, Params& p, void* workspace, size_t workspace_bytes, hipStream_t s) {
-  WorkspaceLayout wl = workspace_layout(*d);
+  const WorkspaceLayout wl = workspace_layout(*d);
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return CORM_EINVAL;
   if (workspace_bytes < wl.total) return CORM_ECAPACITY;
   char* ws = reinterpret_cast<char*>(workspace);
-  p.counters = reinterpret_cast<int32_t*>(ws + wl.counters_off);
+  p.counts = reinterpret_cast<int32_t*>(ws + wl.counts_off);
+  if (!p.keep) p.keep = reinterpret_cast<uint8_t*>(ws + wl.keep_off);
   p.partials = reinterpret_cast<float*>(ws + wl.partials_off);
   p.logits = reinterpret_cast<float*>(ws + wl.logits_off);
   p.B = d->B; p.Hq = d->Hq; p.Hkv = d->Hkv; p.Lcap = d->Lcap; p.Tcap = d->Tcap; p.w = d->w; p.r = d->r;
@@ -731,11 +836,22 @@ int launch_step(const corm_desc* d, Params& p, void* workspace, size_t workspace
   p.scale_log2 = sm * LOG2E;
   p.ring_bf16 = d->score_dtype == CORM_BF16;
   const int G = d->Hq / d->Hkv;
-  dim3 grid(wl.nsplit, d->B * d->Hkv);
+  const dim3 grid(wl.nsplit, d->B * d->Hkv);
+  int rc;
+  const hipEvent_t ev0 = g_prof_start, ev1 = g_prof_stop;
+  g_prof_start = g_prof_stop = nullptr;
+  if (ev0 && hipEventRecord(ev0, s) != hipSuccess) return CORM_EHIP;
   if (d->kv_dtype == CORM_F32) {
-    return d->d == 64 ? launch_step_g<F32, 64>(p, G, grid, s) : launch_step_g<F32, 128>(p, G, grid, s);
+    rc = d->d == 64 ? launch_attend_g<F32, 64>(p, G, grid, s) : launch_attend_g<F32, 128>(p, G, grid, s);
+  } else {
+    rc = d->d == 64 ? launch_attend_g<BF16, 64>(p, G, grid, s) : launch_attend_g<BF16, 128>(p, G, grid, s);
   }
-  return d->d == 64 ? launch_step_g<BF16, 64>(p, G, grid, s) : launch_step_g<BF16, 128>(p, G, grid, s);
+  if (rc) return rc;
+  if (ev1 && hipEventRecord(ev1, s) != hipSuccess) return CORM_EHIP;
+  rc = launch_record(p, G, d->d, grid, s);
+  if (rc || !p.do_evict) return rc;
+  return launch_compact(d, reinterpret_cast<char*>(p.K), reinterpret_cast<char*>(p.V), p.pos, p.last_hit, p.lens,
+                        p.keep, p.kept_idx, p.counts, wl.nsplit, p.do_append, s);
 }
 
 }  // namespace
@@ -769,11 +885,11 @@ int corm_workspace_init(const corm_desc* desc, void* workspace, size_t workspace
   int rc = validate_desc(desc);
   if (rc) return rc;
   if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return CORM_EINVAL;
-  WorkspaceLayout wl = workspace_layout(*desc);
+  const WorkspaceLayout wl = workspace_layout(*desc);
   if (workspace_bytes < wl.total) return CORM_ECAPACITY;
-  size_t n = (size_t)desc->B * desc->Hkv;
+  const size_t n = (size_t)desc->B * desc->Hkv * wl.nsplit;
   hipLaunchKernelGGL(corm_fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
-                     reinterpret_cast<int32_t*>(workspace), n, 0);
+                     reinterpret_cast<int32_t*>(reinterpret_cast<char*>(workspace) + wl.counts_off), n, 0);
   return launch_status();
 }
 
@@ -845,18 +961,8 @@ int corm_compact(const corm_desc* desc, void* K, void* V, int32_t* pos, int32_t*
   if (misaligned16(K) || misaligned16(V) || misaligned4(pos) || misaligned4(last_hit) || misaligned4(lens) ||
       misaligned4(kept_idx))
     return CORM_EINVAL;
-  const int rb = row_bytes(desc);
-  dim3 grid(desc->B * desc->Hkv);
-  char* Kc = reinterpret_cast<char*>(K);
-  char* Vc = reinterpret_cast<char*>(V);
-  hipStream_t s = (hipStream_t)stream;
-  switch (rb) {
-    case 128: hipLaunchKernelGGL((corm_compact_kernel<128>), grid, dim3(WG), 0, s, Kc, Vc, pos, last_hit, lens, keep, kept_idx, desc->Lcap); break;
-    case 256: hipLaunchKernelGGL((corm_compact_kernel<256>), grid, dim3(WG), 0, s, Kc, Vc, pos, last_hit, lens, keep, kept_idx, desc->Lcap); break;
-    case 512: hipLaunchKernelGGL((corm_compact_kernel<512>), grid, dim3(WG), 0, s, Kc, Vc, pos, last_hit, lens, keep, kept_idx, desc->Lcap); break;
-    default: return CORM_EUNSUPPORTED;
-  }
-  return launch_status();
+  return launch_compact(desc, reinterpret_cast<char*>(K), reinterpret_cast<char*>(V), pos, last_hit, lens, keep,
+                        kept_idx, nullptr, 0, 0, (hipStream_t)stream);
 }
 
 int corm_decode_step(const corm_desc* desc, const void* q, const void* k_new, const void* v_new, void* K, void* V,
@@ -875,10 +981,17 @@ int corm_decode_step(const corm_desc* desc, const void* q, const void* k_new, co
     return CORM_EINVAL;
   Params p = {};
   p.q = q; p.k_new = k_new; p.v_new = v_new; p.K = K; p.V = V; p.lens = lens; p.pos = pos; p.last_hit = last_hit;
-  p.t = t; p.t_first = t_first; p.ring = score_ring; p.out = out; p.keep_out = keep; p.kept_idx = kept_idx;
+  p.t = t; p.t_first = t_first; p.ring = score_ring; p.out = out; p.keep = keep; p.kept_idx = kept_idx;
   p.status = status;
   p.do_append = 1; p.do_evict = 1;
   return launch_step(desc, p, workspace, workspace_bytes, (hipStream_t)stream);
+}
+
+int corm_profile_attend(void* start_event, void* stop_event) {
+  if ((start_event == nullptr) != (stop_event == nullptr)) return CORM_EINVAL;
+  g_prof_start = (hipEvent_t)start_event;
+  g_prof_stop = (hipEvent_t)stop_event;
+  return CORM_OK;
 }
 
 int corm_threshold(float c, const int32_t* t, int32_t n, float* thr, void* stream) {

@@ -16,11 +16,12 @@ import numpy as np
 import torch
 
 from oracle import corm_oracle as O
+from oracle.snapshot import unit_from_device_arrays
 from paper_2404_15949_amd import corm, inputs
 
 OUT_TOL = {"f32": 1e-5, "bf16": 2e-3}          # max_c |delta| / max_c |ref| per output row
-# recorded score vs the oracle's fp64 score: fp32 arithmetic error, plus bf16 storage rounding (2^-9 relative)
-SCORE_RTOL = {"f32": 2e-5, "bf16": 2.0 ** -8}
+# recorded score vs the oracle's fp64 score: fp32 arithmetic error, plus bf16 storage rounding
+SCORE_RTOL = {"f32": 2e-5, "bf16": 2.0 ** -8 + 5e-5}   # bf16 half-ulp is 2^-8 relative at worst
 SCORE_ATOL_OF_MAX = {"f32": 2e-6, "bf16": 1e-5}
 
 
@@ -157,19 +158,5 @@ def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_sca
 def oracle_from_snapshot(st: corm.LayerState, b: int, h: int, t_prev: int, t_first: int, dtype: str,
                          thr_scale: float) -> O.UnitCache:
     """Rebuild the oracle state of unit (b,h) from device memory as it stands after step t_prev."""
-    G = st.Hq // st.Hkv
-    u = O.UnitCache(st.d, G, st.w, st.r, thr_scale, score_dtype=dtype)
-    l = int(st.lens[b, h].item())
-    u.keys = _f32(st.K[b, h, :l]).astype(np.float64)
-    u.values = _f32(st.V[b, h, :l]).astype(np.float64)
-    u.positions = st.pos[b, h, :l].cpu().numpy().astype(np.int64)
-    rows = list(range(max(t_first, t_prev - st.w + 1), t_prev + 1))
-    pos_t = torch.from_numpy(u.positions).to(st.ring.device)
-    msg = np.zeros((len(rows), G, l), dtype=bool)
-    for a, tau in enumerate(rows):
-        sc = _f32(st.ring[b, h * G:(h + 1) * G, (tau - 1) % st.w][:, pos_t])      # [G, l]
-        born = u.positions <= tau - 1
-        msg[a] = O.important(sc, tau, thr_scale) & born[None, :]
-    u.message = msg
-    u.row_steps = rows
-    return u
+    return unit_from_device_arrays(st.K, st.V, st.pos, st.lens, st.ring, b, h, st.Hq // st.Hkv, st.w, st.r,
+                                   t_prev, t_first, dtype, thr_scale)

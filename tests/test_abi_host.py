@@ -43,8 +43,9 @@ def test_workspace_size_formula():
     d = _desc()
     n = corm.corm_workspace_bytes(d)
     nsplit = (1024 + 511) // 512
-    need = 2 * 2 * 4 + 2 * 8 * nsplit * 130 * 4 + 2 * 8 * 1024 * 4
-    assert need <= n <= need + 3 * 256
+    units, heads = 2 * 2, 2 * 8
+    need = units * nsplit * 4 + units * 1024 + heads * nsplit * 130 * 4 + heads * 1024 * 4
+    assert need <= n <= need + 4 * 256
 
 
 @pytest.mark.parametrize("kw,code", [

@@ -29,7 +29,7 @@ TRAJ = {
     # grouped queries on bf16: G = 4 and G = 2, G = 8
     "bf16_gqa4": (W["gqa_llama3"].replace(B=2, Hq=8, Hkv=2, P=600, D=40, w=40, r=40), 8),
     "bf16_gqa2": (W["gqa_llama3"].replace(B=1, Hq=4, Hkv=2, P=300, D=30, w=24, r=24), 8),
-    "bf16_gqa8": (W["gqa_llama3"].replace(B=1, Hq=8, Hkv=1, P=530, D=20, w=24, r=24), 8),
+    "bf16_gqa8": (W["gqa_llama3"].replace(B=1, Hq=8, Hkv=1, P=530, D=20, w=4, r=4, key_scale=2.0), 8),
     # other row geometries: fp32 d128 (512-byte rows), bf16 d64 (128-byte rows)
     "f32_d128": (W["tiny_f32"].replace(d=128, Hq=2, Hkv=2, P=540, D=30, w=24, r=24), 6),
     "bf16_d64": (W["llama7b_1layer"].replace(B=1, Hq=2, Hkv=2, d=64, P=520, D=30, w=24, r=24), 6),
@@ -180,7 +180,7 @@ def test_evict_mask_standalone_random_ring():
                     want = O.keep_from_score_window(sc, rows, w, r)
                     got = st.keep[b, h, :l].cpu().numpy().astype(bool)
                     assert np.array_equal(got, want), (dtype, tcur, tfirst, b, h)
-                    if len(rows) >= w:
+                    if len(rows) >= w and l > 50:
                         assert not want.all()
 
 
@@ -215,7 +215,7 @@ def test_attend_edge_lengths_and_status_flags():
     say("status: unit full")
     k = torch.randn(B, Hkv, d, generator=g).to(torch.bfloat16).to(DEV)
     K_before = st.K.clone()
-    tf = torch.ones(B, dtype=torch.int32, device=DEV)
+    tf = t.clone()            # window not full: nothing is evicted
     st.step(q, k, k, t, tf)
     torch.cuda.synchronize()
     assert int(st.status.item()) & corm.CORM_DEV_UNIT_FULL
