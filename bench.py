@@ -38,18 +38,25 @@ def parse():
     ap.add_argument("--structured", action="store_true",
                     help="supplementary variant: per-head query means so that eviction happens at w >= 256")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference dispatch for rocprofv3 byte counters)")
     ap.add_argument("--cpu-units", type=int, default=24)
     ap.add_argument("--cpu-steps", type=int, default=6)
     return ap.parse_args()
 
 
-def algorithmic_bytes(lens_before, wl, esz, ssz):
-    """Bytes one launch must move for units whose live lengths (before the append) are lens_before:
-    K and V rows read once, the ring row written, pos and last_hit read; q/k_new/v_new/out per head.
-    (Rows moved by the compaction and the logits scratch are NOT counted.)"""
+def algorithmic_bytes(lens_before, wl, esz, ssz, part="step"):
+    """Bytes a launch must move for units whose live lengths (before the append) are lens_before.
+    part="attend": what the attend kernel streams -- every live K and V row once, plus per unit the G
+    queries, k_new and v_new read and the appended row written.
+    part="step": that plus the record kernel's share: ring row written, pos and last_hit read, out written.
+    Rows moved by the compaction, the logits scratch and the split partials are NOT counted."""
     L = lens_before.double() + 1.0
-    per_key = 2 * wl.d * esz + wl.G * ssz + 8
-    per_unit = (2 * wl.G + 2) * wl.d * esz + wl.G * wl.d * 4
+    per_key = 2 * wl.d * esz
+    per_unit = (wl.G + 4) * wl.d * esz
+    if part == "step":
+        per_key += wl.G * ssz + 8
+        per_unit += wl.G * wl.d * 4
     return float((L * per_key).sum().item() + L.numel() * per_unit)
 
 
@@ -124,6 +131,13 @@ def main():
     if not args.no_cpu_baseline:
         cpu_baseline = cpu_baseline_leg(args, wl, states, Qs, Kns, Vns, n_replay, pre, layers)
 
+    if args.calibrate_copy:
+        src = torch.ones(2 ** 28, dtype=torch.float32, device=dev)   # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---------------- warm-up, then the timed region
     for j in range(n_replay, n_replay + W_steps):
         run_step(j)
@@ -155,7 +169,7 @@ def main():
     ssz = esz
     # the dominant kernel (attend): algorithmic bytes of the probed launches / their measured durations
     probe_ms = [hip.elapsed_ms(a, b_) for (a, b_) in pairs]
-    probe_bytes = [algorithmic_bytes(lens_hist[k][k % layers], wl, esz, ssz) for k in range(K_steps)]
+    probe_bytes = [algorithmic_bytes(lens_hist[k][k % layers], wl, esz, ssz, "attend") for k in range(K_steps)]
     avg_attend_ms = sum(probe_ms) / len(probe_ms)
     bytes_per_launch = sum(probe_bytes) / len(probe_bytes)
     achieved = bytes_per_launch / (avg_attend_ms * 1e-3) / 1e9
