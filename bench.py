@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--layers", type=int, default=None, help="override the number of layers (development only)")
     ap.add_argument("--structured", action="store_true",
                     help="supplementary variant: per-head query means so that eviction happens at w >= 256")
+    ap.add_argument("--streams", type=int, default=2, choices=[1, 2],
+                    help="2: attend on the main stream, record+evict+compact of the same layer on a second stream\n"
+                         "(overlaps the next layer's attend); 1: the fused call on one stream")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference dispatch for rocprofv3 byte counters)")
@@ -113,14 +116,43 @@ def main():
     log(f"allocated + generated {layers} layers in {time.time() - t0:.1f}s; "
         f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB resident")
 
-    def run_step(j):
+    # Launch order of one step.  One stream: the fused call per layer.  Two streams: layer n's attend runs on
+    # the main stream; its record + evict + compact run on a side stream (ordered by events) while the main
+    # stream already attends over the next layer.  Two workspaces alternate, so attend n waits for evict n-2.
+    main = torch.cuda.current_stream()
+    side = torch.cuda.Stream() if args.streams == 2 else None
+    wss = [ws, torch.empty_like(ws)] if side is not None else [ws]
+    ev_att = [torch.cuda.Event() for _ in range(layers)]
+    ev_evi = [torch.cuda.Event() for _ in range(layers)]
+    launch_no = [0]
+
+    def run_step(j, probe_layer=-1, probe_events=None):
         tj = t_all[j]
         for l in range(layers):
-            states[l].step(Qs[l][j], Kns[l][j], Vns[l][j], tj, t_first)
+            st = states[l]
+            if l == probe_layer:
+                corm.corm_profile_attend(probe_events[0], probe_events[1])
+            if side is None:
+                st.step(Qs[l][j], Kns[l][j], Vns[l][j], tj, t_first)
+                continue
+            n = launch_no[0]
+            if n >= 2:
+                main.wait_event(ev_evi[(n - 2) % layers] if layers > 1 else ev_evi[0])
+            st.step_attend(Qs[l][j], Kns[l][j], Vns[l][j], tj, stream=main, workspace=wss[n % 2])
+            ev_att[l].record(main)
+            side.wait_event(ev_att[l])
+            st.step_evict(tj, t_first, stream=side, workspace=wss[n % 2])
+            ev_evi[l].record(side)
+            launch_no[0] = n + 1
+
+    def join():
+        if side is not None:
+            main.wait_stream(side)
 
     t0 = time.time()
     for j in range(n_replay):          # prompt tail: seeds the recent-query window; bulk eviction at its end
         run_step(j)
+    join()
     torch.cuda.synchronize()
     log(f"prompt replay ({n_replay} positions) {time.time() - t0:.1f}s; "
         f"live fraction after the prompt {lens_all.float().mean().item() / wl.P:.4f}")
@@ -141,6 +173,7 @@ def main():
     # ---------------- warm-up, then the timed region
     for j in range(n_replay, n_replay + W_steps):
         run_step(j)
+    join()
     lens_hist = torch.empty(K_steps + 1, layers, B, Hkv, dtype=torch.int32, device=dev)
     lens_hist[0].copy_(lens_all)
     # HIP events around the attend kernel of ONE launch per step (layer k mod layers), recorded by the
@@ -151,13 +184,8 @@ def main():
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     ev0.record()
     for k in range(K_steps):
-        j = n_replay + W_steps + k
-        tj = t_all[j]
-        probe = k % layers
-        for l in range(layers):
-            if l == probe:
-                corm.corm_profile_attend(pairs[k][0], pairs[k][1])
-            states[l].step(Qs[l][j], Kns[l][j], Vns[l][j], tj, t_first)
+        run_step(n_replay + W_steps + k, probe_layer=k % layers, probe_events=pairs[k])
+        join()                             # the step ends when both streams have finished it
         lens_hist[k + 1].copy_(lens_all)   # one tiny copy per step: the live lengths the next step starts from
     ev1.record()
     torch.cuda.synchronize()
@@ -188,7 +216,7 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name + ("+structured_queries" if args.structured else ""),
                    "layers": layers, "batch": B, "q_heads": Hq, "kv_heads": Hkv, "head_dim": d,
-                   "prompt": wl.P, "w": wl.w, "r": wl.r, "tokens_per_step": B,
+                   "prompt": wl.P, "w": wl.w, "r": wl.r, "tokens_per_step": B, "streams": args.streams,
                    "live_fraction_end": live_end, "keys_evicted_in_timed_region": evicted},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,

@@ -128,9 +128,9 @@ int corm_evict_mask_summary(const corm_desc* desc, const int32_t* last_hit, cons
 
 /* Stable per-unit compaction (the gather of Algorithm 1), in place: survivors keep their order;
  * K, V, pos, last_hit rows move to slot (number of survivors before them); lens = survivors.
- * kept_idx (may be NULL) receives the old slot of each survivor. */
+ * kept_idx (may be NULL) receives the old slot of each survivor.  Uses the workspace for staging. */
 int corm_compact(const corm_desc* desc, void* K, void* V, int32_t* pos, int32_t* last_hit, int32_t* lens,
-                 const uint8_t* keep, int32_t* kept_idx, void* stream);
+                 const uint8_t* keep, int32_t* kept_idx, void* workspace, size_t workspace_bytes, void* stream);
 
 /* One fused decode step = append, attend, record, evict, compact, in Algorithm 1's order (the
  * current query attends over ALL l keys, eviction takes effect from the next step).  Same bits
@@ -142,7 +142,23 @@ int corm_decode_step(const corm_desc* desc, const void* q, const void* k_new, co
                      uint8_t* keep, int32_t* kept_idx, void* workspace, size_t workspace_bytes,
                      int32_t* status, void* stream);
 
-/* Measurement hook (host call, not thread safe): the NEXT corm_decode_attend / corm_decode_step call
+/* The fused step in two phases, for callers that overlap the bookkeeping with other work (another
+ * layer's attention, the model's GEMMs) on a second stream:
+ *   corm_step_attend  append + attend (Eq. 1, Eq. 2 numerators): reads the cache and lens, writes the new
+ *                     row (K, V, pos, last_hit at slot lens) and the workspace (split partials, logits).
+ *   corm_step_evict   merge -> out; record -> score_ring, last_hit (Def. 3.1); decide (Def. 4.1 + recent r);
+ *                     compact (Algorithm 1's gather) -> K, V, pos, last_hit, lens.
+ * corm_decode_step == corm_step_attend then corm_step_evict on one stream, with the same workspace.
+ * The caller orders: evict after attend of the same step; the next step's attend of the same cache
+ * after evict; no other call may use the workspace between the two phases. */
+int corm_step_attend(const corm_desc* desc, const void* q, const void* k_new, const void* v_new, void* K, void* V,
+                     const int32_t* lens, int32_t* pos, int32_t* last_hit, const int32_t* t, void* workspace,
+                     size_t workspace_bytes, void* stream);
+int corm_step_evict(const corm_desc* desc, void* K, void* V, int32_t* lens, int32_t* pos, int32_t* last_hit,
+                    const int32_t* t, const int32_t* t_first, void* score_ring, float* out, uint8_t* keep,
+                    int32_t* kept_idx, void* workspace, size_t workspace_bytes, int32_t* status, void* stream);
+
+/* Measurement hook (host call, not thread safe): the NEXT corm_decode_attend / corm_step_attend / corm_decode_step call
  * records start_event immediately before and stop_event immediately after its attend launch, on
  * that call's stream, then forgets them.  Both are hipEvent_t handles passed as void*; both NULL
  * cancels.  The attend kernel streams K and V (the step's dominant traffic); this is how its

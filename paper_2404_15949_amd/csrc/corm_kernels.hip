@@ -391,6 +391,7 @@ __global__ __launch_bounds__(WG) void corm_attend_kernel(const Params p) {
 
 template <int G>
 __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const int D) {
+  constexpr int KPT = CHUNK / WG;  // keys per thread
   const int split = blockIdx.x;
   const int unit = blockIdx.y;
   const UnitLen ul = unit_len(p, unit);
@@ -405,9 +406,28 @@ __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const i
   const int hq0 = hkv * G;
   const int lane = tid & 63, wv = tid >> 6;
   const int PSTRIDE = D + 2;
+  const int cbeg = split * CHUNK;
+  const int cend = min(cbeg + CHUNK, L);
 
   __shared__ float sh_M[G], sh_Z[G];
   __shared__ int sh_cnt[WAVES];
+
+  // this thread's keys: issue their loads first, they are consumed after the merge below
+  const int32_t* posb = p.pos + (size_t)unit * p.Lcap;
+  int32_t* lhb = p.last_hit + (size_t)unit * p.Lcap;
+  const float* logit_u = p.logits + (size_t)(b * p.Hq + hq0) * p.Lcap;
+  int my_pos[KPT], my_lh[KPT];
+  float lg[KPT][G];
+#pragma unroll
+  for (int k = 0; k < KPT; ++k) {
+    const int i = min(cbeg + k * WG + tid, max(cend - 1, 0));   // clamped: a live slot (or 0 in an empty unit)
+    my_pos[k] = posb[i];
+    my_lh[k] = lhb[i];
+#pragma unroll
+    for (int g = 0; g < G; ++g) lg[k][g] = logit_u[(size_t)g * p.Lcap + i];
+  }
+  const int tcur = p.t[b];
+  const int tfirst = p.do_evict ? p.t_first[b] : tcur;
 
   // global max and sum of Eq. 2 from the split partials (wave g handles head g, g + WAVES, ...)
   for (int g = wv; g < G; g += WAVES) {
@@ -448,34 +468,28 @@ __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const i
   if (split >= nlive) return;  // an empty unit: nothing to record
 
   // record (Def. 3.1) and decide (Def. 4.1 + recent r) for the keys of this chunk
-  const int tcur = p.t[b];
   const bool step_ok = tcur >= 1 && tcur <= p.Tcap;
   if (!step_ok && split == 0 && tid == 0 && p.status) atomicOr(p.status, CORM_DEV_BAD_STEP);
   const int slot = step_ok ? (tcur - 1) % p.w : 0;
   const float thr = importance_threshold(p.thr_scale, step_ok ? tcur : 1);
-  const bool full = p.do_evict && step_ok && (tcur - p.t_first[b] + 1 >= p.w);
-  const int32_t* posb = p.pos + (size_t)unit * p.Lcap;
-  int32_t* lhb = p.last_hit + (size_t)unit * p.Lcap;
-  const float* logit_u = p.logits + (size_t)(b * p.Hq + hq0) * p.Lcap;
-  uint8_t* keepb = p.keep ? p.keep + (size_t)unit * p.Lcap : nullptr;
+  const bool full = p.do_evict && step_ok && (tcur - tfirst + 1 >= p.w);
+  uint8_t* keepb = p.keep + (size_t)unit * p.Lcap;
 
-  const int cbeg = split * CHUNK;
-  const int cend = min(cbeg + CHUNK, L);
   int kept = 0;
-  for (int i = cbeg + tid; i < cbeg + CHUNK; i += WG) {
+#pragma unroll
+  for (int k = 0; k < KPT; ++k) {
+    const int i = cbeg + k * WG + tid;
     const bool live = i < cend;
     bool keep = false;
     if (live) {
-      const int my_pos = posb[i];
-      int my_lh = lhb[i];
-      const bool pos_ok = my_pos >= 0 && my_pos < p.Tcap;
+      const bool pos_ok = my_pos[k] >= 0 && my_pos[k] < p.Tcap;
       if (!pos_ok && p.status) atomicOr(p.status, CORM_DEV_BAD_STEP);
       bool hit = false;
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        const float sc = exp2f(logit_u[(size_t)g * p.Lcap + i] - sh_M[g]) / sh_Z[g];
+        const float sc = exp2f(lg[k][g] - sh_M[g]) / sh_Z[g];
         float stored;
-        const size_t ri = ((size_t)(b * p.Hq + hq0 + g) * p.w + slot) * p.Tcap + (size_t)my_pos;
+        const size_t ri = ((size_t)(b * p.Hq + hq0 + g) * p.w + slot) * p.Tcap + (size_t)my_pos[k];
         if (p.ring_bf16) {
           const uint16_t hb = f32_to_bf16_rne(sc);
           stored = __uint_as_float((uint32_t)hb << 16);
@@ -486,12 +500,13 @@ __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const i
         }
         hit |= (stored >= thr);
       }
+      int lh = my_lh[k];
       if (hit && step_ok) {
-        my_lh = tcur;
+        lh = tcur;
         lhb[i] = tcur;
       }
-      keep = !full || (my_lh > tcur - p.w) || (i >= L - p.r);
-      if (p.do_evict && keepb) keepb[i] = keep ? 1 : 0;
+      keep = !full || (lh > tcur - p.w) || (i >= L - p.r);
+      if (p.do_evict) keepb[i] = keep ? 1 : 0;
     }
     kept += __popcll(__ballot(keep));
   }
@@ -507,21 +522,53 @@ __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const i
   }
 }
 
-// ---------------------------------------------------------------- stable in-place compaction of one unit
+// ---------------------------------------------------------------- stable in-place compaction
 //
-// One workgroup per unit.  Tiles of WG slots in ascending order; for each tile: keep flags ->
-// exclusive scan (ballot + popcount per wave, LDS across waves, running base across tiles) ->
-// metadata moves -> cooperative row moves of K and V.  Every destination is <= its source and
-// tiles ascend, so a tile's writes only land on slots whose contents were already read; inside a
-// tile all reads complete (explicit wait + barrier) before any write.
+// Survivor number rho of a unit (in slot order) must end in slot rho.  Two launches, no
+// cross-workgroup synchronization inside either:
+//
+//   local     grid (splits, units).  R_c = survivors before chunk c (from the per-split counts).
+//             The workgroup of chunk c = slots [a_c, a_c + CHUNK) moves its survivors with rho >= a_c
+//             to slot rho -- inside its own chunk, so it reads and writes only its own slots -- in
+//             ascending tiles (every destination <= its source; inside a tile all loads complete
+//             before any store).  Its first survivors, those with rho < a_c ("boundary rows", at most
+//             as many as keys were evicted before the chunk), belong in the tail of earlier chunks,
+//             whose owners may not have read those slots yet: they go to a staging area instead.
+//   boundary  grid (units).  Copies the staged rows to slots [R_c, min(a_c, R_{c+1})): slots no local
+//             workgroup writes, and whose old contents were consumed in the previous launch.  Writes
+//             lens (nobody reads lens of this step after it).
+//
+// The staging area holds STAGE_ROWS rows per chunk.  A unit that lost more than STAGE_ROWS keys in
+// one step (the bulk eviction at the end of a prompt) is compacted by the workgroup of its chunk 0
+// alone, walking the whole unit in ascending tiles.
+
+constexpr int STAGE_ROWS = 16;
 
 struct CompactShared {
   int32_t wave_count[WAVES];
   int32_t src_of[WG];
 };
 
+struct CompactArgs {
+  char* K;
+  char* V;
+  int32_t* pos;
+  int32_t* last_hit;
+  int32_t* lens;
+  const uint8_t* keep;
+  int32_t* kept_idx;        // optional
+  const int32_t* counts;    // [units, nsplit]
+  char* stage_k;            // [units, nsplit, STAGE_ROWS, ROWB]
+  char* stage_v;
+  int32_t* stage_meta;      // [units, nsplit, STAGE_ROWS, 2] (pos, last_hit)
+  int32_t nsplit, Lcap, do_append;
+};
+
+// Moves the n_rows survivors listed in src_of (ascending) to consecutive destinations starting at
+// survivor number rho0: slot rho if rho >= own_begin, else staging row (rho - stage_rho0).
 template <int ROWB>
-__device__ __forceinline__ void move_rows(char* Kb, char* Vb, const int32_t* src_of, int n_rows, int dst_base) {
+__device__ __forceinline__ void move_rows(char* Kb, char* Vb, char* sk, char* sv, const int32_t* src_of, int n_rows,
+                                          int rho0, int own_begin, int stage_rho0) {
   constexpr int LPR = ROWB / 16;
   constexpr int RPP = WG / LPR;  // rows per pass of the workgroup
   const int tid = threadIdx.x;
@@ -546,26 +593,24 @@ __device__ __forceinline__ void move_rows(char* Kb, char* Vb, const int32_t* src
     const uint4 v3 = *reinterpret_cast<const uint4*>(Vb + o3);
     wait_vm_loads();
     __syncthreads();
-    if (j0 < n_rows) {
-      const size_t d = (size_t)(dst_base + j0) * ROWB + col;
-      *reinterpret_cast<uint4*>(Kb + d) = k0;
-      *reinterpret_cast<uint4*>(Vb + d) = v0;
+#define CORM_STORE_ROW(J, KR, VR)                                              \
+    if ((J) < n_rows) {                                                          \
+      const int rho = rho0 + (J);                                                \
+      if (rho >= own_begin) {                                                    \
+        const size_t d = (size_t)rho * ROWB + col;                               \
+        *reinterpret_cast<uint4*>(Kb + d) = (KR);                                \
+        *reinterpret_cast<uint4*>(Vb + d) = (VR);                                \
+      } else {                                                                   \
+        const size_t d = (size_t)(rho - stage_rho0) * ROWB + col;                \
+        *reinterpret_cast<uint4*>(sk + d) = (KR);                                \
+        *reinterpret_cast<uint4*>(sv + d) = (VR);                                \
+      }                                                                          \
     }
-    if (j1 < n_rows) {
-      const size_t d = (size_t)(dst_base + j1) * ROWB + col;
-      *reinterpret_cast<uint4*>(Kb + d) = k1;
-      *reinterpret_cast<uint4*>(Vb + d) = v1;
-    }
-    if (j2 < n_rows) {
-      const size_t d = (size_t)(dst_base + j2) * ROWB + col;
-      *reinterpret_cast<uint4*>(Kb + d) = k2;
-      *reinterpret_cast<uint4*>(Vb + d) = v2;
-    }
-    if (j3 < n_rows) {
-      const size_t d = (size_t)(dst_base + j3) * ROWB + col;
-      *reinterpret_cast<uint4*>(Kb + d) = k3;
-      *reinterpret_cast<uint4*>(Vb + d) = v3;
-    }
+    CORM_STORE_ROW(j0, k0, v0)
+    CORM_STORE_ROW(j1, k1, v1)
+    CORM_STORE_ROW(j2, k2, v2)
+    CORM_STORE_ROW(j3, k3, v3)
+#undef CORM_STORE_ROW
   }
 }
 
@@ -588,41 +633,83 @@ __device__ __forceinline__ int tile_scan(bool keep, CompactShared& sh, int* tile
   return before + rank;
 }
 
-// counts != nullptr: the record kernel's per-split survivor counts allow an early exit when the
-// unit lost nothing.  do_append: lens still holds the length before the step's append.
-template <int ROWB>
-__global__ __launch_bounds__(WG) void corm_compact_kernel(char* K, char* V, int32_t* pos, int32_t* last_hit,
-                                                          int32_t* lens, const uint8_t* keep, int32_t* kept_idx,
-                                                          const int32_t* counts, int nsplit, int Lcap,
-                                                          int do_append) {
-  __shared__ CompactShared sh_c;
-  const int unit = blockIdx.x;
-  const int tid = threadIdx.x;
-  int L = lens[unit];
-  L = L < 0 ? 0 : (L > Lcap ? Lcap : L);
-  if (do_append && L < Lcap) L += 1;
-  int32_t* idxb = kept_idx ? kept_idx + (size_t)unit * Lcap : nullptr;
-  if (counts) {
-    const int nlive = (L + CHUNK - 1) / CHUNK;
+__device__ __forceinline__ int compact_unit_len(const CompactArgs& a, int unit) {
+  int L = a.lens[unit];
+  L = L < 0 ? 0 : (L > a.Lcap ? a.Lcap : L);
+  if (a.do_append && L < a.Lcap) L += 1;
+  return L;
+}
+
+// survivors per split -> keep-flag counts, for callers that come with a mask only (corm_compact)
+__global__ __launch_bounds__(WG) void corm_count_kernel(const CompactArgs a, int32_t* counts) {
+  __shared__ int sh_cnt[WAVES];
+  const int split = blockIdx.x, unit = blockIdx.y;
+  const int L = compact_unit_len(a, unit);
+  const int cbeg = split * CHUNK;
+  if (cbeg >= L) return;
+  const int cend = min(cbeg + CHUNK, L);
+  const uint8_t* keepb = a.keep + (size_t)unit * a.Lcap;
+  int kept = 0;
+  for (int i = cbeg + threadIdx.x; i < cbeg + CHUNK; i += WG) kept += __popcll(__ballot(i < cend && keepb[i] != 0));
+  if ((threadIdx.x & 63) == 0) sh_cnt[threadIdx.x >> 6] = kept;
+  __syncthreads();
+  if (threadIdx.x == 0) {
     int tot = 0;
-    for (int s = 0; s < nlive; ++s) tot += counts[(size_t)unit * nsplit + s];
-    if (tot == L) {  // nothing evicted: the cache is already compact
-      if (idxb)
-        for (int i = tid; i < L; i += WG) idxb[i] = i;
-      if (tid == 0) lens[unit] = L;
-      return;
-    }
+#pragma unroll
+    for (int i = 0; i < WAVES; ++i) tot += sh_cnt[i];
+    counts[(size_t)unit * a.nsplit + split] = tot;
   }
-  char* Kb = K + (size_t)unit * Lcap * ROWB;
-  char* Vb = V + (size_t)unit * Lcap * ROWB;
-  int32_t* posb = pos + (size_t)unit * Lcap;
-  int32_t* lhb = last_hit + (size_t)unit * Lcap;
-  const uint8_t* keepb = keep + (size_t)unit * Lcap;
-  int dst_base = 0;
-  for (int tile = 0; tile < L; tile += WG) {
+}
+
+template <int ROWB>
+__global__ __launch_bounds__(WG) void corm_compact_local_kernel(const CompactArgs a) {
+  __shared__ CompactShared sh_c;
+  const int split = blockIdx.x, unit = blockIdx.y;
+  const int tid = threadIdx.x;
+  const int L = compact_unit_len(a, unit);
+  const int nlive = (L + CHUNK - 1) / CHUNK;
+  if (split >= nlive) return;
+  const int32_t* cnt = a.counts + (size_t)unit * a.nsplit;
+  int R = 0, T = 0;   // survivors before this chunk, survivors of the unit
+  for (int s = 0; s < nlive; ++s) {
+    const int c = cnt[s];
+    if (s < split) R += c;
+    T += c;
+  }
+  int32_t* idxb = a.kept_idx ? a.kept_idx + (size_t)unit * a.Lcap : nullptr;
+  int cbeg = split * CHUNK;
+  int cend = min(cbeg + CHUNK, L);
+  if (T == L) {   // nothing evicted: the cache is already compact
+    if (idxb)
+      for (int i = cbeg + tid; i < cend; i += WG) idxb[i] = i;
+    return;
+  }
+  const bool serial = (L - T) > STAGE_ROWS;   // too many holes for the staging area: chunk 0 walks the unit
+  int own_begin = cbeg;
+  if (serial) {
+    if (split != 0) return;
+    cend = L;
+    own_begin = 0;
+  }
+  if (R == cbeg && cnt[split] == cend - cbeg && !serial) {   // no hole before or inside this chunk
+    if (idxb)
+      for (int i = cbeg + tid; i < cend; i += WG) idxb[i] = i;
+    return;
+  }
+  char* Kb = a.K + (size_t)unit * a.Lcap * ROWB;
+  char* Vb = a.V + (size_t)unit * a.Lcap * ROWB;
+  int32_t* posb = a.pos + (size_t)unit * a.Lcap;
+  int32_t* lhb = a.last_hit + (size_t)unit * a.Lcap;
+  const uint8_t* keepb = a.keep + (size_t)unit * a.Lcap;
+  const size_t stage_row0 = ((size_t)unit * a.nsplit + split) * STAGE_ROWS;
+  char* sk = a.stage_k + stage_row0 * ROWB;
+  char* sv = a.stage_v + stage_row0 * ROWB;
+  int32_t* sm = a.stage_meta + stage_row0 * 2;
+
+  int rho_base = R;  // survivor number of the first survivor of the current tile
+  for (int tile = cbeg; tile < cend; tile += WG) {
     const int i = tile + tid;
-    const bool live = i < L;
-    const bool kp = live && keepb[i] != 0;
+    const bool kp = i < cend && keepb[i] != 0;
     int my_pos = 0, my_lh = 0;
     if (kp) {
       my_pos = posb[i];
@@ -631,22 +718,68 @@ __global__ __launch_bounds__(WG) void corm_compact_kernel(char* K, char* V, int3
     wait_vm_loads();
     int tile_kept;
     const int rank = tile_scan(kp, sh_c, &tile_kept);
-    const int dst = dst_base + rank;
+    const int rho = rho_base + rank;
     if (kp) {
       sh_c.src_of[rank] = i;
-      if (idxb) idxb[dst] = i;
-      if (dst != i) {
-        posb[dst] = my_pos;
-        lhb[dst] = my_lh;
+      if (idxb) idxb[rho] = i;
+      if (rho >= own_begin) {
+        if (rho != i) {
+          posb[rho] = my_pos;
+          lhb[rho] = my_lh;
+        }
+      } else {
+        sm[(rho - R) * 2] = my_pos;
+        sm[(rho - R) * 2 + 1] = my_lh;
       }
     }
     __syncthreads();
-    const int tile_n = min(WG, L - tile);
-    if (!(dst_base == tile && tile_kept == tile_n)) move_rows<ROWB>(Kb, Vb, sh_c.src_of, tile_kept, dst_base);
-    dst_base += tile_kept;
+    const int tile_n = min(WG, cend - tile);
+    if (!(rho_base == tile && tile_kept == tile_n))
+      move_rows<ROWB>(Kb, Vb, sk, sv, sh_c.src_of, tile_kept, rho_base, own_begin, R);
+    rho_base += tile_kept;
     __syncthreads();
   }
-  if (tid == 0) lens[unit] = dst_base;
+}
+
+template <int ROWB>
+__global__ __launch_bounds__(WG) void corm_compact_boundary_kernel(const CompactArgs a) {
+  constexpr int LPR = ROWB / 16;
+  const int unit = blockIdx.x;
+  const int tid = threadIdx.x;
+  const int L = compact_unit_len(a, unit);
+  const int nlive = (L + CHUNK - 1) / CHUNK;
+  const int32_t* cnt = a.counts + (size_t)unit * a.nsplit;
+  int T = 0;
+  for (int s = 0; s < nlive; ++s) T += cnt[s];
+  if (T < L && (L - T) <= STAGE_ROWS) {
+    char* Kb = a.K + (size_t)unit * a.Lcap * ROWB;
+    char* Vb = a.V + (size_t)unit * a.Lcap * ROWB;
+    int32_t* posb = a.pos + (size_t)unit * a.Lcap;
+    int32_t* lhb = a.last_hit + (size_t)unit * a.Lcap;
+    // thread -> (row j of the chunk's staging area, 16-byte column): STAGE_ROWS * LPR threads per chunk
+    const int j = tid / LPR;
+    const size_t col = (size_t)(tid % LPR) * 16;
+    int R = cnt[0];
+    for (int c = 1; c < nlive; ++c) {
+      const int Rn = R + cnt[c];
+      const int nb = min(c * CHUNK, Rn) - R;   // boundary rows of chunk c: survivor numbers [R, R + nb)
+      if (nb > 0) {
+        const size_t stage_row0 = ((size_t)unit * a.nsplit + c) * STAGE_ROWS;
+        for (int jj = j; jj < nb; jj += WG / LPR) {
+          const size_t s = (stage_row0 + jj) * ROWB + col;
+          const size_t d = (size_t)(R + jj) * ROWB + col;
+          *reinterpret_cast<uint4*>(Kb + d) = *reinterpret_cast<const uint4*>(a.stage_k + s);
+          *reinterpret_cast<uint4*>(Vb + d) = *reinterpret_cast<const uint4*>(a.stage_v + s);
+        }
+        if (tid < nb) {
+          posb[R + tid] = a.stage_meta[(stage_row0 + tid) * 2];
+          lhb[R + tid] = a.stage_meta[(stage_row0 + tid) * 2 + 1];
+        }
+      }
+      R = Rn;
+    }
+  }
+  if (tid == 0) a.lens[unit] = T;
 }
 
 // ---------------------------------------------------------------- standalone kernels
@@ -739,21 +872,27 @@ __global__ void corm_fill_i32_kernel(int32_t* p, size_t n, int32_t v) {
 // ---------------------------------------------------------------- host side
 
 struct WorkspaceLayout {
-  size_t counts_off, keep_off, partials_off, logits_off, total;
+  size_t counts_off, keep_off, partials_off, logits_off, stage_meta_off, stage_k_off, stage_v_off, total;
   int nsplit;
 };
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+int row_bytes(const corm_desc* d) { return d->d * (d->kv_dtype == CORM_F32 ? 4 : 2); }
+
 WorkspaceLayout workspace_layout(const corm_desc& d) {
   WorkspaceLayout w;
   w.nsplit = (d.Lcap + CHUNK - 1) / CHUNK;
   const size_t units = (size_t)d.B * d.Hkv, heads = (size_t)d.B * d.Hq;
+  const size_t stage_rows = units * w.nsplit * STAGE_ROWS;
   w.counts_off = 0;
   w.keep_off = align_up(units * w.nsplit * sizeof(int32_t), 256);
   w.partials_off = align_up(w.keep_off + units * d.Lcap, 256);
   w.logits_off = align_up(w.partials_off + heads * w.nsplit * (d.d + 2) * sizeof(float), 256);
-  w.total = align_up(w.logits_off + heads * d.Lcap * sizeof(float), 256);
+  w.stage_meta_off = align_up(w.logits_off + heads * d.Lcap * sizeof(float), 256);
+  w.stage_k_off = align_up(w.stage_meta_off + stage_rows * 2 * sizeof(int32_t), 256);
+  w.stage_v_off = align_up(w.stage_k_off + stage_rows * row_bytes(&d), 256);
+  w.total = align_up(w.stage_v_off + stage_rows * row_bytes(&d), 256);
   return w;
 }
 
@@ -776,12 +915,32 @@ int validate_desc(const corm_desc* d) {
 bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 bool misaligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) != 0; }
 
-int row_bytes(const corm_desc* d) { return d->d * (d->kv_dtype == CORM_F32 ? 4 : 2); }
-
 int launch_status() { return hipGetLastError() == hipSuccess ? CORM_OK : CORM_EHIP; }
 
 // optional events recorded around the attend launch of the next step call (corm_profile_attend)
 hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
+
+int check_workspace(const corm_desc* d, void* workspace, size_t workspace_bytes, WorkspaceLayout* wl) {
+  *wl = workspace_layout(*d);
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return CORM_EINVAL;
+  if (workspace_bytes < wl->total) return CORM_ECAPACITY;
+  return CORM_OK;
+}
+
+// fills the descriptor- and workspace-derived fields of p
+void bind_params(const corm_desc* d, const WorkspaceLayout& wl, void* workspace, Params& p) {
+  char* ws = reinterpret_cast<char*>(workspace);
+  p.counts = reinterpret_cast<int32_t*>(ws + wl.counts_off);
+  if (!p.keep) p.keep = reinterpret_cast<uint8_t*>(ws + wl.keep_off);
+  p.partials = reinterpret_cast<float*>(ws + wl.partials_off);
+  p.logits = reinterpret_cast<float*>(ws + wl.logits_off);
+  p.B = d->B; p.Hq = d->Hq; p.Hkv = d->Hkv; p.Lcap = d->Lcap; p.Tcap = d->Tcap; p.w = d->w; p.r = d->r;
+  p.nsplit = wl.nsplit;
+  p.thr_scale = d->thr_scale;
+  const float sm = d->sm_scale > 0.f ? d->sm_scale : 1.0f / sqrtf((float)d->d);
+  p.scale_log2 = sm * LOG2E;
+  p.ring_bf16 = d->score_dtype == CORM_BF16;
+}
 
 template <typename DT, int D>
 int launch_attend_g(const Params& p, int G, dim3 grid, hipStream_t s) {
@@ -795,52 +954,13 @@ int launch_attend_g(const Params& p, int G, dim3 grid, hipStream_t s) {
   return launch_status();
 }
 
-int launch_record(const Params& p, int G, int D, dim3 grid, hipStream_t s) {
-  switch (G) {
-    case 1: hipLaunchKernelGGL((corm_record_kernel<1>), grid, dim3(WG), 0, s, p, D); break;
-    case 2: hipLaunchKernelGGL((corm_record_kernel<2>), grid, dim3(WG), 0, s, p, D); break;
-    case 4: hipLaunchKernelGGL((corm_record_kernel<4>), grid, dim3(WG), 0, s, p, D); break;
-    case 8: hipLaunchKernelGGL((corm_record_kernel<8>), grid, dim3(WG), 0, s, p, D); break;
-    default: return CORM_EUNSUPPORTED;
-  }
-  return launch_status();
-}
-
-int launch_compact(const corm_desc* d, char* K, char* V, int32_t* pos, int32_t* last_hit, int32_t* lens,
-                   const uint8_t* keep, int32_t* kept_idx, const int32_t* counts, int nsplit, int do_append,
-                   hipStream_t s) {
-  dim3 grid(d->B * d->Hkv);
-  switch (row_bytes(d)) {
-    case 128: hipLaunchKernelGGL((corm_compact_kernel<128>), grid, dim3(WG), 0, s, K, V, pos, last_hit, lens, keep, kept_idx, counts, nsplit, d->Lcap, do_append); break;
-    case 256: hipLaunchKernelGGL((corm_compact_kernel<256>), grid, dim3(WG), 0, s, K, V, pos, last_hit, lens, keep, kept_idx, counts, nsplit, d->Lcap, do_append); break;
-    case 512: hipLaunchKernelGGL((corm_compact_kernel<512>), grid, dim3(WG), 0, s, K, V, pos, last_hit, lens, keep, kept_idx, counts, nsplit, d->Lcap, do_append); break;
-    default: return CORM_EUNSUPPORTED;
-  }
-  return launch_status();
-}
-
-// attend + record (+ compact when evicting), all on stream s
-int launch_step(const corm_desc* d, Params& p, void* workspace, size_t workspace_bytes, hipStream_t s) {
-  const WorkspaceLayout wl = workspace_layout(*d);
-  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return CORM_EINVAL;
-  if (workspace_bytes < wl.total) return CORM_ECAPACITY;
-  char* ws = reinterpret_cast<char*>(workspace);
-  p.counts = reinterpret_cast<int32_t*>(ws + wl.counts_off);
-  if (!p.keep) p.keep = reinterpret_cast<uint8_t*>(ws + wl.keep_off);
-  p.partials = reinterpret_cast<float*>(ws + wl.partials_off);
-  p.logits = reinterpret_cast<float*>(ws + wl.logits_off);
-  p.B = d->B; p.Hq = d->Hq; p.Hkv = d->Hkv; p.Lcap = d->Lcap; p.Tcap = d->Tcap; p.w = d->w; p.r = d->r;
-  p.nsplit = wl.nsplit;
-  p.thr_scale = d->thr_scale;
-  const float sm = d->sm_scale > 0.f ? d->sm_scale : 1.0f / sqrtf((float)d->d);
-  p.scale_log2 = sm * LOG2E;
-  p.ring_bf16 = d->score_dtype == CORM_BF16;
+int launch_attend(const corm_desc* d, const Params& p, hipStream_t s) {
   const int G = d->Hq / d->Hkv;
-  const dim3 grid(wl.nsplit, d->B * d->Hkv);
-  int rc;
+  const dim3 grid(p.nsplit, d->B * d->Hkv);
   const hipEvent_t ev0 = g_prof_start, ev1 = g_prof_stop;
   g_prof_start = g_prof_stop = nullptr;
   if (ev0 && hipEventRecord(ev0, s) != hipSuccess) return CORM_EHIP;
+  int rc;
   if (d->kv_dtype == CORM_F32) {
     rc = d->d == 64 ? launch_attend_g<F32, 64>(p, G, grid, s) : launch_attend_g<F32, 128>(p, G, grid, s);
   } else {
@@ -848,10 +968,73 @@ int launch_step(const corm_desc* d, Params& p, void* workspace, size_t workspace
   }
   if (rc) return rc;
   if (ev1 && hipEventRecord(ev1, s) != hipSuccess) return CORM_EHIP;
-  rc = launch_record(p, G, d->d, grid, s);
-  if (rc || !p.do_evict) return rc;
-  return launch_compact(d, reinterpret_cast<char*>(p.K), reinterpret_cast<char*>(p.V), p.pos, p.last_hit, p.lens,
-                        p.keep, p.kept_idx, p.counts, wl.nsplit, p.do_append, s);
+  return CORM_OK;
+}
+
+int launch_record(const corm_desc* d, const Params& p, hipStream_t s) {
+  const int G = d->Hq / d->Hkv;
+  const dim3 grid(p.nsplit, d->B * d->Hkv);
+  switch (G) {
+    case 1: hipLaunchKernelGGL((corm_record_kernel<1>), grid, dim3(WG), 0, s, p, d->d); break;
+    case 2: hipLaunchKernelGGL((corm_record_kernel<2>), grid, dim3(WG), 0, s, p, d->d); break;
+    case 4: hipLaunchKernelGGL((corm_record_kernel<4>), grid, dim3(WG), 0, s, p, d->d); break;
+    case 8: hipLaunchKernelGGL((corm_record_kernel<8>), grid, dim3(WG), 0, s, p, d->d); break;
+    default: return CORM_EUNSUPPORTED;
+  }
+  return launch_status();
+}
+
+// local + boundary launches of the compaction; count_first: derive the per-split counts from the mask
+int launch_compact(const corm_desc* d, const WorkspaceLayout& wl, void* workspace, void* K, void* V, int32_t* pos,
+                   int32_t* last_hit, int32_t* lens, const uint8_t* keep, int32_t* kept_idx, int do_append,
+                   bool count_first, hipStream_t s) {
+  char* ws = reinterpret_cast<char*>(workspace);
+  CompactArgs a;
+  a.K = reinterpret_cast<char*>(K);
+  a.V = reinterpret_cast<char*>(V);
+  a.pos = pos; a.last_hit = last_hit; a.lens = lens; a.keep = keep; a.kept_idx = kept_idx;
+  int32_t* counts = reinterpret_cast<int32_t*>(ws + wl.counts_off);
+  a.counts = counts;
+  a.stage_k = ws + wl.stage_k_off;
+  a.stage_v = ws + wl.stage_v_off;
+  a.stage_meta = reinterpret_cast<int32_t*>(ws + wl.stage_meta_off);
+  a.nsplit = wl.nsplit; a.Lcap = d->Lcap; a.do_append = do_append;
+  const dim3 grid2(wl.nsplit, d->B * d->Hkv), grid1(d->B * d->Hkv);
+  if (count_first) {
+    hipLaunchKernelGGL(corm_count_kernel, grid2, dim3(WG), 0, s, a, counts);
+    if (launch_status()) return CORM_EHIP;
+  }
+  switch (row_bytes(d)) {
+    case 128:
+      hipLaunchKernelGGL((corm_compact_local_kernel<128>), grid2, dim3(WG), 0, s, a);
+      hipLaunchKernelGGL((corm_compact_boundary_kernel<128>), grid1, dim3(WG), 0, s, a);
+      break;
+    case 256:
+      hipLaunchKernelGGL((corm_compact_local_kernel<256>), grid2, dim3(WG), 0, s, a);
+      hipLaunchKernelGGL((corm_compact_boundary_kernel<256>), grid1, dim3(WG), 0, s, a);
+      break;
+    case 512:
+      hipLaunchKernelGGL((corm_compact_local_kernel<512>), grid2, dim3(WG), 0, s, a);
+      hipLaunchKernelGGL((corm_compact_boundary_kernel<512>), grid1, dim3(WG), 0, s, a);
+      break;
+    default: return CORM_EUNSUPPORTED;
+  }
+  return launch_status();
+}
+
+int check_step_pointers(const void* q, const void* k_new, const void* v_new, const void* K, const void* V,
+                        const int32_t* lens, const int32_t* pos, const int32_t* last_hit, const int32_t* t,
+                        const int32_t* t_first, const void* score_ring, const float* out, const int32_t* kept_idx,
+                        const int32_t* status) {
+  if (!q || !k_new || !v_new || !K || !V || !lens || !pos || !last_hit || !t || !t_first || !score_ring || !out)
+    return CORM_EINVAL;
+  if (misaligned16(q) || misaligned16(k_new) || misaligned16(v_new) || misaligned16(K) || misaligned16(V) ||
+      misaligned4(out) || misaligned4(score_ring))
+    return CORM_EINVAL;
+  if (misaligned4(lens) || misaligned4(pos) || misaligned4(last_hit) || misaligned4(t) || misaligned4(t_first) ||
+      misaligned4(kept_idx) || misaligned4(status))
+    return CORM_EINVAL;
+  return CORM_OK;
 }
 
 }  // namespace
@@ -913,18 +1096,21 @@ int corm_decode_attend(const corm_desc* desc, const void* q, const void* K, cons
                        void* workspace, size_t workspace_bytes, int32_t* status, void* stream) {
   int rc = validate_desc(desc);
   if (rc) return rc;
-  if (!q || !K || !V || !lens || !pos || !t || !score_ring || !last_hit || !out) return CORM_EINVAL;
-  if (misaligned16(q) || misaligned16(K) || misaligned16(V) || misaligned4(out) || misaligned4(score_ring))
-    return CORM_EINVAL;
-  if (misaligned4(lens) || misaligned4(pos) || misaligned4(last_hit) || misaligned4(t) || misaligned4(status))
-    return CORM_EINVAL;
+  rc = check_step_pointers(q, K, V, K, V, lens, pos, last_hit, t, t, score_ring, out, nullptr, status);
+  if (rc) return rc;
+  WorkspaceLayout wl;
+  rc = check_workspace(desc, workspace, workspace_bytes, &wl);
+  if (rc) return rc;
   Params p = {};
-  p.q = q; p.k_new = K; p.v_new = V;  // k_new/v_new unused without append; kept non-null
+  p.q = q; p.k_new = K; p.v_new = V;  // k_new/v_new are not read without an append; kept non-null
   p.K = const_cast<void*>(K); p.V = const_cast<void*>(V);
   p.lens = const_cast<int32_t*>(lens); p.pos = const_cast<int32_t*>(pos); p.last_hit = last_hit;
   p.t = t; p.t_first = t; p.ring = score_ring; p.out = out; p.status = status;
   p.do_append = 0; p.do_evict = 0;
-  return launch_step(desc, p, workspace, workspace_bytes, (hipStream_t)stream);
+  bind_params(desc, wl, workspace, p);
+  rc = launch_attend(desc, p, (hipStream_t)stream);
+  if (rc) return rc;
+  return launch_record(desc, p, (hipStream_t)stream);
 }
 
 int corm_evict_mask(const corm_desc* desc, const void* score_ring, const int32_t* lens, const int32_t* pos,
@@ -954,15 +1140,58 @@ int corm_evict_mask_summary(const corm_desc* desc, const int32_t* last_hit, cons
 }
 
 int corm_compact(const corm_desc* desc, void* K, void* V, int32_t* pos, int32_t* last_hit, int32_t* lens,
-                 const uint8_t* keep, int32_t* kept_idx, void* stream) {
+                 const uint8_t* keep, int32_t* kept_idx, void* workspace, size_t workspace_bytes, void* stream) {
   int rc = validate_desc(desc);
   if (rc) return rc;
   if (!K || !V || !pos || !last_hit || !lens || !keep) return CORM_EINVAL;
   if (misaligned16(K) || misaligned16(V) || misaligned4(pos) || misaligned4(last_hit) || misaligned4(lens) ||
       misaligned4(kept_idx))
     return CORM_EINVAL;
-  return launch_compact(desc, reinterpret_cast<char*>(K), reinterpret_cast<char*>(V), pos, last_hit, lens, keep,
-                        kept_idx, nullptr, 0, 0, (hipStream_t)stream);
+  WorkspaceLayout wl;
+  rc = check_workspace(desc, workspace, workspace_bytes, &wl);
+  if (rc) return rc;
+  return launch_compact(desc, wl, workspace, K, V, pos, last_hit, lens, keep, kept_idx, 0, true,
+                        (hipStream_t)stream);
+}
+
+int corm_step_attend(const corm_desc* desc, const void* q, const void* k_new, const void* v_new, void* K, void* V,
+                     const int32_t* lens, int32_t* pos, int32_t* last_hit, const int32_t* t, void* workspace,
+                     size_t workspace_bytes, void* stream) {
+  int rc = validate_desc(desc);
+  if (rc) return rc;
+  rc = check_step_pointers(q, k_new, v_new, K, V, lens, pos, last_hit, t, t, K, reinterpret_cast<const float*>(K),
+                           nullptr, nullptr);
+  if (rc) return rc;
+  WorkspaceLayout wl;
+  rc = check_workspace(desc, workspace, workspace_bytes, &wl);
+  if (rc) return rc;
+  Params p = {};
+  p.q = q; p.k_new = k_new; p.v_new = v_new; p.K = K; p.V = V; p.lens = const_cast<int32_t*>(lens); p.pos = pos;
+  p.last_hit = last_hit; p.t = t; p.t_first = t;
+  p.do_append = 1; p.do_evict = 1;
+  bind_params(desc, wl, workspace, p);
+  return launch_attend(desc, p, (hipStream_t)stream);
+}
+
+int corm_step_evict(const corm_desc* desc, void* K, void* V, int32_t* lens, int32_t* pos, int32_t* last_hit,
+                    const int32_t* t, const int32_t* t_first, void* score_ring, float* out, uint8_t* keep,
+                    int32_t* kept_idx, void* workspace, size_t workspace_bytes, int32_t* status, void* stream) {
+  int rc = validate_desc(desc);
+  if (rc) return rc;
+  rc = check_step_pointers(K, K, V, K, V, lens, pos, last_hit, t, t_first, score_ring, out, kept_idx, status);
+  if (rc) return rc;
+  WorkspaceLayout wl;
+  rc = check_workspace(desc, workspace, workspace_bytes, &wl);
+  if (rc) return rc;
+  Params p = {};
+  p.K = K; p.V = V; p.lens = lens; p.pos = pos; p.last_hit = last_hit; p.t = t; p.t_first = t_first;
+  p.ring = score_ring; p.out = out; p.keep = keep; p.kept_idx = kept_idx; p.status = status;
+  p.do_append = 1; p.do_evict = 1;
+  bind_params(desc, wl, workspace, p);
+  rc = launch_record(desc, p, (hipStream_t)stream);
+  if (rc) return rc;
+  return launch_compact(desc, wl, workspace, K, V, pos, last_hit, lens, p.keep, kept_idx, 1, false,
+                        (hipStream_t)stream);
 }
 
 int corm_decode_step(const corm_desc* desc, const void* q, const void* k_new, const void* v_new, void* K, void* V,
@@ -971,20 +1200,12 @@ int corm_decode_step(const corm_desc* desc, const void* q, const void* k_new, co
                      size_t workspace_bytes, int32_t* status, void* stream) {
   int rc = validate_desc(desc);
   if (rc) return rc;
-  if (!q || !k_new || !v_new || !K || !V || !lens || !pos || !last_hit || !t || !t_first || !score_ring || !out)
-    return CORM_EINVAL;
-  if (misaligned16(q) || misaligned16(k_new) || misaligned16(v_new) || misaligned16(K) || misaligned16(V) ||
-      misaligned4(out) || misaligned4(score_ring))
-    return CORM_EINVAL;
-  if (misaligned4(lens) || misaligned4(pos) || misaligned4(last_hit) || misaligned4(t) || misaligned4(t_first) ||
-      misaligned4(kept_idx) || misaligned4(status))
-    return CORM_EINVAL;
-  Params p = {};
-  p.q = q; p.k_new = k_new; p.v_new = v_new; p.K = K; p.V = V; p.lens = lens; p.pos = pos; p.last_hit = last_hit;
-  p.t = t; p.t_first = t_first; p.ring = score_ring; p.out = out; p.keep = keep; p.kept_idx = kept_idx;
-  p.status = status;
-  p.do_append = 1; p.do_evict = 1;
-  return launch_step(desc, p, workspace, workspace_bytes, (hipStream_t)stream);
+  rc = check_step_pointers(q, k_new, v_new, K, V, lens, pos, last_hit, t, t_first, score_ring, out, kept_idx, status);
+  if (rc) return rc;
+  rc = corm_step_attend(desc, q, k_new, v_new, K, V, lens, pos, last_hit, t, workspace, workspace_bytes, stream);
+  if (rc) return rc;
+  return corm_step_evict(desc, K, V, lens, pos, last_hit, t, t_first, score_ring, out, keep, kept_idx, workspace,
+                         workspace_bytes, status, stream);
 }
 
 int corm_profile_attend(void* start_event, void* stop_event) {

@@ -113,7 +113,7 @@ def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_sca
             for (b, h) in units:
                 lb = int(lens_before[b, h])
                 assert torch.equal(keep_lit[b, h, :lb], st.keep[b, h, :lb]), ("literal vs summary mask", j, b, h)
-            corm.corm_compact(st.desc, st.K, st.V, st.pos, st.last_hit, st.lens, st.keep, st.kept_idx)
+            corm.corm_compact(st.desc, st.K, st.V, st.pos, st.last_hit, st.lens, st.keep, st.kept_idx, st.workspace)
         else:
             st.step(q, k, v, t_dev, t_first)
         torch.cuda.synchronize()

@@ -44,8 +44,10 @@ def test_workspace_size_formula():
     n = corm.corm_workspace_bytes(d)
     nsplit = (1024 + 511) // 512
     units, heads = 2 * 2, 2 * 8
-    need = units * nsplit * 4 + units * 1024 + heads * nsplit * 130 * 4 + heads * 1024 * 4
-    assert need <= n <= need + 4 * 256
+    stage_rows = units * nsplit * 16
+    need = (units * nsplit * 4 + units * 1024 + heads * nsplit * 130 * 4 + heads * 1024 * 4
+            + stage_rows * (8 + 2 * 256))
+    assert need <= n <= need + 7 * 256
 
 
 @pytest.mark.parametrize("kw,code", [
@@ -85,7 +87,10 @@ def test_null_and_misaligned_pointers_are_rejected_on_the_host():
     assert rc == corm.CORM_ECAPACITY
     rc = corm.corm_decode_step(d, *[args[k] for k in order], workspace=None, workspace_bytes=0, check=False)
     assert rc == corm.CORM_EINVAL
-    assert corm.corm_compact(d, None, a, a, a, a, a, check=False) == corm.CORM_EINVAL
+    assert corm.corm_compact(d, None, a, a, a, a, a, workspace=a, workspace_bytes=1 << 30, check=False) == corm.CORM_EINVAL
+    assert corm.corm_compact(d, a, a, a, a, a, a, workspace=a, workspace_bytes=8, check=False) == corm.CORM_ECAPACITY
+    assert corm.corm_step_attend(d, a, a, a, a, a, a, a, a, None, a, 1 << 30, check=False) == corm.CORM_EINVAL
+    assert corm.corm_step_evict(d, a, a, a, a, a, a, a, a, None, workspace=a, workspace_bytes=1 << 30, check=False) == corm.CORM_EINVAL
     assert corm.corm_evict_mask(d, a, a, a, a, None, a, check=False) == corm.CORM_EINVAL
     assert corm.corm_append(d, a, a, a, a, a, a + 4, a, a, check=False) == corm.CORM_EINVAL
     assert corm.corm_threshold(-1.0, a, 4, a, check=False) == corm.CORM_EINVAL

@@ -122,7 +122,7 @@ def test_compact_standalone_random_masks():
         K0, V0 = st.K.clone(), st.V.clone()
         pos0, lh0, lens0 = st.pos.clone(), st.last_hit.clone(), st.lens.clone()
         st.keep.copy_(keep)
-        corm.corm_compact(st.desc, st.K, st.V, st.pos, st.last_hit, st.lens, st.keep, st.kept_idx)
+        corm.corm_compact(st.desc, st.K, st.V, st.pos, st.last_hit, st.lens, st.keep, st.kept_idx, st.workspace)
         torch.cuda.synchronize()
         for b in range(B):
             for h in range(Hkv):
@@ -137,7 +137,7 @@ def test_compact_standalone_random_masks():
         # idempotence: compacting again with an all-ones mask changes nothing
         K1, lens1 = st.K.clone(), st.lens.clone()
         st.keep.fill_(1)
-        corm.corm_compact(st.desc, st.K, st.V, st.pos, st.last_hit, st.lens, st.keep, None)
+        corm.corm_compact(st.desc, st.K, st.V, st.pos, st.last_hit, st.lens, st.keep, None, st.workspace)
         torch.cuda.synchronize()
         assert torch.equal(st.lens, lens1)
         for b in range(B):
@@ -269,3 +269,95 @@ def test_repeat_run_is_bit_identical():
     for a, b in zip(*snaps):
         assert torch.equal(a, b)
     assert snaps[0][1].min() < wl.P
+
+
+def test_compact_few_holes_takes_the_parallel_path():
+    """Units that lose at most 16 keys are compacted chunk-parallel with staged boundary rows; holes at the
+    first slot, around the 512-slot chunk boundaries, at the end, and runs that straddle a boundary."""
+    B, Hkv, Lcap, d = 1, 8, 2100, 128
+    lens = [2100, 2048, 1537, 1025, 1024, 513, 512, 40]
+    st, g = _rand_state(B, Hkv, Hkv, d, Lcap, Lcap, 4, 4, "bf16", lens, seed=11)
+    st.pos.copy_(torch.arange(Lcap, dtype=torch.int32).expand(B, Hkv, Lcap) * 3 + 1)
+    st.last_hit.copy_(torch.randint(0, 999, (B, Hkv, Lcap), generator=g).int())
+    hole_sets = [
+        [0], [511], [512], [513], [1023, 1024], [510, 511, 512, 513], [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15],
+        [5, 700, 1400], list(range(505, 521)), [39], [0, 39], list(range(1016, 1032)), [1536], [2047], [2099],
+        [100, 600, 1100, 1600, 2050], list(range(496, 512)), list(range(512, 528)),
+    ]
+    rng = np.random.default_rng(7)
+    for _ in range(6):
+        hole_sets.append(sorted(rng.choice(2100, size=int(rng.integers(1, 17)), replace=False).tolist()))
+    K0, V0 = st.K.clone(), st.V.clone()
+    pos0, lh0, lens0 = st.pos.clone(), st.last_hit.clone(), st.lens.clone()
+    for trial, holes in enumerate(hole_sets):
+        say("few holes", trial, holes[:6], "...")
+        keep = torch.ones(B, Hkv, Lcap, dtype=torch.uint8)
+        keep[:, :, holes] = 0
+        st.keep.copy_(keep)
+        st.kept_idx.fill_(-1)
+        corm.corm_compact(st.desc, st.K, st.V, st.pos, st.last_hit, st.lens, st.keep, st.kept_idx, st.workspace)
+        torch.cuda.synchronize()
+        for h in range(Hkv):
+            l = lens[h]
+            idx = O.stable_compact(keep[0, h, :l].numpy())
+            n = len(idx)
+            assert int(st.lens[0, h]) == n, (trial, h)
+            it = torch.from_numpy(idx).to(DEV)
+            assert torch.equal(st.kept_idx[0, h, :n].long(), it), (trial, h)
+            assert torch.equal(st.K[0, h, :n], K0[0, h][it]) and torch.equal(st.V[0, h, :n], V0[0, h][it]), (trial, h)
+            assert torch.equal(st.pos[0, h, :n], pos0[0, h][it]), (trial, h)
+            assert torch.equal(st.last_hit[0, h, :n], lh0[0, h][it]), (trial, h)
+        st.K.copy_(K0); st.V.copy_(V0); st.pos.copy_(pos0); st.last_hit.copy_(lh0); st.lens.copy_(lens0)
+
+
+def test_two_phase_calls_on_two_streams_equal_the_fused_step():
+    """corm_step_attend on one stream and corm_step_evict on another, ordered by events and alternating
+    two workspaces (the benchmark's pipeline), leave exactly the state the fused call leaves."""
+    wl = W["llama7b_1layer"].replace(B=2, Hq=4, Hkv=4, P=1300, D=24, w=64, r=64,
+                                     q_mean_scales=inputs.STRUCTURED_Q_MEAN)
+    say("two-phase pipeline", wl)
+    n_layers = 3
+    xs = [{k: v.to(DEV) for k, v in inputs.make_layer(wl, l).items() if k != "sinks"} for l in range(n_layers)]
+    n_replay = wl.w
+    pre = wl.P - n_replay
+    results = []
+    for mode in ("fused", "pipelined"):
+        sts = [harness.make_state(wl, DEV, want_masks=False) for _ in range(n_layers)]
+        for st, x in zip(sts, xs):
+            st.preload(x["K0"][:, :, :pre], x["V0"][:, :, :pre])
+        tf = torch.full((wl.B,), pre + 1, dtype=torch.int32, device=DEV)
+        wss = [sts[0].workspace, sts[1].workspace]
+        main, side = torch.cuda.current_stream(), torch.cuda.Stream()
+        ev_att = [torch.cuda.Event() for _ in range(n_layers)]
+        ev_evi = [torch.cuda.Event() for _ in range(n_layers)]
+        outs = []
+        n = 0
+        for j in range(n_replay + wl.D):
+            td = torch.full((wl.B,), pre + 1 + j, dtype=torch.int32, device=DEV)
+            for l, (st, x) in enumerate(zip(sts, xs)):
+                q, k, v, t = harness.step_inputs(wl, x, j, n_replay)
+                if mode == "fused":
+                    st.step(q, k, v, td, tf)
+                else:
+                    if n >= 2:
+                        main.wait_event(ev_evi[(n - 2) % n_layers])
+                    st.step_attend(q, k, v, td, stream=main, workspace=wss[n % 2])
+                    ev_att[l].record(main)
+                    side.wait_event(ev_att[l])
+                    st.step_evict(td, tf, stream=side, workspace=wss[n % 2])
+                    ev_evi[l].record(side)
+                    td.record_stream(side)
+                n += 1
+            if mode == "pipelined":
+                main.wait_stream(side)
+            outs.append(torch.stack([st.out.clone() for st in sts]))
+        torch.cuda.synchronize()
+        lens = torch.stack([st.lens for st in sts]).cpu()
+        live = torch.arange(sts[0].Lcap).view(1, 1, 1, -1) < lens.unsqueeze(-1)
+        Ks = torch.stack([st.K for st in sts]).cpu() * live.unsqueeze(-1)
+        results.append((torch.stack(outs).cpu(), lens, Ks, torch.stack([st.pos for st in sts]).cpu() * live,
+                        torch.stack([st.ring for st in sts]).cpu()))
+        assert all(int(st.status.item()) == 0 for st in sts)
+    for a, b in zip(*results):
+        assert torch.equal(a, b)
+    assert results[0][1].min() < wl.P
