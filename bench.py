@@ -138,10 +138,10 @@ def main():
             n = launch_no[0]
             if n >= 2:
                 main.wait_event(ev_evi[(n - 2) % layers] if layers > 1 else ev_evi[0])
-            st.step_attend(Qs[l][j], Kns[l][j], Vns[l][j], tj, stream=main, workspace=wss[n % 2])
+            st.step_attend(Qs[l][j], Kns[l][j], Vns[l][j], tj, t_first, stream=main, workspace=wss[n % 2])
             ev_att[l].record(main)
             side.wait_event(ev_att[l])
-            st.step_evict(tj, t_first, stream=side, workspace=wss[n % 2])
+            st.step_evict(stream=side, workspace=wss[n % 2])
             ev_evi[l].record(side)
             launch_no[0] = n + 1
 

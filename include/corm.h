@@ -142,24 +142,34 @@ int corm_decode_step(const corm_desc* desc, const void* q, const void* k_new, co
                      uint8_t* keep, int32_t* kept_idx, void* workspace, size_t workspace_bytes,
                      int32_t* status, void* stream);
 
-/* The fused step in two phases, for callers that overlap the bookkeeping with other work (another
+/* The fused step in two phases, for callers that overlap the compaction with other work (another
  * layer's attention, the model's GEMMs) on a second stream:
- *   corm_step_attend  append + attend (Eq. 1, Eq. 2 numerators): reads the cache and lens, writes the new
- *                     row (K, V, pos, last_hit at slot lens) and the workspace (split partials, logits).
- *   corm_step_evict   merge -> out; record -> score_ring, last_hit (Def. 3.1); decide (Def. 4.1 + recent r);
- *                     compact (Algorithm 1's gather) -> K, V, pos, last_hit, lens.
+ *   corm_step_attend  append + attend + record + decide (Eq. 1, Eq. 2, Def. 3.1, Def. 4.1): reads the cache
+ *                     and lens; writes the new row (K, V, pos, last_hit at slot lens), out, the ring row,
+ *                     last_hit of important keys, and the keep flags and per-chunk survivor counts
+ *                     (keep array if given, else workspace).  Does NOT change lens.
+ *   corm_step_evict   compact (Algorithm 1's gather): moves K, V, pos, last_hit rows, writes lens and,
+ *                     if given, kept_idx.  `keep` must be the array passed to corm_step_attend (or NULL).
  * corm_decode_step == corm_step_attend then corm_step_evict on one stream, with the same workspace.
  * The caller orders: evict after attend of the same step; the next step's attend of the same cache
  * after evict; no other call may use the workspace between the two phases. */
 int corm_step_attend(const corm_desc* desc, const void* q, const void* k_new, const void* v_new, void* K, void* V,
-                     const int32_t* lens, int32_t* pos, int32_t* last_hit, const int32_t* t, void* workspace,
-                     size_t workspace_bytes, void* stream);
+                     const int32_t* lens, int32_t* pos, int32_t* last_hit, const int32_t* t, const int32_t* t_first,
+                     void* score_ring, float* out, uint8_t* keep, void* workspace, size_t workspace_bytes,
+                     int32_t* status, void* stream);
 int corm_step_evict(const corm_desc* desc, void* K, void* V, int32_t* lens, int32_t* pos, int32_t* last_hit,
-                    const int32_t* t, const int32_t* t_first, void* score_ring, float* out, uint8_t* keep,
-                    int32_t* kept_idx, void* workspace, size_t workspace_bytes, int32_t* status, void* stream);
+                    const uint8_t* keep, int32_t* kept_idx, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Tuning / test knob (host call, process-wide, not thread safe): how attend + record are launched.
+ * 0 = choose by shape (default); 1 = split kernels (several workgroups per unit, partials merged by a
+ * second launch); 2 = one workgroup per unit with the logits in LDS (taken only if they fit).
+ * Every path produces the same keep mask, indices and cache; out and the recorded scores agree within
+ * fp32 rounding. */
+int corm_force_path(int path);
 
 /* Measurement hook (host call, not thread safe): the NEXT corm_decode_attend / corm_step_attend / corm_decode_step call
- * records start_event immediately before and stop_event immediately after its attend launch, on
+ * records start_event immediately before and stop_event immediately after its attend launch (the
+ * launch that streams K and V: the split attend kernel or the fused unit kernel), on
  * that call's stream, then forgets them.  Both are hipEvent_t handles passed as void*; both NULL
  * cancels.  The attend kernel streams K and V (the step's dominant traffic); this is how its
  * duration is measured in place, without instrumenting any other call. */

@@ -22,7 +22,7 @@ CORM_DEV_UNIT_FULL, CORM_DEV_BAD_STEP, CORM_DEV_BAD_LENS = 1, 2, 4
 
 EXPORTS = ("corm_version", "corm_strerror", "corm_workspace_bytes", "corm_workspace_init", "corm_append",
            "corm_decode_attend", "corm_evict_mask", "corm_evict_mask_summary", "corm_compact",
-           "corm_decode_step", "corm_step_attend", "corm_step_evict", "corm_profile_attend",
+           "corm_decode_step", "corm_step_attend", "corm_step_evict", "corm_force_path", "corm_profile_attend",
            "corm_threshold")
 
 
@@ -63,8 +63,10 @@ def lib() -> ctypes.CDLL:
         L.corm_evict_mask.argtypes = [dp, vp, i32p, i32p, i32p, i32p, vp, vp]
         L.corm_evict_mask_summary.argtypes = [dp, i32p, i32p, i32p, i32p, vp, vp]
         L.corm_compact.argtypes = [dp, vp, vp, i32p, i32p, i32p, vp, i32p, vp, sz, vp]
-        L.corm_step_attend.argtypes = [dp, vp, vp, vp, vp, vp, i32p, i32p, i32p, i32p, vp, sz, vp]
-        L.corm_step_evict.argtypes = [dp, vp, vp, i32p, i32p, i32p, i32p, i32p, vp, vp, vp, i32p, vp, sz, i32p, vp]
+        L.corm_step_attend.argtypes = [dp, vp, vp, vp, vp, vp, i32p, i32p, i32p, i32p, i32p, vp, vp, vp, vp, sz,
+                                       i32p, vp]
+        L.corm_step_evict.argtypes = [dp, vp, vp, i32p, i32p, i32p, vp, i32p, vp, sz, vp]
+        L.corm_force_path.argtypes = [ctypes.c_int]
         L.corm_decode_step.argtypes = [dp, vp, vp, vp, vp, vp, i32p, i32p, i32p, i32p, i32p, vp, vp, vp, i32p,
                                        vp, sz, i32p, vp]
         L.corm_threshold.argtypes = [ctypes.c_float, i32p, ctypes.c_int32, vp, vp]
@@ -174,20 +176,27 @@ def corm_compact(desc, K, V, pos, last_hit, lens, keep, kept_idx=None, workspace
     return _check(rc, "corm_compact") if check else rc
 
 
-def corm_step_attend(desc, q, k_new, v_new, K, V, lens, pos, last_hit, t, workspace, workspace_bytes=None,
-                     stream=None, check=True) -> int:
+def corm_step_attend(desc, q, k_new, v_new, K, V, lens, pos, last_hit, t, t_first, score_ring, out, keep=None,
+                     workspace=None, workspace_bytes=None, status=None, stream=None, check=True) -> int:
     rc = lib().corm_step_attend(ctypes.byref(desc), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(K), _ptr(V), _ptr(lens),
-                                _ptr(pos), _ptr(last_hit), _ptr(t), _ptr(workspace),
-                                _nbytes(workspace, workspace_bytes), _stream(stream))
+                                _ptr(pos), _ptr(last_hit), _ptr(t), _ptr(t_first), _ptr(score_ring), _ptr(out),
+                                _ptr(keep), _ptr(workspace), _nbytes(workspace, workspace_bytes), _ptr(status),
+                                _stream(stream))
     return _check(rc, "corm_step_attend") if check else rc
 
 
-def corm_step_evict(desc, K, V, lens, pos, last_hit, t, t_first, score_ring, out, keep=None, kept_idx=None,
-                    workspace=None, workspace_bytes=None, status=None, stream=None, check=True) -> int:
-    rc = lib().corm_step_evict(ctypes.byref(desc), _ptr(K), _ptr(V), _ptr(lens), _ptr(pos), _ptr(last_hit), _ptr(t),
-                               _ptr(t_first), _ptr(score_ring), _ptr(out), _ptr(keep), _ptr(kept_idx),
-                               _ptr(workspace), _nbytes(workspace, workspace_bytes), _ptr(status), _stream(stream))
+def corm_step_evict(desc, K, V, lens, pos, last_hit, keep=None, kept_idx=None, workspace=None, workspace_bytes=None,
+                    stream=None, check=True) -> int:
+    rc = lib().corm_step_evict(ctypes.byref(desc), _ptr(K), _ptr(V), _ptr(lens), _ptr(pos), _ptr(last_hit),
+                               _ptr(keep), _ptr(kept_idx), _ptr(workspace), _nbytes(workspace, workspace_bytes),
+                               _stream(stream))
     return _check(rc, "corm_step_evict") if check else rc
+
+
+def corm_force_path(path: int, check=True) -> int:
+    """0 = by shape, 1 = split kernels, 2 = one workgroup per unit."""
+    rc = lib().corm_force_path(path)
+    return _check(rc, "corm_force_path") if check else rc
 
 
 def corm_decode_step(desc, q, k_new, v_new, K, V, lens, pos, last_hit, t, t_first, score_ring, out, keep=None,
@@ -247,14 +256,14 @@ class LayerState:
         self.last_hit[:, :, :n] = 0
         self.lens.fill_(n)
 
-    def step_attend(self, q, k_new, v_new, t, stream=None, workspace=None) -> None:
-        corm_step_attend(self.desc, q, k_new, v_new, self.K, self.V, self.lens, self.pos, self.last_hit, t,
-                         self.workspace if workspace is None else workspace, stream=stream)
+    def step_attend(self, q, k_new, v_new, t, t_first, stream=None, workspace=None) -> None:
+        corm_step_attend(self.desc, q, k_new, v_new, self.K, self.V, self.lens, self.pos, self.last_hit, t, t_first,
+                         self.ring, self.out, self.keep, self.workspace if workspace is None else workspace,
+                         status=self.status, stream=stream)
 
-    def step_evict(self, t, t_first, stream=None, workspace=None) -> None:
-        corm_step_evict(self.desc, self.K, self.V, self.lens, self.pos, self.last_hit, t, t_first, self.ring,
-                        self.out, self.keep, self.kept_idx, self.workspace if workspace is None else workspace,
-                        status=self.status, stream=stream)
+    def step_evict(self, stream=None, workspace=None) -> None:
+        corm_step_evict(self.desc, self.K, self.V, self.lens, self.pos, self.last_hit, self.keep, self.kept_idx,
+                        self.workspace if workspace is None else workspace, stream=stream)
 
     def step(self, q, k_new, v_new, t, t_first, stream=None) -> None:
         corm_decode_step(self.desc, q, k_new, v_new, self.K, self.V, self.lens, self.pos, self.last_hit, t, t_first,

@@ -55,6 +55,7 @@ struct Params {
   int32_t B, Hq, Hkv, Lcap, Tcap, w, r, nsplit;
   float thr_scale, scale_log2;
   int32_t do_append, do_evict, ring_bf16;
+  int32_t keep_always;  // write every keep flag (the caller asked for the mask), not only from the first hole on
 };
 
 // ---------------------------------------------------------------- small device helpers
@@ -173,14 +174,32 @@ __device__ __forceinline__ UnitLen unit_len(const Params& p, int unit) {
 
 // ---------------------------------------------------------------- attend
 
-template <typename DT, int D, int G>
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+// Raw buffer descriptor (gfx9 family): hardware range checking makes a 16-byte load that does not
+// lie entirely below num_bytes return zeros without touching memory.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, uint32_t num_bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)num_bytes, 0x00020000);
+}
+
+__device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t r, uint32_t byte_offset) {
+  const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_offset, 0, 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// 2^x by the hardware instruction alone (results below the normal range flush to zero: such
+// probabilities vanish against a sum that is >= 1)
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+template <typename DT, int D, int G, int NW>
 struct Attend {
   static constexpr int EPL = DT::EPL;
   static constexpr int ROWB = D * DT::ESZ;
   static constexpr int LPR = ROWB / 16;   // lanes per row
   static constexpr int RPL = 64 / LPR;    // rows per wave-wide load
   static constexpr int U = UNROLL;
-  static constexpr int STAGE_ROWS = WAVES * RPL * U;  // rows one pipeline stage of the workgroup covers
+  static constexpr int LOAD_ROWS = NW * RPL;          // consecutive rows one unrolled load of the workgroup covers
+  static constexpr int STAGE_ROWS = LOAD_ROWS * U;    // rows one pipeline stage of the workgroup covers
   static_assert(U <= LPR, "logit store uses one lane per unrolled load");
 
   struct Stage {
@@ -188,57 +207,47 @@ struct Attend {
     uint4 v[U];
   };
 
-  // rows of a stage: the workgroup reads WAVES*RPL consecutive rows per unrolled load
-  __device__ static __forceinline__ int row_of(int it, int j, int wv, int sub) { return it + (j * WAVES + wv) * RPL + sub; }
-
-  __device__ static __forceinline__ void load(Stage& st, int it, int cend, int wv, int sub, int cl, const char* Kb,
-                                              const char* Vb, const char* knew, const char* vnew, int new_slot) {
+  // Unrolled load j of a stage: the workgroup reads LOAD_ROWS consecutive rows per load.
+  // off0 = byte offset of this lane's slice in row (wv*RPL + sub) of the stage.
+  __device__ static __forceinline__ void load(Stage& st, __amdgpu_buffer_rsrc_t rk, __amdgpu_buffer_rsrc_t rv,
+                                              uint32_t off) {
 #pragma unroll
-    for (int j = 0; j < U; ++j) {
-      const int rc = min(row_of(it, j, wv, sub), cend - 1);   // clamped: always a live row
-      // the appended row is read from the step's input, not from the cache
-      const char* kp = rc == new_slot ? knew : Kb + (size_t)rc * ROWB;
-      st.k[j] = *reinterpret_cast<const uint4*>(kp + (size_t)cl * 16);
-    }
+    for (int j = 0; j < U; ++j) st.k[j] = buffer_load16(rk, off + (uint32_t)(j * LOAD_ROWS * ROWB));
 #pragma unroll
-    for (int j = 0; j < U; ++j) {
-      const int rc = min(row_of(it, j, wv, sub), cend - 1);
-      const char* vp = rc == new_slot ? vnew : Vb + (size_t)rc * ROWB;
-      st.v[j] = *reinterpret_cast<const uint4*>(vp + (size_t)cl * 16);
-    }
+    for (int j = 0; j < U; ++j) st.v[j] = buffer_load16(rv, off + (uint32_t)(j * LOAD_ROWS * ROWB));
   }
 
-  __device__ static __forceinline__ void compute(const Stage& st, int it, int cend, int wv, int sub, int cl,
-                                                 const uint4 (&qreg)[G], float scale_log2, float* logit_u, int Lcap,
-                                                 float (&m_run)[G], float (&z_run)[G], float (&acc)[G][EPL]) {
+  // row0 = this lane's row in unrolled load 0, lrel0 = its index in the logit staging array
+  // sh_logit (LDS, `lstride` floats per head)
+  __device__ static __forceinline__ void compute(const Stage& st, int row0, int lrel0, int cend, int cl,
+                                                 const uint4 (&qreg)[G], float scale_log2, float* sh_logit,
+                                                 int lstride, float (&m_run)[G], float (&z_run)[G],
+                                                 float (&acc)[G][EPL]) {
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       float s[U];
       float my_logit = 0.f;
-      int my_row = -1;
 #pragma unroll
       for (int j = 0; j < U; ++j) {
-        const int row = row_of(it, j, wv, sub);
+        const int row = row0 + j * LOAD_ROWS;
         const float part = DT::dot(st.k[j], qreg[g]);
         const float tot = row_allreduce_sum<LPR>(part) * scale_log2;
         s[j] = row < cend ? tot : neg_inf();
-        if (cl == j && row < cend) {
-          my_logit = tot;
-          my_row = row;
-        }
+        if (cl == j) my_logit = tot;
       }
-      if (my_row >= 0) logit_u[(size_t)g * Lcap + my_row] = my_logit;
+      // lane cl == j keeps the logit of the row of load j: staged in LDS, written out once per chunk
+      if (cl < U) sh_logit[g * lstride + lrel0 + cl * LOAD_ROWS] = my_logit;
 
       float mnew = m_run[g];
 #pragma unroll
       for (int j = 0; j < U; ++j) mnew = fmaxf(mnew, s[j]);
       const float msafe = mnew == neg_inf() ? 0.f : mnew;
-      const float a = exp2f(m_run[g] - msafe);
+      const float a = fast_exp2(m_run[g] - msafe);
       float pj[U];
       float zs = 0.f;
 #pragma unroll
       for (int j = 0; j < U; ++j) {
-        pj[j] = exp2f(s[j] - msafe);
+        pj[j] = fast_exp2(s[j] - msafe);
         zs += pj[j];
       }
       z_run[g] = fmaf(z_run[g], a, zs);
@@ -253,8 +262,8 @@ struct Attend {
 
 template <typename DT, int D, int G>
 __global__ __launch_bounds__(WG) void corm_attend_kernel(const Params p) {
-  using A = Attend<DT, D, G>;
-  constexpr int EPL = A::EPL, ROWB = A::ROWB, LPR = A::LPR;
+  using A = Attend<DT, D, G, WAVES>;
+  constexpr int EPL = A::EPL, ROWB = A::ROWB, LPR = A::LPR, RPL = A::RPL;
 
   const int split = blockIdx.x;
   const int unit = blockIdx.y;
@@ -271,13 +280,33 @@ __global__ __launch_bounds__(WG) void corm_attend_kernel(const Params p) {
   __shared__ float sh_m[G][WAVES];
   __shared__ float sh_z[G][WAVES];
   __shared__ float sh_acc[G][WAVES][D];
+  __shared__ float sh_logit[G][CHUNK];   // raw logits of the chunk, stored to the workspace at the end
 
   char* Kb = reinterpret_cast<char*>(p.K) + (size_t)unit * p.Lcap * ROWB;
   char* Vb = reinterpret_cast<char*>(p.V) + (size_t)unit * p.Lcap * ROWB;
-  const char* knew = reinterpret_cast<const char*>(p.k_new) + (size_t)unit * ROWB;
-  const char* vnew = reinterpret_cast<const char*>(p.v_new) + (size_t)unit * ROWB;
   const int hq0 = hkv * G;
-  const int new_slot = ul.appended ? ul.L0 : -1;
+  const int cbeg = split * CHUNK;
+  const int cend = min(cbeg + CHUNK, L);
+
+  // The append: the owner of the chunk that holds the new slot writes the row and its metadata into the
+  // cache first; after the barrier every wave of this workgroup reads it back like any other row.
+  if (ul.appended && ul.L0 >= cbeg) {   // L0 = L-1 < cend: this workgroup owns the new slot
+    if (wv == 0) {
+      if (lane < LPR) {
+        const char* knew = reinterpret_cast<const char*>(p.k_new) + (size_t)unit * ROWB;
+        const char* vnew = reinterpret_cast<const char*>(p.v_new) + (size_t)unit * ROWB;
+        const uint4 kx = *reinterpret_cast<const uint4*>(knew + (size_t)lane * 16);
+        const uint4 vx = *reinterpret_cast<const uint4*>(vnew + (size_t)lane * 16);
+        *reinterpret_cast<uint4*>(Kb + (size_t)ul.L0 * ROWB + (size_t)lane * 16) = kx;
+        *reinterpret_cast<uint4*>(Vb + (size_t)ul.L0 * ROWB + (size_t)lane * 16) = vx;
+      }
+      if (lane == 0) {
+        p.pos[(size_t)unit * p.Lcap + ul.L0] = p.t[b] - 1;
+        p.last_hit[(size_t)unit * p.Lcap + ul.L0] = 0;
+      }
+    }
+    __syncthreads();
+  }
 
   // this lane's slice of the G queries
   uint4 qreg[G];
@@ -285,23 +314,6 @@ __global__ __launch_bounds__(WG) void corm_attend_kernel(const Params p) {
   for (int g = 0; g < G; ++g)
     qreg[g] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(p.q) +
                                               ((size_t)(b * p.Hq + hq0 + g) * ROWB + (size_t)cl * 16));
-
-  const int cbeg = split * CHUNK;
-  const int cend = min(cbeg + CHUNK, L);
-
-  // the append: the owner of the chunk that holds the new slot writes the row and its metadata
-  if (new_slot >= cbeg && new_slot < cend && wv == 0) {
-    if (lane < LPR) {
-      const uint4 kx = *reinterpret_cast<const uint4*>(knew + (size_t)lane * 16);
-      const uint4 vx = *reinterpret_cast<const uint4*>(vnew + (size_t)lane * 16);
-      *reinterpret_cast<uint4*>(Kb + (size_t)new_slot * ROWB + (size_t)lane * 16) = kx;
-      *reinterpret_cast<uint4*>(Vb + (size_t)new_slot * ROWB + (size_t)lane * 16) = vx;
-    }
-    if (lane == 0) {
-      p.pos[(size_t)unit * p.Lcap + new_slot] = p.t[b] - 1;
-      p.last_hit[(size_t)unit * p.Lcap + new_slot] = 0;
-    }
-  }
 
   float m_run[G], z_run[G], acc[G][EPL];
 #pragma unroll
@@ -313,37 +325,47 @@ __global__ __launch_bounds__(WG) void corm_attend_kernel(const Params p) {
   }
   float* logit_u = p.logits + (size_t)(b * p.Hq + hq0) * p.Lcap;
 
-  // two register stages: the loads of the next stage are in flight while this one is consumed
+  // Rows of this chunk only: the descriptors end at row cend, so the pipeline may run past the end of
+  // the chunk (those loads return zeros and cost no memory traffic; their scores are masked).
+  const __amdgpu_buffer_rsrc_t rk = make_rsrc(Kb, (uint32_t)cend * ROWB);
+  const __amdgpu_buffer_rsrc_t rv = make_rsrc(Vb, (uint32_t)cend * ROWB);
+  const int lane_row = wv * RPL + sub;                            // this lane's row inside a load
+  uint32_t off = (uint32_t)(cbeg + lane_row) * ROWB + (uint32_t)cl * 16;
+  constexpr uint32_t STAGE_BYTES = (uint32_t)A::STAGE_ROWS * ROWB;
+
+  // Two register stages, loads always issued one stage ahead.  The chunk loop is fully unrolled
+  // (CHUNK is a compile-time constant): no loop-carried registers, no branch around a load, so each
+  // stage is consumed while the next one is still in flight and the wait counts are exact.
+  constexpr int PAIRS = CHUNK / (2 * A::STAGE_ROWS);
+  static_assert(PAIRS >= 1 && CHUNK % (2 * A::STAGE_ROWS) == 0, "CHUNK must hold whole stage pairs");
   typename A::Stage s0, s1;
-  int it = cbeg;
-  A::load(s0, it, cend, wv, sub, cl, Kb, Vb, knew, vnew, new_slot);
-  while (true) {
-    const bool more1 = it + A::STAGE_ROWS < cend;
-    if (more1) A::load(s1, it + A::STAGE_ROWS, cend, wv, sub, cl, Kb, Vb, knew, vnew, new_slot);
-    A::compute(s0, it, cend, wv, sub, cl, qreg, p.scale_log2, logit_u, p.Lcap, m_run, z_run, acc);
-    if (!more1) break;
-    it += A::STAGE_ROWS;
-    const bool more0 = it + A::STAGE_ROWS < cend;
-    if (more0) A::load(s0, it + A::STAGE_ROWS, cend, wv, sub, cl, Kb, Vb, knew, vnew, new_slot);
-    A::compute(s1, it, cend, wv, sub, cl, qreg, p.scale_log2, logit_u, p.Lcap, m_run, z_run, acc);
-    if (!more0) break;
-    it += A::STAGE_ROWS;
+  A::load(s0, rk, rv, off);
+#pragma unroll
+  for (int i = 0; i < PAIRS; ++i) {
+    const int it = cbeg + i * 2 * A::STAGE_ROWS;
+    if (it >= cend) break;
+    A::load(s1, rk, rv, off + (uint32_t)(2 * i + 1) * STAGE_BYTES);
+    A::compute(s0, it + lane_row, it - cbeg + lane_row, cend, cl, qreg, p.scale_log2, &sh_logit[0][0], CHUNK, m_run,
+               z_run, acc);
+    if (i + 1 < PAIRS) A::load(s0, rk, rv, off + (uint32_t)(2 * i + 2) * STAGE_BYTES);
+    A::compute(s1, it + A::STAGE_ROWS + lane_row, it - cbeg + A::STAGE_ROWS + lane_row, cend, cl, qreg,
+               p.scale_log2, &sh_logit[0][0], CHUNK, m_run, z_run, acc);
   }
 
   // merge the row groups of the wave (lanes differing in bits >= log2(LPR)), then the waves
 #pragma unroll
   for (int g = 0; g < G; ++g) {
 #pragma unroll
-    for (int off = LPR; off < 64; off <<= 1) {
-      const float mo = __shfl_xor(m_run[g], off);
-      const float zo = __shfl_xor(z_run[g], off);
+    for (int o = LPR; o < 64; o <<= 1) {
+      const float mo = __shfl_xor(m_run[g], o);
+      const float zo = __shfl_xor(z_run[g], o);
       const float mn = fmaxf(m_run[g], mo);
       const float ms = mn == neg_inf() ? 0.f : mn;
-      const float a0 = exp2f(m_run[g] - ms), a1 = exp2f(mo - ms);
+      const float a0 = fast_exp2(m_run[g] - ms), a1 = fast_exp2(mo - ms);
       z_run[g] = z_run[g] * a0 + zo * a1;
 #pragma unroll
       for (int e = 0; e < EPL; ++e) {
-        const float ao = __shfl_xor(acc[g][e], off);
+        const float ao = __shfl_xor(acc[g][e], o);
         acc[g][e] = acc[g][e] * a0 + ao * a1;
       }
       m_run[g] = mn;
@@ -358,6 +380,12 @@ __global__ __launch_bounds__(WG) void corm_attend_kernel(const Params p) {
     }
   }
   __syncthreads();
+
+  // the chunk's logits, coalesced
+  for (int idx = tid; idx < G * CHUNK; idx += WG) {
+    const int g = idx / CHUNK, i = idx - g * CHUNK;
+    if (cbeg + i < cend) logit_u[(size_t)g * p.Lcap + cbeg + i] = sh_logit[g][i];
+  }
 
   // partial of this split: [max, sum, acc[D]] per query head
   constexpr int PSTRIDE = D + 2;
@@ -374,7 +402,7 @@ __global__ __launch_bounds__(WG) void corm_attend_kernel(const Params p) {
     float zt = 0.f, at = 0.f;
 #pragma unroll
     for (int i = 0; i < WAVES; ++i) {
-      const float a = exp2f(mw[i] - ms);
+      const float a = fast_exp2(mw[i] - ms);
       zt = fmaf(sh_z[g][i], a, zt);
       at = fmaf(sh_acc[g][i][c], a, at);
     }
@@ -384,6 +412,216 @@ __global__ __launch_bounds__(WG) void corm_attend_kernel(const Params p) {
       part[0] = mx;
       part[1] = zt;
     }
+  }
+}
+
+// ---------------------------------------------------------------- fused unit kernel (no split)
+//
+// When a launch has at least as many units as the chip has compute units, splitting units buys
+// nothing: one workgroup of 512 threads streams a whole unit, keeps the raw logits in LDS, and,
+// knowing the unit's max and sum itself, writes out, the ring row, last_hit and the keep flags in
+// the same launch.  No partials, no logits round trip through memory, no second kernel.  Only the
+// (rare) compaction remains for the two compaction launches.
+
+constexpr int UNIT_WG = 512;
+constexpr int UNIT_WAVES = UNIT_WG / 64;
+static_assert(UNIT_WG == CHUNK, "the unit kernel reports survivors per CHUNK slots, one tile each");
+
+template <typename DT, int D, int G>
+__global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, const int lstride) {
+  using A = Attend<DT, D, G, UNIT_WAVES>;
+  constexpr int EPL = A::EPL, ROWB = A::ROWB, LPR = A::LPR, RPL = A::RPL;
+
+  extern __shared__ float sh_logit[];   // [G][lstride] raw logits of the unit (log2 domain)
+  __shared__ float sh_m[G][UNIT_WAVES];
+  __shared__ float sh_z[G][UNIT_WAVES];
+  __shared__ float sh_acc[G][UNIT_WAVES][D];
+  __shared__ float sh_M[G], sh_Z[G];
+  __shared__ int sh_cnt[UNIT_WAVES];
+
+  const int unit = blockIdx.x;
+  const UnitLen ul = unit_len(p, unit);
+  const int L = ul.L;
+  const int b = unit / p.Hkv;
+  const int hkv = unit - b * p.Hkv;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wv = tid >> 6;
+  const int sub = lane / LPR, cl = lane % LPR;
+  const int hq0 = hkv * G;
+  if (tid == 0 && ul.flags && p.status) atomicOr(p.status, ul.flags);
+
+  char* Kb = reinterpret_cast<char*>(p.K) + (size_t)unit * p.Lcap * ROWB;
+  char* Vb = reinterpret_cast<char*>(p.V) + (size_t)unit * p.Lcap * ROWB;
+  int32_t* posb = p.pos + (size_t)unit * p.Lcap;
+  int32_t* lhb = p.last_hit + (size_t)unit * p.Lcap;
+  const int tcur = p.t[b];
+
+  if (L == 0) {   // empty unit: out = 0, nothing to record
+    for (int idx = tid; idx < G * D; idx += UNIT_WG) p.out[(size_t)(b * p.Hq + hq0) * D + idx] = 0.f;
+    return;
+  }
+
+  // the append: the row and its metadata go into the cache first, then everybody reads them back
+  if (ul.appended) {
+    if (wv == 0) {
+      if (lane < LPR) {
+        const char* knew = reinterpret_cast<const char*>(p.k_new) + (size_t)unit * ROWB;
+        const char* vnew = reinterpret_cast<const char*>(p.v_new) + (size_t)unit * ROWB;
+        const uint4 kx = *reinterpret_cast<const uint4*>(knew + (size_t)lane * 16);
+        const uint4 vx = *reinterpret_cast<const uint4*>(vnew + (size_t)lane * 16);
+        *reinterpret_cast<uint4*>(Kb + (size_t)ul.L0 * ROWB + (size_t)lane * 16) = kx;
+        *reinterpret_cast<uint4*>(Vb + (size_t)ul.L0 * ROWB + (size_t)lane * 16) = vx;
+      }
+      if (lane == 0) {
+        posb[ul.L0] = tcur - 1;
+        lhb[ul.L0] = 0;
+      }
+    }
+    __syncthreads();
+  }
+
+  uint4 qreg[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+    qreg[g] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(p.q) +
+                                              ((size_t)(b * p.Hq + hq0 + g) * ROWB + (size_t)cl * 16));
+  float m_run[G], z_run[G], acc[G][EPL];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    m_run[g] = neg_inf();
+    z_run[g] = 0.f;
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+  }
+
+  // stream the unit: descriptors end at row L, loads past it return zeros and cost no traffic
+  const __amdgpu_buffer_rsrc_t rk = make_rsrc(Kb, (uint32_t)L * ROWB);
+  const __amdgpu_buffer_rsrc_t rv = make_rsrc(Vb, (uint32_t)L * ROWB);
+  const int lane_row = wv * RPL + sub;
+  uint32_t off = (uint32_t)lane_row * ROWB + (uint32_t)cl * 16;
+  constexpr uint32_t STAGE_BYTES = (uint32_t)A::STAGE_ROWS * ROWB;
+  // Super-chunks of PAIRS_U stage pairs, each fully unrolled (two register stages, the next stage's
+  // loads in flight while one is consumed; straight-line code keeps the wait counts exact).  The
+  // pipeline drains between super-chunks; the other waves of the compute unit cover that gap.
+  constexpr int PAIRS_U = 4;
+  constexpr int SUPER_ROWS = 2 * PAIRS_U * A::STAGE_ROWS;
+  typename A::Stage s0, s1;
+  for (int c0 = 0; c0 < L; c0 += SUPER_ROWS) {
+    A::load(s0, rk, rv, off);
+#pragma unroll
+    for (int i = 0; i < PAIRS_U; ++i) {
+      const int it = c0 + i * 2 * A::STAGE_ROWS;
+      if (it >= L) break;
+      A::load(s1, rk, rv, off + (uint32_t)(2 * i + 1) * STAGE_BYTES);
+      A::compute(s0, it + lane_row, it + lane_row, L, cl, qreg, p.scale_log2, sh_logit, lstride, m_run, z_run, acc);
+      if (i + 1 < PAIRS_U) A::load(s0, rk, rv, off + (uint32_t)(2 * i + 2) * STAGE_BYTES);
+      A::compute(s1, it + A::STAGE_ROWS + lane_row, it + A::STAGE_ROWS + lane_row, L, cl, qreg, p.scale_log2,
+                 sh_logit, lstride, m_run, z_run, acc);
+    }
+    off += (uint32_t)(2 * PAIRS_U) * STAGE_BYTES;
+  }
+
+  // merge the row groups of each wave, then the waves
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+#pragma unroll
+    for (int o = LPR; o < 64; o <<= 1) {
+      const float mo = __shfl_xor(m_run[g], o);
+      const float zo = __shfl_xor(z_run[g], o);
+      const float mn = fmaxf(m_run[g], mo);
+      const float ms = mn == neg_inf() ? 0.f : mn;
+      const float a0 = fast_exp2(m_run[g] - ms), a1 = fast_exp2(mo - ms);
+      z_run[g] = z_run[g] * a0 + zo * a1;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) {
+        const float ao = __shfl_xor(acc[g][e], o);
+        acc[g][e] = acc[g][e] * a0 + ao * a1;
+      }
+      m_run[g] = mn;
+    }
+    if (sub == 0) {
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) sh_acc[g][wv][cl * EPL + e] = acc[g][e];
+      if (cl == 0) {
+        sh_m[g][wv] = m_run[g];
+        sh_z[g][wv] = z_run[g];
+      }
+    }
+  }
+  __syncthreads();
+
+  // out (Eq. 1) and the unit's max / sum (Eq. 2)
+  for (int idx = tid; idx < G * D; idx += UNIT_WG) {
+    const int g = idx / D, c = idx - g * D;
+    float mx = neg_inf();
+#pragma unroll
+    for (int i = 0; i < UNIT_WAVES; ++i) mx = fmaxf(mx, sh_m[g][i]);
+    float zt = 0.f, at = 0.f;
+#pragma unroll
+    for (int i = 0; i < UNIT_WAVES; ++i) {
+      const float a = fast_exp2(sh_m[g][i] - mx);
+      zt = fmaf(sh_z[g][i], a, zt);
+      at = fmaf(sh_acc[g][i][c], a, at);
+    }
+    p.out[(size_t)(b * p.Hq + hq0 + g) * D + c] = at / zt;
+    if (c == 0) {
+      sh_M[g] = mx;
+      sh_Z[g] = zt;
+    }
+  }
+  __syncthreads();
+
+  // record (Def. 3.1) and decide (Def. 4.1 + recent r)
+  const bool step_ok = tcur >= 1 && tcur <= p.Tcap;
+  if (!step_ok && tid == 0 && p.status) atomicOr(p.status, CORM_DEV_BAD_STEP);
+  const int slot = step_ok ? (tcur - 1) % p.w : 0;
+  const float thr = importance_threshold(p.thr_scale, step_ok ? tcur : 1);
+  const int tfirst = p.do_evict ? p.t_first[b] : tcur;
+  const bool full = p.do_evict && step_ok && (tcur - tfirst + 1 >= p.w);
+  uint8_t* keepb = p.keep + (size_t)unit * p.Lcap;
+  bool write_keep = p.keep_always != 0;   // else only from the first tile that lost a key
+  for (int tile = 0; tile < L; tile += UNIT_WG) {
+    const int i = tile + tid;
+    const bool live = i < L;
+    bool keep = false;
+    if (live) {
+      const int my_pos = posb[i];
+      int lh = lhb[i];
+      const bool pos_ok = my_pos >= 0 && my_pos < p.Tcap;
+      if (!pos_ok && p.status) atomicOr(p.status, CORM_DEV_BAD_STEP);
+      bool hit = false;
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float sc = fast_exp2(sh_logit[g * lstride + i] - sh_M[g]) / sh_Z[g];
+        float stored;
+        const size_t ri = ((size_t)(b * p.Hq + hq0 + g) * p.w + slot) * p.Tcap + (size_t)my_pos;
+        if (p.ring_bf16) {
+          const uint16_t hb = f32_to_bf16_rne(sc);
+          stored = __uint_as_float((uint32_t)hb << 16);
+          if (step_ok && pos_ok) reinterpret_cast<uint16_t*>(p.ring)[ri] = hb;
+        } else {
+          stored = sc;
+          if (step_ok && pos_ok) reinterpret_cast<float*>(p.ring)[ri] = sc;
+        }
+        hit |= (stored >= thr);
+      }
+      if (hit && step_ok) {
+        lh = tcur;
+        lhb[i] = tcur;
+      }
+      keep = !full || (lh > tcur - p.w) || (i >= L - p.r);
+    }
+    if (!p.do_evict) continue;
+    const int cnt = __popcll(__ballot(keep));
+    if (lane == 0) sh_cnt[wv] = cnt;
+    __syncthreads();
+    int tot = 0;
+#pragma unroll
+    for (int k = 0; k < UNIT_WAVES; ++k) tot += sh_cnt[k];
+    write_keep = write_keep || tot < min(UNIT_WG, L - tile);
+    if (write_keep && live) keepb[i] = keep ? 1 : 0;
+    if (tid == 0) p.counts[(size_t)unit * p.nsplit + tile / CHUNK] = tot;
+    __syncthreads();
   }
 }
 
@@ -709,7 +947,10 @@ __global__ __launch_bounds__(WG) void corm_compact_local_kernel(const CompactArg
   int rho_base = R;  // survivor number of the first survivor of the current tile
   for (int tile = cbeg; tile < cend; tile += WG) {
     const int i = tile + tid;
-    const bool kp = i < cend && keepb[i] != 0;
+    // a chunk whose count equals its size lost nothing: its flags are implied (and may be unwritten)
+    const int ch = tile / CHUNK;
+    const bool chunk_full = cnt[ch] == min(CHUNK, L - ch * CHUNK);
+    const bool kp = i < cend && (chunk_full || keepb[i] != 0);
     int my_pos = 0, my_lh = 0;
     if (kp) {
       my_pos = posb[i];
@@ -904,6 +1145,7 @@ int validate_desc(const corm_desc* d) {
   if (!(d->sm_scale >= 0.f) || !std::isfinite(d->sm_scale)) return CORM_EINVAL;
   if ((long long)d->B * d->Hkv > 2147483647LL / 2 || (long long)d->B * d->Hq > 2147483647LL / 2) return CORM_EINVAL;
   if (d->B * d->Hkv > 65535) return CORM_EUNSUPPORTED;  // grid.y limit
+  if ((long long)d->Lcap * 512 >= (1LL << 31)) return CORM_EUNSUPPORTED;  // byte offsets inside a unit are 32-bit
   if (d->kv_dtype != CORM_F32 && d->kv_dtype != CORM_BF16) return CORM_EUNSUPPORTED;
   if (d->score_dtype != CORM_F32 && d->score_dtype != CORM_BF16) return CORM_EUNSUPPORTED;
   if (d->d != 64 && d->d != 128) return CORM_EUNSUPPORTED;
@@ -971,6 +1213,68 @@ int launch_attend(const corm_desc* d, const Params& p, hipStream_t s) {
   return CORM_OK;
 }
 
+// 0 = choose by shape, 1 = split kernels (attend + record), 2 = fused unit kernel
+int g_force_path = 0;
+int g_num_cus = 0;
+
+size_t unit_lds_bytes(const corm_desc* d, int* lstride) {
+  const int rowb = row_bytes(d);
+  const int stage_rows = UNIT_WAVES * (64 / (rowb / 16)) * UNROLL;
+  *lstride = (d->Lcap + 2 * stage_rows - 1) / (2 * stage_rows) * (2 * stage_rows);
+  return (size_t)(d->Hq / d->Hkv) * (size_t)(*lstride) * sizeof(float);
+}
+
+// The unit kernel needs the unit's logits in LDS (48 KiB of dynamic LDS at most here, so that two
+// workgroups fit a compute unit) and pays off once there are at least as many units as compute units.
+bool use_unit_path(const corm_desc* d) {
+  int lstride;
+  const bool fits = unit_lds_bytes(d, &lstride) <= 48 * 1024 && d->Hq / d->Hkv <= 4;  // G = 8 exceeds the register file
+  if (g_force_path == 1 || !fits) return false;
+  if (g_force_path == 2) return true;
+  if (g_num_cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      n = 256;
+    g_num_cus = n;
+  }
+  return d->B * d->Hkv >= g_num_cus;
+}
+
+template <typename DT, int D>
+int launch_unit_g(const Params& p, int G, int units, size_t lds, int lstride, hipStream_t s) {
+  switch (G) {
+    case 1: hipLaunchKernelGGL((corm_unit_kernel<DT, D, 1>), dim3(units), dim3(UNIT_WG), lds, s, p, lstride); break;
+    case 2: hipLaunchKernelGGL((corm_unit_kernel<DT, D, 2>), dim3(units), dim3(UNIT_WG), lds, s, p, lstride); break;
+    case 4: hipLaunchKernelGGL((corm_unit_kernel<DT, D, 4>), dim3(units), dim3(UNIT_WG), lds, s, p, lstride); break;
+    default: return CORM_EUNSUPPORTED;
+  }
+  return launch_status();
+}
+
+int launch_unit(const corm_desc* d, const Params& p, hipStream_t s) {
+  int lstride;
+  const size_t lds = unit_lds_bytes(d, &lstride);
+  const int G = d->Hq / d->Hkv, units = d->B * d->Hkv;
+  const hipEvent_t ev0 = g_prof_start, ev1 = g_prof_stop;
+  g_prof_start = g_prof_stop = nullptr;
+  if (ev0 && hipEventRecord(ev0, s) != hipSuccess) return CORM_EHIP;
+  int rc;
+  if (d->kv_dtype == CORM_F32) {
+    rc = d->d == 64 ? launch_unit_g<F32, 64>(p, G, units, lds, lstride, s)
+                    : launch_unit_g<F32, 128>(p, G, units, lds, lstride, s);
+  } else {
+    rc = d->d == 64 ? launch_unit_g<BF16, 64>(p, G, units, lds, lstride, s)
+                    : launch_unit_g<BF16, 128>(p, G, units, lds, lstride, s);
+  }
+  if (rc) return rc;
+  if (ev1 && hipEventRecord(ev1, s) != hipSuccess) return CORM_EHIP;
+  return CORM_OK;
+}
+
+// append (if p.do_append) + attend + record: one fused launch or the attend / record pair
+int launch_attend_record(const corm_desc* d, const Params& p, hipStream_t s);
+
 int launch_record(const corm_desc* d, const Params& p, hipStream_t s) {
   const int G = d->Hq / d->Hkv;
   const dim3 grid(p.nsplit, d->B * d->Hkv);
@@ -982,6 +1286,13 @@ int launch_record(const corm_desc* d, const Params& p, hipStream_t s) {
     default: return CORM_EUNSUPPORTED;
   }
   return launch_status();
+}
+
+int launch_attend_record(const corm_desc* d, const Params& p, hipStream_t s) {
+  if (use_unit_path(d)) return launch_unit(d, p, s);
+  const int rc = launch_attend(d, p, s);
+  if (rc) return rc;
+  return launch_record(d, p, s);
 }
 
 // local + boundary launches of the compaction; count_first: derive the per-split counts from the mask
@@ -1108,9 +1419,7 @@ int corm_decode_attend(const corm_desc* desc, const void* q, const void* K, cons
   p.t = t; p.t_first = t; p.ring = score_ring; p.out = out; p.status = status;
   p.do_append = 0; p.do_evict = 0;
   bind_params(desc, wl, workspace, p);
-  rc = launch_attend(desc, p, (hipStream_t)stream);
-  if (rc) return rc;
-  return launch_record(desc, p, (hipStream_t)stream);
+  return launch_attend_record(desc, p, (hipStream_t)stream);
 }
 
 int corm_evict_mask(const corm_desc* desc, const void* score_ring, const int32_t* lens, const int32_t* pos,
@@ -1155,42 +1464,38 @@ int corm_compact(const corm_desc* desc, void* K, void* V, int32_t* pos, int32_t*
 }
 
 int corm_step_attend(const corm_desc* desc, const void* q, const void* k_new, const void* v_new, void* K, void* V,
-                     const int32_t* lens, int32_t* pos, int32_t* last_hit, const int32_t* t, void* workspace,
-                     size_t workspace_bytes, void* stream) {
+                     const int32_t* lens, int32_t* pos, int32_t* last_hit, const int32_t* t, const int32_t* t_first,
+                     void* score_ring, float* out, uint8_t* keep, void* workspace, size_t workspace_bytes,
+                     int32_t* status, void* stream) {
   int rc = validate_desc(desc);
   if (rc) return rc;
-  rc = check_step_pointers(q, k_new, v_new, K, V, lens, pos, last_hit, t, t, K, reinterpret_cast<const float*>(K),
-                           nullptr, nullptr);
+  rc = check_step_pointers(q, k_new, v_new, K, V, lens, pos, last_hit, t, t_first, score_ring, out, nullptr, status);
   if (rc) return rc;
   WorkspaceLayout wl;
   rc = check_workspace(desc, workspace, workspace_bytes, &wl);
   if (rc) return rc;
   Params p = {};
   p.q = q; p.k_new = k_new; p.v_new = v_new; p.K = K; p.V = V; p.lens = const_cast<int32_t*>(lens); p.pos = pos;
-  p.last_hit = last_hit; p.t = t; p.t_first = t;
+  p.last_hit = last_hit; p.t = t; p.t_first = t_first; p.ring = score_ring; p.out = out; p.keep = keep;
+  p.keep_always = keep != nullptr; p.status = status;
   p.do_append = 1; p.do_evict = 1;
   bind_params(desc, wl, workspace, p);
-  return launch_attend(desc, p, (hipStream_t)stream);
+  return launch_attend_record(desc, p, (hipStream_t)stream);
 }
 
 int corm_step_evict(const corm_desc* desc, void* K, void* V, int32_t* lens, int32_t* pos, int32_t* last_hit,
-                    const int32_t* t, const int32_t* t_first, void* score_ring, float* out, uint8_t* keep,
-                    int32_t* kept_idx, void* workspace, size_t workspace_bytes, int32_t* status, void* stream) {
+                    const uint8_t* keep, int32_t* kept_idx, void* workspace, size_t workspace_bytes, void* stream) {
   int rc = validate_desc(desc);
   if (rc) return rc;
-  rc = check_step_pointers(K, K, V, K, V, lens, pos, last_hit, t, t_first, score_ring, out, kept_idx, status);
-  if (rc) return rc;
+  if (!K || !V || !pos || !last_hit || !lens) return CORM_EINVAL;
+  if (misaligned16(K) || misaligned16(V) || misaligned4(pos) || misaligned4(last_hit) || misaligned4(lens) ||
+      misaligned4(kept_idx))
+    return CORM_EINVAL;
   WorkspaceLayout wl;
   rc = check_workspace(desc, workspace, workspace_bytes, &wl);
   if (rc) return rc;
-  Params p = {};
-  p.K = K; p.V = V; p.lens = lens; p.pos = pos; p.last_hit = last_hit; p.t = t; p.t_first = t_first;
-  p.ring = score_ring; p.out = out; p.keep = keep; p.kept_idx = kept_idx; p.status = status;
-  p.do_append = 1; p.do_evict = 1;
-  bind_params(desc, wl, workspace, p);
-  rc = launch_record(desc, p, (hipStream_t)stream);
-  if (rc) return rc;
-  return launch_compact(desc, wl, workspace, K, V, pos, last_hit, lens, p.keep, kept_idx, 1, false,
+  if (!keep) keep = reinterpret_cast<const uint8_t*>(reinterpret_cast<char*>(workspace) + wl.keep_off);
+  return launch_compact(desc, wl, workspace, K, V, pos, last_hit, lens, keep, kept_idx, 1, false,
                         (hipStream_t)stream);
 }
 
@@ -1200,12 +1505,17 @@ int corm_decode_step(const corm_desc* desc, const void* q, const void* k_new, co
                      size_t workspace_bytes, int32_t* status, void* stream) {
   int rc = validate_desc(desc);
   if (rc) return rc;
-  rc = check_step_pointers(q, k_new, v_new, K, V, lens, pos, last_hit, t, t_first, score_ring, out, kept_idx, status);
+  if (misaligned4(kept_idx)) return CORM_EINVAL;
+  rc = corm_step_attend(desc, q, k_new, v_new, K, V, lens, pos, last_hit, t, t_first, score_ring, out, keep,
+                        workspace, workspace_bytes, status, stream);
   if (rc) return rc;
-  rc = corm_step_attend(desc, q, k_new, v_new, K, V, lens, pos, last_hit, t, workspace, workspace_bytes, stream);
-  if (rc) return rc;
-  return corm_step_evict(desc, K, V, lens, pos, last_hit, t, t_first, score_ring, out, keep, kept_idx, workspace,
-                         workspace_bytes, status, stream);
+  return corm_step_evict(desc, K, V, lens, pos, last_hit, keep, kept_idx, workspace, workspace_bytes, stream);
+}
+
+int corm_force_path(int path) {
+  if (path < 0 || path > 2) return CORM_EINVAL;
+  g_force_path = path;
+  return CORM_OK;
 }
 
 int corm_profile_attend(void* start_event, void* stop_event) {

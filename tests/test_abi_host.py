@@ -89,8 +89,11 @@ def test_null_and_misaligned_pointers_are_rejected_on_the_host():
     assert rc == corm.CORM_EINVAL
     assert corm.corm_compact(d, None, a, a, a, a, a, workspace=a, workspace_bytes=1 << 30, check=False) == corm.CORM_EINVAL
     assert corm.corm_compact(d, a, a, a, a, a, a, workspace=a, workspace_bytes=8, check=False) == corm.CORM_ECAPACITY
-    assert corm.corm_step_attend(d, a, a, a, a, a, a, a, a, None, a, 1 << 30, check=False) == corm.CORM_EINVAL
-    assert corm.corm_step_evict(d, a, a, a, a, a, a, a, a, None, workspace=a, workspace_bytes=1 << 30, check=False) == corm.CORM_EINVAL
+    assert corm.corm_step_attend(d, a, a, a, a, a, a, a, a, None, a, a, a, workspace=a, workspace_bytes=1 << 30,
+                                 check=False) == corm.CORM_EINVAL
+    assert corm.corm_step_evict(d, a, a, None, a, a, workspace=a, workspace_bytes=1 << 30, check=False) == corm.CORM_EINVAL
+    assert corm.corm_force_path(3, check=False) == corm.CORM_EINVAL
+    assert corm.corm_force_path(0) == corm.CORM_OK
     assert corm.corm_evict_mask(d, a, a, a, a, None, a, check=False) == corm.CORM_EINVAL
     assert corm.corm_append(d, a, a, a, a, a, a + 4, a, a, check=False) == corm.CORM_EINVAL
     assert corm.corm_threshold(-1.0, a, 4, a, check=False) == corm.CORM_EINVAL

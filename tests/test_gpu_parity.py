@@ -14,6 +14,15 @@ DEV = "cuda:0"
 W = inputs.WORKLOADS
 
 
+@pytest.fixture(params=["split", "unit"], autouse=True)
+def launch_path(request):
+    """Every test runs with both ways of launching attend + record: split kernels (several workgroups
+    per unit) and the fused one-workgroup-per-unit kernel."""
+    corm.corm_force_path({"split": 1, "unit": 2}[request.param])
+    yield request.param
+    corm.corm_force_path(0)
+
+
 def say(*a):
     print("[case]", *a, flush=True)
     sys.stdout.flush()
@@ -341,10 +350,10 @@ def test_two_phase_calls_on_two_streams_equal_the_fused_step():
                 else:
                     if n >= 2:
                         main.wait_event(ev_evi[(n - 2) % n_layers])
-                    st.step_attend(q, k, v, td, stream=main, workspace=wss[n % 2])
+                    st.step_attend(q, k, v, td, tf, stream=main, workspace=wss[n % 2])
                     ev_att[l].record(main)
                     side.wait_event(ev_att[l])
-                    st.step_evict(td, tf, stream=side, workspace=wss[n % 2])
+                    st.step_evict(stream=side, workspace=wss[n % 2])
                     ev_evi[l].record(side)
                     td.record_stream(side)
                 n += 1
