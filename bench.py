@@ -37,14 +37,15 @@ def parse():
     ap.add_argument("--layers", type=int, default=None, help="override the number of layers (development only)")
     ap.add_argument("--structured", action="store_true",
                     help="supplementary variant: per-head query means so that eviction happens at w >= 256")
-    ap.add_argument("--streams", type=int, default=2, choices=[1, 2],
-                    help="2: attend on the main stream, record+evict+compact of the same layer on a second stream\n"
-                         "(overlaps the next layer's attend); 1: the fused call on one stream")
+    ap.add_argument("--streams", type=int, default=2, choices=[1, 2, 3, 4],
+                    help="layers are issued round-robin on this many streams (they are independent)")
+    ap.add_argument("--extra-steps", type=int, default=4, help="untimed single-stream steps after the timed region "
+                    "(exclusive measurement of the dominant kernel)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference dispatch for rocprofv3 byte counters)")
-    ap.add_argument("--cpu-units", type=int, default=24)
-    ap.add_argument("--cpu-steps", type=int, default=6)
+    ap.add_argument("--cpu-units", type=int, default=48)
+    ap.add_argument("--cpu-steps", type=int, default=8)
     return ap.parse_args()
 
 
@@ -83,7 +84,7 @@ def main():
         wl = wl.replace(q_mean_scales=inputs.STRUCTURED_Q_MEAN)
     layers = wl.layers if args.layers is None else args.layers
     K_steps, W_steps = args.steps, args.warmup
-    n_dec = W_steps + K_steps
+    n_dec = W_steps + K_steps + args.extra_steps
     n_replay = min(wl.w, wl.P)
     Lcap = Tcap = wl.P + n_dec
     esz = 2 if wl.dtype == "bf16" else 4
@@ -116,15 +117,15 @@ def main():
     log(f"allocated + generated {layers} layers in {time.time() - t0:.1f}s; "
         f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB resident")
 
-    # Launch order of one step.  One stream: the fused call per layer.  Two streams: layer n's attend runs on
-    # the main stream; its record + evict + compact run on a side stream (ordered by events) while the main
-    # stream already attends over the next layer.  Two workspaces alternate, so attend n waits for evict n-2.
+    # Launch order of one step.  --streams 1: every layer's fused step call on one stream.  --streams 2:
+    # layers alternate between two streams, each with its own workspace.  Layers are independent and a
+    # layer always runs on the same stream, so no event is needed; the device overlaps the tail of one
+    # layer's launch (its record / compaction work, which moves few bytes) with the head of the next.
     main = torch.cuda.current_stream()
-    side = torch.cuda.Stream() if args.streams == 2 else None
-    wss = [ws, torch.empty_like(ws)] if side is not None else [ws]
-    ev_att = [torch.cuda.Event() for _ in range(layers)]
-    ev_evi = [torch.cuda.Event() for _ in range(layers)]
-    launch_no = [0]
+    streams = [main] + [torch.cuda.Stream() for _ in range(args.streams - 1)]
+    wss = [ws] + [torch.empty_like(ws) for _ in range(args.streams - 1)]
+    for extra in streams[1:]:
+        extra.wait_stream(main)
 
     def run_step(j, probe_layer=-1, probe_events=None):
         tj = t_all[j]
@@ -132,22 +133,18 @@ def main():
             st = states[l]
             if l == probe_layer:
                 corm.corm_profile_attend(probe_events[0], probe_events[1])
-            if side is None:
-                st.step(Qs[l][j], Kns[l][j], Vns[l][j], tj, t_first)
-                continue
-            n = launch_no[0]
-            if n >= 2:
-                main.wait_event(ev_evi[(n - 2) % layers] if layers > 1 else ev_evi[0])
-            st.step_attend(Qs[l][j], Kns[l][j], Vns[l][j], tj, t_first, stream=main, workspace=wss[n % 2])
-            ev_att[l].record(main)
-            side.wait_event(ev_att[l])
-            st.step_evict(stream=side, workspace=wss[n % 2])
-            ev_evi[l].record(side)
-            launch_no[0] = n + 1
+            k = l % len(streams)
+            corm.corm_decode_step(st.desc, Qs[l][j], Kns[l][j], Vns[l][j], st.K, st.V, st.lens, st.pos, st.last_hit,
+                                  tj, t_first, st.ring, st.out, None, None, wss[k], status=st.status,
+                                  stream=streams[k])
 
     def join():
-        if side is not None:
-            main.wait_stream(side)
+        for extra in streams[1:]:
+            main.wait_stream(extra)
+
+    def fork():
+        for extra in streams[1:]:
+            extra.wait_stream(main)
 
     t0 = time.time()
     for j in range(n_replay):          # prompt tail: seeds the recent-query window; bulk eviction at its end
@@ -183,10 +180,12 @@ def main():
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     ev0.record()
+    fork()
     for k in range(K_steps):
         run_step(n_replay + W_steps + k, probe_layer=k % layers, probe_events=pairs[k])
-        join()                             # the step ends when both streams have finished it
+        join()                             # the step ends when every stream has finished it
         lens_hist[k + 1].copy_(lens_all)   # one tiny copy per step: the live lengths the next step starts from
+        fork()
     ev1.record()
     torch.cuda.synchronize()
     ms_total = ev0.elapsed_time(ev1)
@@ -195,16 +194,36 @@ def main():
     ms_per_step = ms_total / K_steps
     n_launch = K_steps * layers
     ssz = esz
-    # the dominant kernel (attend): algorithmic bytes of the probed launches / their measured durations
-    probe_ms = [hip.elapsed_ms(a, b_) for (a, b_) in pairs]
-    probe_bytes = [algorithmic_bytes(lens_hist[k][k % layers], wl, esz, ssz, "attend") for k in range(K_steps)]
+    # the whole step (every launch of every layer) against its algorithmic bytes
+    total_bytes = sum(algorithmic_bytes(lens_hist[k], wl, esz, ssz) for k in range(K_steps))
+    step_gbs = total_bytes / (ms_total * 1e-3) / 1e9
+    # The dominant kernel (the launch that streams K and V).  With several streams its launches overlap, so
+    # a per-launch event duration also counts the time a launch waits for compute units held by its
+    # neighbour; an exclusive measurement follows the timed region: a few more steps on ONE stream with
+    # events around every such launch.
+    overlapped_ms = sum(hip.elapsed_ms(a, b_) for (a, b_) in pairs) / len(pairs)
+    n_probe_steps = min(4, args.extra_steps)
+    probe_pairs, probe_bytes = [], []
+    for s in range(n_probe_steps):
+        j = n_replay + W_steps + K_steps + s
+        tj = t_all[j]
+        lens_now = lens_all.clone()
+        for l in range(layers):
+            st = states[l]
+            pr = (hip.create(), hip.create())
+            corm.corm_profile_attend(pr[0], pr[1])
+            corm.corm_decode_step(st.desc, Qs[l][j], Kns[l][j], Vns[l][j], st.K, st.V, st.lens, st.pos, st.last_hit,
+                                  tj, t_first, st.ring, st.out, None, None, wss[0], status=st.status, stream=main)
+            probe_pairs.append(pr)
+            probe_bytes.append(algorithmic_bytes(lens_now[l], wl, esz, ssz, "attend"))
+    torch.cuda.synchronize()
+    probe_ms = [hip.elapsed_ms(a, b_) for (a, b_) in probe_pairs]
     avg_attend_ms = sum(probe_ms) / len(probe_ms)
     bytes_per_launch = sum(probe_bytes) / len(probe_bytes)
     achieved = bytes_per_launch / (avg_attend_ms * 1e-3) / 1e9
-    # the whole step (attend + record + compact of every layer) against the same algorithmic bytes
-    total_bytes = sum(algorithmic_bytes(lens_hist[k], wl, esz, ssz) for k in range(K_steps))
-    step_gbs = total_bytes / (ms_total * 1e-3) / 1e9
-    live_end = lens_hist[-1].float().mean().item() / (wl.P + n_dec)
+    live_end = lens_hist[-1].float().mean().item() / (wl.P + W_steps + K_steps)
+    unit_path = corm.corm_selected_path(desc) == 2
+    kernel_name = "corm_unit_kernel" if unit_path else "corm_attend_kernel"
     evicted = int((lens_hist[:-1].long() + 1 - lens_hist[1:].long()).sum().item())
 
     result = {
@@ -220,13 +239,15 @@ def main():
                    "live_fraction_end": live_end, "keys_evicted_in_timed_region": evicted},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "corm_attend_kernel", "bytes_per_launch": bytes_per_launch,
+                     "kernel": kernel_name, "bytes_per_launch": bytes_per_launch,
                      "avg_launch_ms": avg_attend_ms, "launches_probed": len(probe_ms),
-                     "launches": n_launch},
+                     "how": "exclusive: one stream, HIP events around every launch of this kernel, "
+                            f"{n_probe_steps} steps right after the timed region",
+                     "avg_launch_ms_overlapped_in_timed_region": overlapped_ms},
         "whole_step": {"achieved": step_gbs, "unit": "GB/s", "frac": step_gbs / HBM_PEAK_GBS,
-                       "avg_layer_step_ms": ms_total / n_launch,
+                       "avg_layer_step_ms": ms_total / n_launch, "layer_steps": n_launch,
                        "note": "algorithmic bytes of all launches / wall time of the timed region "
-                               "(attend + record + compact kernels and launch gaps)"},
+                               "(every kernel of the step, launch gaps included)"},
         "cpu_baseline": cpu_baseline,
     }
     if cpu_baseline:

@@ -146,10 +146,10 @@ int corm_decode_step(const corm_desc* desc, const void* q, const void* k_new, co
  * layer's attention, the model's GEMMs) on a second stream:
  *   corm_step_attend  append + attend + record + decide (Eq. 1, Eq. 2, Def. 3.1, Def. 4.1): reads the cache
  *                     and lens; writes the new row (K, V, pos, last_hit at slot lens), out, the ring row,
- *                     last_hit of important keys, and the keep flags and per-chunk survivor counts
- *                     (keep array if given, else workspace).  Does NOT change lens.
- *   corm_step_evict   compact (Algorithm 1's gather): moves K, V, pos, last_hit rows, writes lens and,
- *                     if given, kept_idx.  `keep` must be the array passed to corm_step_attend (or NULL).
+ *                     last_hit of important keys, the keep flags (bit masks in the workspace; also one
+ *                     byte per slot in `keep` if given) and per-chunk survivor counts.  Does NOT change lens.
+ *   corm_step_evict   compact (Algorithm 1's gather) from the workspace's keep masks: moves K, V, pos,
+ *                     last_hit rows, writes lens and, if given, kept_idx.
  * corm_decode_step == corm_step_attend then corm_step_evict on one stream, with the same workspace.
  * The caller orders: evict after attend of the same step; the next step's attend of the same cache
  * after evict; no other call may use the workspace between the two phases. */
@@ -158,7 +158,7 @@ int corm_step_attend(const corm_desc* desc, const void* q, const void* k_new, co
                      void* score_ring, float* out, uint8_t* keep, void* workspace, size_t workspace_bytes,
                      int32_t* status, void* stream);
 int corm_step_evict(const corm_desc* desc, void* K, void* V, int32_t* lens, int32_t* pos, int32_t* last_hit,
-                    const uint8_t* keep, int32_t* kept_idx, void* workspace, size_t workspace_bytes, void* stream);
+                    int32_t* kept_idx, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Tuning / test knob (host call, process-wide, not thread safe): how attend + record are launched.
  * 0 = choose by shape (default); 1 = split kernels (several workgroups per unit, partials merged by a
@@ -166,6 +166,10 @@ int corm_step_evict(const corm_desc* desc, void* K, void* V, int32_t* lens, int3
  * Every path produces the same keep mask, indices and cache; out and the recorded scores agree within
  * fp32 rounding. */
 int corm_force_path(int path);
+
+/* The path (1 or 2, see corm_force_path) the attend/step calls take for this descriptor on the current
+ * device; a negative corm_status for a bad descriptor. */
+int corm_selected_path(const corm_desc* desc);
 
 /* Measurement hook (host call, not thread safe): the NEXT corm_decode_attend / corm_step_attend / corm_decode_step call
  * records start_event immediately before and stop_event immediately after its attend launch (the

@@ -22,7 +22,7 @@ CORM_DEV_UNIT_FULL, CORM_DEV_BAD_STEP, CORM_DEV_BAD_LENS = 1, 2, 4
 
 EXPORTS = ("corm_version", "corm_strerror", "corm_workspace_bytes", "corm_workspace_init", "corm_append",
            "corm_decode_attend", "corm_evict_mask", "corm_evict_mask_summary", "corm_compact",
-           "corm_decode_step", "corm_step_attend", "corm_step_evict", "corm_force_path", "corm_profile_attend",
+           "corm_decode_step", "corm_step_attend", "corm_step_evict", "corm_force_path", "corm_selected_path", "corm_profile_attend",
            "corm_threshold")
 
 
@@ -65,8 +65,9 @@ def lib() -> ctypes.CDLL:
         L.corm_compact.argtypes = [dp, vp, vp, i32p, i32p, i32p, vp, i32p, vp, sz, vp]
         L.corm_step_attend.argtypes = [dp, vp, vp, vp, vp, vp, i32p, i32p, i32p, i32p, i32p, vp, vp, vp, vp, sz,
                                        i32p, vp]
-        L.corm_step_evict.argtypes = [dp, vp, vp, i32p, i32p, i32p, vp, i32p, vp, sz, vp]
+        L.corm_step_evict.argtypes = [dp, vp, vp, i32p, i32p, i32p, i32p, vp, sz, vp]
         L.corm_force_path.argtypes = [ctypes.c_int]
+        L.corm_selected_path.argtypes = [dp]
         L.corm_decode_step.argtypes = [dp, vp, vp, vp, vp, vp, i32p, i32p, i32p, i32p, i32p, vp, vp, vp, i32p,
                                        vp, sz, i32p, vp]
         L.corm_threshold.argtypes = [ctypes.c_float, i32p, ctypes.c_int32, vp, vp]
@@ -185,12 +186,18 @@ def corm_step_attend(desc, q, k_new, v_new, K, V, lens, pos, last_hit, t, t_firs
     return _check(rc, "corm_step_attend") if check else rc
 
 
-def corm_step_evict(desc, K, V, lens, pos, last_hit, keep=None, kept_idx=None, workspace=None, workspace_bytes=None,
+def corm_step_evict(desc, K, V, lens, pos, last_hit, kept_idx=None, workspace=None, workspace_bytes=None,
                     stream=None, check=True) -> int:
     rc = lib().corm_step_evict(ctypes.byref(desc), _ptr(K), _ptr(V), _ptr(lens), _ptr(pos), _ptr(last_hit),
-                               _ptr(keep), _ptr(kept_idx), _ptr(workspace), _nbytes(workspace, workspace_bytes),
-                               _stream(stream))
+                               _ptr(kept_idx), _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream))
     return _check(rc, "corm_step_evict") if check else rc
+
+
+def corm_selected_path(desc) -> int:
+    rc = lib().corm_selected_path(ctypes.byref(desc))
+    if rc < 0:
+        raise CormError(rc, "corm_selected_path")
+    return rc
 
 
 def corm_force_path(path: int, check=True) -> int:
@@ -262,7 +269,7 @@ class LayerState:
                          status=self.status, stream=stream)
 
     def step_evict(self, stream=None, workspace=None) -> None:
-        corm_step_evict(self.desc, self.K, self.V, self.lens, self.pos, self.last_hit, self.keep, self.kept_idx,
+        corm_step_evict(self.desc, self.K, self.V, self.lens, self.pos, self.last_hit, self.kept_idx,
                         self.workspace if workspace is None else workspace, stream=stream)
 
     def step(self, q, k_new, v_new, t, t_first, stream=None) -> None:

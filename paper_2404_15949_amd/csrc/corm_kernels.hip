@@ -46,7 +46,8 @@ struct Params {
   const int32_t* t_first;
   void* ring;
   float* out;
-  uint8_t* keep;       // keep flags [B,Hkv,Lcap] (caller's array or workspace)
+  uint8_t* keep;       // optional: the caller's keep flags [B,Hkv,Lcap], one byte per slot
+  unsigned long long* keepbits;  // keep flags as wave ballots [B*Hkv, ceil(Lcap/64)] (workspace)
   int32_t* kept_idx;   // optional
   int32_t* counts;     // survivors per (unit, split)
   float* partials;     // [B*Hq, nsplit, d+2]
@@ -55,7 +56,7 @@ struct Params {
   int32_t B, Hq, Hkv, Lcap, Tcap, w, r, nsplit;
   float thr_scale, scale_log2;
   int32_t do_append, do_evict, ring_bf16;
-  int32_t keep_always;  // write every keep flag (the caller asked for the mask), not only from the first hole on
+  int32_t kb_stride;    // 64-bit words per unit in keepbits
 };
 
 // ---------------------------------------------------------------- small device helpers
@@ -425,6 +426,7 @@ __global__ __launch_bounds__(WG) void corm_attend_kernel(const Params p) {
 
 constexpr int UNIT_WG = 512;
 constexpr int UNIT_WAVES = UNIT_WG / 64;
+constexpr int UNIT_MAX_TILES = 24;   // 48 KiB of logits hold at most 12288 slots = 24 tiles of 512
 static_assert(UNIT_WG == CHUNK, "the unit kernel reports survivors per CHUNK slots, one tile each");
 
 template <typename DT, int D, int G>
@@ -437,7 +439,7 @@ __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, cons
   __shared__ float sh_z[G][UNIT_WAVES];
   __shared__ float sh_acc[G][UNIT_WAVES][D];
   __shared__ float sh_M[G], sh_Z[G];
-  __shared__ int sh_cnt[UNIT_WAVES];
+  __shared__ int sh_tilecnt[UNIT_MAX_TILES];
 
   const int unit = blockIdx.x;
   const UnitLen ul = unit_len(p, unit);
@@ -479,6 +481,11 @@ __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, cons
     }
     __syncthreads();
   }
+
+  // metadata of the first record tile, fetched now and used after the stream
+  int pos_next = posb[min(tid, L - 1)];
+  int lh_next = lhb[min(tid, L - 1)];
+  if (tid < UNIT_MAX_TILES) sh_tilecnt[tid] = 0;
 
   uint4 qreg[G];
 #pragma unroll
@@ -571,22 +578,34 @@ __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, cons
   }
   __syncthreads();
 
-  // record (Def. 3.1) and decide (Def. 4.1 + recent r)
+  // record (Def. 3.1) and decide (Def. 4.1 + recent r).  The metadata of the next tile is loaded
+  // while the current one is processed; survivors per tile are summed with LDS atomics, so the
+  // loop has no barrier.
   const bool step_ok = tcur >= 1 && tcur <= p.Tcap;
   if (!step_ok && tid == 0 && p.status) atomicOr(p.status, CORM_DEV_BAD_STEP);
   const int slot = step_ok ? (tcur - 1) % p.w : 0;
   const float thr = importance_threshold(p.thr_scale, step_ok ? tcur : 1);
   const int tfirst = p.do_evict ? p.t_first[b] : tcur;
   const bool full = p.do_evict && step_ok && (tcur - tfirst + 1 >= p.w);
-  uint8_t* keepb = p.keep + (size_t)unit * p.Lcap;
-  bool write_keep = p.keep_always != 0;   // else only from the first tile that lost a key
-  for (int tile = 0; tile < L; tile += UNIT_WG) {
+  uint8_t* keepb = p.keep ? p.keep + (size_t)unit * p.Lcap : nullptr;
+  unsigned long long* bitsb = p.keepbits + (size_t)unit * p.kb_stride;
+  // (fully unrolled up to the largest tile count the LDS budget allows: straight-line code keeps the
+  // wait counts exact, so a tile's stores are never waited for before the next tile starts)
+#pragma unroll
+  for (int kt = 0; kt < UNIT_MAX_TILES; ++kt) {
+    const int tile = kt * UNIT_WG;
+    if (tile >= L) break;
     const int i = tile + tid;
     const bool live = i < L;
+    const int my_pos = pos_next;
+    int lh = lh_next;
+    if (kt + 1 < UNIT_MAX_TILES) {   // clamped index: always a live slot, no branch around the load
+      const int in = min(i + UNIT_WG, L - 1);
+      pos_next = posb[in];
+      lh_next = lhb[in];
+    }
     bool keep = false;
     if (live) {
-      const int my_pos = posb[i];
-      int lh = lhb[i];
       const bool pos_ok = my_pos >= 0 && my_pos < p.Tcap;
       if (!pos_ok && p.status) atomicOr(p.status, CORM_DEV_BAD_STEP);
       bool hit = false;
@@ -610,18 +629,20 @@ __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, cons
         lhb[i] = tcur;
       }
       keep = !full || (lh > tcur - p.w) || (i >= L - p.r);
+      if (p.do_evict && keepb) keepb[i] = keep ? 1 : 0;
     }
-    if (!p.do_evict) continue;
-    const int cnt = __popcll(__ballot(keep));
-    if (lane == 0) sh_cnt[wv] = cnt;
+    if (p.do_evict) {
+      const unsigned long long bal = __ballot(keep);
+      if (lane == 0 && tile + wv * 64 < L) {
+        bitsb[(tile >> 6) + wv] = bal;
+        atomicAdd(&sh_tilecnt[tile / CHUNK], __popcll(bal));
+      }
+    }
+  }
+  if (p.do_evict) {
     __syncthreads();
-    int tot = 0;
-#pragma unroll
-    for (int k = 0; k < UNIT_WAVES; ++k) tot += sh_cnt[k];
-    write_keep = write_keep || tot < min(UNIT_WG, L - tile);
-    if (write_keep && live) keepb[i] = keep ? 1 : 0;
-    if (tid == 0) p.counts[(size_t)unit * p.nsplit + tile / CHUNK] = tot;
-    __syncthreads();
+    const int ntile = (L + CHUNK - 1) / CHUNK;
+    if (tid < ntile) p.counts[(size_t)unit * p.nsplit + tid] = sh_tilecnt[tid];
   }
 }
 
@@ -711,7 +732,8 @@ __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const i
   const int slot = step_ok ? (tcur - 1) % p.w : 0;
   const float thr = importance_threshold(p.thr_scale, step_ok ? tcur : 1);
   const bool full = p.do_evict && step_ok && (tcur - tfirst + 1 >= p.w);
-  uint8_t* keepb = p.keep + (size_t)unit * p.Lcap;
+  uint8_t* keepb = p.keep ? p.keep + (size_t)unit * p.Lcap : nullptr;
+  unsigned long long* bitsb = p.keepbits + (size_t)unit * p.kb_stride;
 
   int kept = 0;
 #pragma unroll
@@ -744,9 +766,11 @@ __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const i
         lhb[i] = tcur;
       }
       keep = !full || (lh > tcur - p.w) || (i >= L - p.r);
-      if (p.do_evict) keepb[i] = keep ? 1 : 0;
+      if (p.do_evict && keepb) keepb[i] = keep ? 1 : 0;
     }
-    kept += __popcll(__ballot(keep));
+    const unsigned long long bal = __ballot(keep);
+    if (p.do_evict && lane == 0 && cbeg + k * WG + wv * 64 < cend) bitsb[((cbeg + k * WG) >> 6) + wv] = bal;
+    kept += __popcll(bal);
   }
   if (p.do_evict) {
     if (lane == 0) sh_cnt[wv] = kept;
@@ -793,13 +817,14 @@ struct CompactArgs {
   int32_t* pos;
   int32_t* last_hit;
   int32_t* lens;
-  const uint8_t* keep;
+  const uint8_t* keep;      // caller's byte mask (corm_compact only)
+  unsigned long long* keepbits;  // [units, kb_stride] wave ballots
   int32_t* kept_idx;        // optional
   const int32_t* counts;    // [units, nsplit]
   char* stage_k;            // [units, nsplit, STAGE_ROWS, ROWB]
   char* stage_v;
   int32_t* stage_meta;      // [units, nsplit, STAGE_ROWS, 2] (pos, last_hit)
-  int32_t nsplit, Lcap, do_append;
+  int32_t nsplit, Lcap, do_append, kb_stride;
 };
 
 // Moves the n_rows survivors listed in src_of (ascending) to consecutive destinations starting at
@@ -878,7 +903,7 @@ __device__ __forceinline__ int compact_unit_len(const CompactArgs& a, int unit) 
   return L;
 }
 
-// survivors per split -> keep-flag counts, for callers that come with a mask only (corm_compact)
+// a caller's byte mask (corm_compact) -> wave ballots and survivors per split
 __global__ __launch_bounds__(WG) void corm_count_kernel(const CompactArgs a, int32_t* counts) {
   __shared__ int sh_cnt[WAVES];
   const int split = blockIdx.x, unit = blockIdx.y;
@@ -887,9 +912,16 @@ __global__ __launch_bounds__(WG) void corm_count_kernel(const CompactArgs a, int
   if (cbeg >= L) return;
   const int cend = min(cbeg + CHUNK, L);
   const uint8_t* keepb = a.keep + (size_t)unit * a.Lcap;
+  unsigned long long* bitsb = a.keepbits + (size_t)unit * a.kb_stride;
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   int kept = 0;
-  for (int i = cbeg + threadIdx.x; i < cbeg + CHUNK; i += WG) kept += __popcll(__ballot(i < cend && keepb[i] != 0));
-  if ((threadIdx.x & 63) == 0) sh_cnt[threadIdx.x >> 6] = kept;
+  for (int i0 = cbeg; i0 < cbeg + CHUNK; i0 += WG) {
+    const int i = i0 + threadIdx.x;
+    const unsigned long long bal = __ballot(i < cend && keepb[i] != 0);
+    if (lane == 0 && i0 + wv * 64 < cend) bitsb[(i0 >> 6) + wv] = bal;
+    kept += __popcll(bal);
+  }
+  if (lane == 0) sh_cnt[wv] = kept;
   __syncthreads();
   if (threadIdx.x == 0) {
     int tot = 0;
@@ -938,7 +970,7 @@ __global__ __launch_bounds__(WG) void corm_compact_local_kernel(const CompactArg
   char* Vb = a.V + (size_t)unit * a.Lcap * ROWB;
   int32_t* posb = a.pos + (size_t)unit * a.Lcap;
   int32_t* lhb = a.last_hit + (size_t)unit * a.Lcap;
-  const uint8_t* keepb = a.keep + (size_t)unit * a.Lcap;
+  const unsigned long long* bitsb = a.keepbits + (size_t)unit * a.kb_stride;
   const size_t stage_row0 = ((size_t)unit * a.nsplit + split) * STAGE_ROWS;
   char* sk = a.stage_k + stage_row0 * ROWB;
   char* sv = a.stage_v + stage_row0 * ROWB;
@@ -950,7 +982,7 @@ __global__ __launch_bounds__(WG) void corm_compact_local_kernel(const CompactArg
     // a chunk whose count equals its size lost nothing: its flags are implied (and may be unwritten)
     const int ch = tile / CHUNK;
     const bool chunk_full = cnt[ch] == min(CHUNK, L - ch * CHUNK);
-    const bool kp = i < cend && (chunk_full || keepb[i] != 0);
+    const bool kp = i < cend && (chunk_full || ((bitsb[i >> 6] >> (i & 63)) & 1ull) != 0);
     int my_pos = 0, my_lh = 0;
     if (kp) {
       my_pos = posb[i];
@@ -1113,8 +1145,8 @@ __global__ void corm_fill_i32_kernel(int32_t* p, size_t n, int32_t v) {
 // ---------------------------------------------------------------- host side
 
 struct WorkspaceLayout {
-  size_t counts_off, keep_off, partials_off, logits_off, stage_meta_off, stage_k_off, stage_v_off, total;
-  int nsplit;
+  size_t counts_off, keepbits_off, partials_off, logits_off, stage_meta_off, stage_k_off, stage_v_off, total;
+  int nsplit, kb_stride;
 };
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -1127,8 +1159,9 @@ WorkspaceLayout workspace_layout(const corm_desc& d) {
   const size_t units = (size_t)d.B * d.Hkv, heads = (size_t)d.B * d.Hq;
   const size_t stage_rows = units * w.nsplit * STAGE_ROWS;
   w.counts_off = 0;
-  w.keep_off = align_up(units * w.nsplit * sizeof(int32_t), 256);
-  w.partials_off = align_up(w.keep_off + units * d.Lcap, 256);
+  w.kb_stride = (d.Lcap + 63) / 64;
+  w.keepbits_off = align_up(units * w.nsplit * sizeof(int32_t), 256);
+  w.partials_off = align_up(w.keepbits_off + units * w.kb_stride * sizeof(unsigned long long), 256);
   w.logits_off = align_up(w.partials_off + heads * w.nsplit * (d.d + 2) * sizeof(float), 256);
   w.stage_meta_off = align_up(w.logits_off + heads * d.Lcap * sizeof(float), 256);
   w.stage_k_off = align_up(w.stage_meta_off + stage_rows * 2 * sizeof(int32_t), 256);
@@ -1173,7 +1206,8 @@ int check_workspace(const corm_desc* d, void* workspace, size_t workspace_bytes,
 void bind_params(const corm_desc* d, const WorkspaceLayout& wl, void* workspace, Params& p) {
   char* ws = reinterpret_cast<char*>(workspace);
   p.counts = reinterpret_cast<int32_t*>(ws + wl.counts_off);
-  if (!p.keep) p.keep = reinterpret_cast<uint8_t*>(ws + wl.keep_off);
+  p.keepbits = reinterpret_cast<unsigned long long*>(ws + wl.keepbits_off);
+  p.kb_stride = wl.kb_stride;
   p.partials = reinterpret_cast<float*>(ws + wl.partials_off);
   p.logits = reinterpret_cast<float*>(ws + wl.logits_off);
   p.B = d->B; p.Hq = d->Hq; p.Hkv = d->Hkv; p.Lcap = d->Lcap; p.Tcap = d->Tcap; p.w = d->w; p.r = d->r;
@@ -1304,6 +1338,8 @@ int launch_compact(const corm_desc* d, const WorkspaceLayout& wl, void* workspac
   a.K = reinterpret_cast<char*>(K);
   a.V = reinterpret_cast<char*>(V);
   a.pos = pos; a.last_hit = last_hit; a.lens = lens; a.keep = keep; a.kept_idx = kept_idx;
+  a.keepbits = reinterpret_cast<unsigned long long*>(ws + wl.keepbits_off);
+  a.kb_stride = wl.kb_stride;
   int32_t* counts = reinterpret_cast<int32_t*>(ws + wl.counts_off);
   a.counts = counts;
   a.stage_k = ws + wl.stage_k_off;
@@ -1477,14 +1513,14 @@ int corm_step_attend(const corm_desc* desc, const void* q, const void* k_new, co
   Params p = {};
   p.q = q; p.k_new = k_new; p.v_new = v_new; p.K = K; p.V = V; p.lens = const_cast<int32_t*>(lens); p.pos = pos;
   p.last_hit = last_hit; p.t = t; p.t_first = t_first; p.ring = score_ring; p.out = out; p.keep = keep;
-  p.keep_always = keep != nullptr; p.status = status;
+  p.status = status;
   p.do_append = 1; p.do_evict = 1;
   bind_params(desc, wl, workspace, p);
   return launch_attend_record(desc, p, (hipStream_t)stream);
 }
 
 int corm_step_evict(const corm_desc* desc, void* K, void* V, int32_t* lens, int32_t* pos, int32_t* last_hit,
-                    const uint8_t* keep, int32_t* kept_idx, void* workspace, size_t workspace_bytes, void* stream) {
+                    int32_t* kept_idx, void* workspace, size_t workspace_bytes, void* stream) {
   int rc = validate_desc(desc);
   if (rc) return rc;
   if (!K || !V || !pos || !last_hit || !lens) return CORM_EINVAL;
@@ -1494,8 +1530,7 @@ int corm_step_evict(const corm_desc* desc, void* K, void* V, int32_t* lens, int3
   WorkspaceLayout wl;
   rc = check_workspace(desc, workspace, workspace_bytes, &wl);
   if (rc) return rc;
-  if (!keep) keep = reinterpret_cast<const uint8_t*>(reinterpret_cast<char*>(workspace) + wl.keep_off);
-  return launch_compact(desc, wl, workspace, K, V, pos, last_hit, lens, keep, kept_idx, 1, false,
+  return launch_compact(desc, wl, workspace, K, V, pos, last_hit, lens, nullptr, kept_idx, 1, false,
                         (hipStream_t)stream);
 }
 
@@ -1509,7 +1544,13 @@ int corm_decode_step(const corm_desc* desc, const void* q, const void* k_new, co
   rc = corm_step_attend(desc, q, k_new, v_new, K, V, lens, pos, last_hit, t, t_first, score_ring, out, keep,
                         workspace, workspace_bytes, status, stream);
   if (rc) return rc;
-  return corm_step_evict(desc, K, V, lens, pos, last_hit, keep, kept_idx, workspace, workspace_bytes, stream);
+  return corm_step_evict(desc, K, V, lens, pos, last_hit, kept_idx, workspace, workspace_bytes, stream);
+}
+
+int corm_selected_path(const corm_desc* desc) {
+  const int rc = validate_desc(desc);
+  if (rc) return rc;
+  return use_unit_path(desc) ? 2 : 1;
 }
 
 int corm_force_path(int path) {
