@@ -64,6 +64,23 @@ def algorithmic_bytes(lens_before, wl, esz, ssz, part="step"):
     return float((L * per_key).sum().item() + L.numel() * per_unit)
 
 
+def measured_traffic(kernel, workload, bytes_per_launch):
+    """HBM bytes per launch from the committed rocprofv3 counter summary (FETCH_SIZE + WRITE_SIZE, calibrated
+    against a plain copy), scaled from that run's algorithmic bytes per launch to this run's; None if there is
+    no summary for this kernel and workload."""
+    path = os.path.join(ROOT, "profiles", "unit_kernel_llama7b_b16_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch="):
+                kv = dict(item.split("=") for item in line.split())
+                if kv["kernel"] == kernel and kv["workload"] == workload:
+                    return float(kv["traffic_bytes_per_launch"]) / float(kv["algorithmic_bytes_per_launch"]) \
+                        * bytes_per_launch
+    except OSError:
+        pass
+    return None
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -238,7 +255,8 @@ def main():
                    "prompt": wl.P, "w": wl.w, "r": wl.r, "tokens_per_step": B, "streams": args.streams,
                    "live_fraction_end": live_end, "keys_evicted_in_timed_region": evicted},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": measured_traffic(kernel_name, wl.name, bytes_per_launch),
                      "kernel": kernel_name, "bytes_per_launch": bytes_per_launch,
                      "avg_launch_ms": avg_attend_ms, "launches_probed": len(probe_ms),
                      "how": "exclusive: one stream, HIP events around every launch of this kernel, "
