@@ -160,3 +160,45 @@ def oracle_from_snapshot(st: corm.LayerState, b: int, h: int, t_prev: int, t_fir
     """Rebuild the oracle state of unit (b,h) from device memory as it stands after step t_prev."""
     return unit_from_device_arrays(st.K, st.V, st.pos, st.lens, st.ring, b, h, st.Hq // st.Hkv, st.w, st.r,
                                    t_prev, t_first, dtype, thr_scale)
+
+
+def snapshot_step_check(st: corm.LayerState, wl: inputs.Workload, q, k, v, t: int, t_first: int,
+                        units: Sequence[Tuple[int, int]], thr_scale: float = 1.0) -> Dict:
+    """One device step checked against oracles rebuilt from the device state just before it.
+
+    q, k, v: this step's device inputs ([B,Hq,d], [B,Hkv,d]); the state `st` must have keep/kept_idx arrays.
+    Compares, for every listed unit: keep mask, kept indices, lens', the compacted K/V/pos rows (bit for
+    bit, the oracle being fed the scores the device recorded) and `out` / recorded scores within tolerance.
+    """
+    dev = st.K.device
+    G = wl.G
+    oracles = {u: oracle_from_snapshot(st, u[0], u[1], t - 1, t_first, wl.dtype, thr_scale) for u in units}
+    t_dev = torch.full((wl.B,), t, dtype=torch.int32, device=dev)
+    tf_dev = torch.full((wl.B,), t_first, dtype=torch.int32, device=dev)
+    st.step(q, k, v, t_dev, tf_dev)
+    torch.cuda.synchronize()
+    assert int(st.status.item()) == 0
+    slot = (t - 1) % wl.w
+    tol = OUT_TOL[wl.dtype]
+    worst = 0.0
+    evicted = 0
+    for (b, h) in units:
+        u = oracles[(b, h)]
+        live_pos = np.concatenate([u.positions, [t - 1]])
+        pos_t = torch.from_numpy(live_pos).to(dev)
+        recorded = _f32(st.ring[b, h * G:(h + 1) * G, slot].index_select(1, pos_t))
+        res = u.step(_f32(q[b, h * G:(h + 1) * G]), _f32(k[b, h]), _f32(v[b, h]), t, recorded=recorded)
+        l = len(live_pos)
+        assert np.array_equal(st.keep[b, h, :l].cpu().numpy().astype(bool), res["keep"]), ("keep", t, b, h)
+        assert int(st.lens[b, h].item()) == u.l, ("lens", t, b, h)
+        assert np.array_equal(st.kept_idx[b, h, :u.l].cpu().numpy().astype(np.int64), res["indices"]), ("idx", t, b, h)
+        evicted += l - u.l
+        for g in range(G):
+            e = out_rel_err(st.out[b, h * G + g].cpu().numpy().astype(np.float64), res["out"][g])
+            worst = max(worst, e)
+            assert e <= tol, ("out", t, b, h, g, e)
+            a = res["alpha"][g]
+            err = np.abs(recorded[g].astype(np.float64) - a)
+            assert (err <= SCORE_RTOL[wl.dtype] * a + SCORE_ATOL_OF_MAX[wl.dtype] * a.max()).all(), ("score", t, b, h, g)
+        check_unit_state(st, b, h, u, t)
+    return {"worst_out_rel_err": worst, "evicted": evicted}

@@ -1,0 +1,104 @@
+"""Parity at the benchmark definition's full per-layer sizes, in the launch configuration bench.py times:
+the device runs every unit; a sample of units is checked against oracles rebuilt from the device state
+(snapshot mode), step by step, bit for bit on masks / indices / cache rows and within tolerance on out."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2404_15949_amd import corm, inputs
+from tests import harness
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+W = inputs.WORKLOADS
+
+
+def say(*a):
+    print("[case]", *a, flush=True)
+    sys.stdout.flush()
+
+
+def _run(wl, layer, n_decode, check_steps, units, expect_path=None, expect_evictions=False):
+    say("full size", wl.name, "layer", layer, "B", wl.B, "Hq/Hkv", wl.Hq, wl.Hkv, "P", wl.P, "w", wl.w,
+        "q_mean", bool(wl.q_mean_scales))
+    n_replay = min(wl.w, wl.P)
+    x = inputs.make_layer(wl, layer, device=DEV, n_decode=n_decode, n_replay=n_replay)
+    st = harness.make_state(wl, DEV, Lcap=wl.P + n_decode, Tcap=wl.P + n_decode)
+    if expect_path is not None:
+        assert corm.corm_selected_path(st.desc) == expect_path
+    pre = wl.P - n_replay
+    st.preload(x["K0"][:, :, :pre], x["V0"][:, :, :pre])
+    tf = torch.full((wl.B,), pre + 1, dtype=torch.int32, device=DEV)
+    # the prompt tail: all but its last position unchecked (the last one carries the bulk eviction)
+    for j in range(n_replay - 1):
+        q, k, v, t = harness.step_inputs(wl, x, j, n_replay)
+        st.step(q, k, v, torch.full((wl.B,), t, dtype=torch.int32, device=DEV), tf)
+    torch.cuda.synchronize()
+    assert int(st.status.item()) == 0
+    total_evicted = 0
+    worst = 0.0
+    for j in range(n_replay - 1, n_replay + n_decode):
+        q, k, v, t = harness.step_inputs(wl, x, j, n_replay)
+        if j in check_steps or j == n_replay - 1:
+            rep = harness.snapshot_step_check(st, wl, q, k, v, t, pre + 1, units)
+            total_evicted += rep["evicted"]
+            worst = max(worst, rep["worst_out_rel_err"])
+            say("step", j, "t", t, rep)
+        else:
+            st.step(q, k, v, torch.full((wl.B,), t, dtype=torch.int32, device=DEV), tf)
+    torch.cuda.synchronize()
+    assert int(st.status.item()) == 0
+    lens = st.lens.cpu().numpy()
+    say("final live fraction", float(lens.mean()) / (wl.P + n_decode), "min", int(lens.min()), "max", int(lens.max()))
+    if expect_evictions:
+        assert total_evicted > 0 and lens.min() < wl.P
+    return lens
+
+
+def _sample_units(wl, n, seed=0):
+    rng = np.random.default_rng(seed)
+    return sorted({(int(rng.integers(wl.B)), int(rng.integers(wl.Hkv))) for _ in range(n)})
+
+
+def test_config2_llama7b_one_layer():
+    wl = W["llama7b_1layer"]
+    n_replay = wl.w
+    _run(wl, 0, 6, {n_replay, n_replay + 3, n_replay + 5}, _sample_units(wl, 4), expect_path=1)
+
+
+@pytest.mark.parametrize("layer", [0, 2])
+def test_config3_llama7b_batch16_layer(layer):
+    """One dense (0) and one sparse (2) layer of the full stack; the launch is exactly the one bench.py times."""
+    wl = W["llama7b_b16"]
+    n_replay = wl.w
+    _run(wl, layer, 5, {n_replay, n_replay + 4}, _sample_units(wl, 5, seed=layer), expect_path=2)
+
+
+def test_config3_structured_queries_evict_and_compact():
+    """Same shape with per-head query means: heads diverge (live fraction ~0.3-0.97), every step evicts,
+    the bulk eviction at the end of the prompt takes the serial compaction path, decode steps the parallel one."""
+    wl = W["llama7b_b16"].replace(q_mean_scales=inputs.STRUCTURED_Q_MEAN)
+    n_replay = wl.w
+    lens = _run(wl, 2, 6, {n_replay, n_replay + 1, n_replay + 5}, _sample_units(wl, 6, seed=5), expect_path=2,
+                expect_evictions=True)
+    assert lens.max() - lens.min() > 1000
+
+
+def test_config4_long_context():
+    wl = W["long32k"]
+    n_replay = wl.w
+    _run(wl, 0, 3, {n_replay + 2}, [(0, 0), (3, 31)], expect_path=1)
+
+
+def test_config5_gqa():
+    wl = W["gqa_llama3"]
+    n_replay = wl.w
+    _run(wl, 0, 4, {n_replay, n_replay + 3}, _sample_units(wl, 3), expect_path=1)
+
+
+def test_config5_gqa_structured_evicts():
+    wl = W["gqa_llama3"].replace(q_mean_scales=(3.0, 5.0), key_scale=1.5)
+    n_replay = wl.w
+    _run(wl, 0, 4, {n_replay, n_replay + 3}, _sample_units(wl, 3, seed=2), expect_path=1, expect_evictions=True)
