@@ -162,7 +162,8 @@ int corm_step_evict(const corm_desc* desc, void* K, void* V, int32_t* lens, int3
 
 /* Tuning / test knob (host call, process-wide, not thread safe): how attend + record are launched.
  * 0 = choose by shape (default); 1 = split kernels (several workgroups per unit, partials merged by a
- * second launch); 2 = one workgroup per unit with the logits in LDS (taken only if they fit).
+ * second launch; grouped bf16 d=128 queries take q.K^T on the matrix cores); 2 = one workgroup per unit
+ * with the logits in LDS (taken only if they fit); 3 = as 1 but q.K^T always on the vector ALU.
  * Every path produces the same keep mask, indices and cache; out and the recorded scores agree within
  * fp32 rounding. */
 int corm_force_path(int path);

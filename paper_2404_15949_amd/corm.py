@@ -201,7 +201,7 @@ def corm_selected_path(desc) -> int:
 
 
 def corm_force_path(path: int, check=True) -> int:
-    """0 = by shape, 1 = split kernels, 2 = one workgroup per unit."""
+    """0 = by shape, 1 = split kernels, 2 = one workgroup per unit, 3 = split kernels without MFMA."""
     rc = lib().corm_force_path(path)
     return _check(rc, "corm_force_path") if check else rc
 

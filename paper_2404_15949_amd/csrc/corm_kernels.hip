@@ -416,6 +416,240 @@ __global__ __launch_bounds__(WG) void corm_attend_kernel(const Params p) {
   }
 }
 
+// ---------------------------------------------------------------- attend, grouped queries: q.K^T on MFMA
+//
+// bf16, d = 128, G query heads per KV head.  Per stage a wave owns a tile of 16 consecutive keys.
+// K is loaded straight into the A-operand layout of v_mfma_f32_16x16x32_bf16 (lane l: key l%16, the 8
+// elements 32*kb + 8*(l/16) .. +8 of block kb: 64 contiguous bytes of a row per load), the G queries
+// sit in columns 0..G-1 of the B operand (the other columns are zero), and four MFMAs give the 16 x G
+// logits of the tile without any cross-lane reduction: lane (n = l%16 < G, lg = l/16) holds the logits
+// of head n for keys 4*lg .. 4*lg+3.  The softmax bookkeeping runs in those lanes (all heads at once),
+// the probabilities go through a per-wave LDS tile to the lanes that hold V in the row layout
+// (lane l: row l/16 of a load, 16-byte column slice l%16), and p.V stays on the vector ALU.
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+template <int G>
+struct AttendGqa {
+  static constexpr int D = 128, ROWB = 256, EPL = 8;
+  static constexpr int TILE = 16;                    // keys per wave and stage
+  static constexpr int STAGE_ROWS = WAVES * TILE;    // keys per workgroup and stage
+
+  struct Stage {
+    uint4 k[4];  // A operand, k-blocks 0..3
+    uint4 v[4];  // rows 4*j + lane/16 of the tile, this lane's 16-byte column slice
+  };
+
+  __device__ static __forceinline__ void load(Stage& st, __amdgpu_buffer_rsrc_t rk, __amdgpu_buffer_rsrc_t rv,
+                                              uint32_t koff, uint32_t voff) {
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) st.k[kb] = buffer_load16(rk, koff + (uint32_t)(64 * kb));
+#pragma unroll
+    for (int j = 0; j < 4; ++j) st.v[j] = buffer_load16(rv, voff + (uint32_t)(j * 4 * ROWB));
+  }
+
+  // row0: first key of this wave's tile; lrel0: its index in the logit staging array
+  __device__ static __forceinline__ void compute(const Stage& st, int row0, int lrel0, int cend, int n, int lg,
+                                                 const uint4 (&qb)[4], float scale_log2, float* sh_logit,
+                                                 int lstride, float* sh_p, float* sh_alpha, float& m_run,
+                                                 float& z_run, float (&acc)[G][EPL]) {
+    f32x4_t d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb)
+      d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, st.k[kb]),
+                                                  __builtin_bit_cast(bf16x8_t, qb[kb]), d, 0, 0, 0);
+    float s[4];
+    float tmax = neg_inf();
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const float v = d[r] * scale_log2;
+      d[r] = v;
+      s[r] = (row0 + 4 * lg + r) < cend ? v : neg_inf();
+      tmax = fmaxf(tmax, s[r]);
+    }
+    // the 16 keys of head n are spread over the four lane groups
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+    const float mnew = fmaxf(m_run, tmax);
+    const float msafe = mnew == neg_inf() ? 0.f : mnew;
+    const float a = fast_exp2(m_run - msafe);
+    float pr[4];
+    float zs = 0.f;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      pr[r] = fast_exp2(s[r] - msafe);
+      zs += pr[r];
+    }
+    z_run = fmaf(z_run, a, zs);
+    m_run = mnew;
+    if (n < G) {
+      *reinterpret_cast<float4*>(&sh_logit[n * lstride + lrel0 + 4 * lg]) = make_float4(d[0], d[1], d[2], d[3]);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) sh_p[(4 * lg + r) * G + n] = pr[r];
+      if (lg == 0) sh_alpha[n] = a;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // LDS is in order within a wave: compiler fence only
+    // p.V for the rows this lane holds: row 4*j + lg of the tile in load j
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const float ag = sh_alpha[g];
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) acc[g][e] *= ag;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) BF16::axpy(acc[g], sh_p[(4 * j + lg) * G + g], st.v[j]);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  }
+};
+
+template <int G>
+__global__ __launch_bounds__(WG) void corm_attend_gqa_kernel(const Params p) {
+  using A = AttendGqa<G>;
+  constexpr int D = A::D, ROWB = A::ROWB, EPL = A::EPL, LPR = 16;
+
+  const int split = blockIdx.x;
+  const int unit = blockIdx.y;
+  const UnitLen ul = unit_len(p, unit);
+  const int L = ul.L;
+  if (split * CHUNK >= L) return;
+
+  const int b = unit / p.Hkv;
+  const int hkv = unit - b * p.Hkv;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wv = tid >> 6;
+  const int n = lane & 15, lg = lane >> 4;   // MFMA column / lane group; also: 16-byte column slice / row in a V load
+
+  __shared__ float sh_m[G][WAVES];
+  __shared__ float sh_z[G][WAVES];
+  __shared__ float sh_acc[G][WAVES][D];
+  __shared__ float sh_logit[G][CHUNK];
+  __shared__ __attribute__((aligned(16))) float sh_p[WAVES][A::TILE * G];
+  __shared__ __attribute__((aligned(16))) float sh_alpha[WAVES][G];
+
+  char* Kb = reinterpret_cast<char*>(p.K) + (size_t)unit * p.Lcap * ROWB;
+  char* Vb = reinterpret_cast<char*>(p.V) + (size_t)unit * p.Lcap * ROWB;
+  const int hq0 = hkv * G;
+  const int cbeg = split * CHUNK;
+  const int cend = min(cbeg + CHUNK, L);
+
+  if (ul.appended && ul.L0 >= cbeg) {   // this workgroup owns the new slot: write it, then read it back
+    if (wv == 0) {
+      if (lane < LPR) {
+        const char* knew = reinterpret_cast<const char*>(p.k_new) + (size_t)unit * ROWB;
+        const char* vnew = reinterpret_cast<const char*>(p.v_new) + (size_t)unit * ROWB;
+        const uint4 kx = *reinterpret_cast<const uint4*>(knew + (size_t)lane * 16);
+        const uint4 vx = *reinterpret_cast<const uint4*>(vnew + (size_t)lane * 16);
+        *reinterpret_cast<uint4*>(Kb + (size_t)ul.L0 * ROWB + (size_t)lane * 16) = kx;
+        *reinterpret_cast<uint4*>(Vb + (size_t)ul.L0 * ROWB + (size_t)lane * 16) = vx;
+      }
+      if (lane == 0) {
+        p.pos[(size_t)unit * p.Lcap + ul.L0] = p.t[b] - 1;
+        p.last_hit[(size_t)unit * p.Lcap + ul.L0] = 0;
+      }
+    }
+    __syncthreads();
+  }
+
+  // B operand: column n < G holds query head n, elements 32*kb + 8*lg .. +8 in block kb
+  uint4 qb[4];
+#pragma unroll
+  for (int kb = 0; kb < 4; ++kb) {
+    qb[kb] = make_uint4(0u, 0u, 0u, 0u);
+    if (n < G)
+      qb[kb] = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(p.q) +
+                                               ((size_t)(b * p.Hq + hq0 + n) * ROWB + (size_t)(64 * kb + 16 * lg)));
+  }
+
+  float m_run = neg_inf(), z_run = 0.f;   // of head n, in the lanes with n < G (equal across lane groups)
+  float acc[G][EPL];
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+  float* logit_u = p.logits + (size_t)(b * p.Hq + hq0) * p.Lcap;
+
+  const __amdgpu_buffer_rsrc_t rk = make_rsrc(Kb, (uint32_t)cend * ROWB);
+  const __amdgpu_buffer_rsrc_t rv = make_rsrc(Vb, (uint32_t)cend * ROWB);
+  const int tile0 = cbeg + wv * A::TILE;   // first key of this wave's tile in stage 0
+  const uint32_t koff = (uint32_t)(tile0 + n) * ROWB + (uint32_t)(16 * lg);
+  const uint32_t voff = (uint32_t)(tile0 + lg) * ROWB + (uint32_t)(16 * n);
+  constexpr uint32_t STAGE_BYTES = (uint32_t)A::STAGE_ROWS * ROWB;
+  constexpr int PAIRS = CHUNK / (2 * A::STAGE_ROWS);
+  static_assert(PAIRS >= 1 && CHUNK % (2 * A::STAGE_ROWS) == 0, "CHUNK must hold whole stage pairs");
+
+  typename A::Stage s0, s1;
+  A::load(s0, rk, rv, koff, voff);
+#pragma unroll
+  for (int i = 0; i < PAIRS; ++i) {
+    const int it = cbeg + i * 2 * A::STAGE_ROWS;
+    if (it >= cend) break;
+    A::load(s1, rk, rv, koff + (uint32_t)(2 * i + 1) * STAGE_BYTES, voff + (uint32_t)(2 * i + 1) * STAGE_BYTES);
+    A::compute(s0, it + wv * A::TILE, it - cbeg + wv * A::TILE, cend, n, lg, qb, p.scale_log2, &sh_logit[0][0],
+               CHUNK, sh_p[wv], sh_alpha[wv], m_run, z_run, acc);
+    if (i + 1 < PAIRS)
+      A::load(s0, rk, rv, koff + (uint32_t)(2 * i + 2) * STAGE_BYTES, voff + (uint32_t)(2 * i + 2) * STAGE_BYTES);
+    A::compute(s1, it + A::STAGE_ROWS + wv * A::TILE, it - cbeg + A::STAGE_ROWS + wv * A::TILE, cend, n, lg, qb,
+               p.scale_log2, &sh_logit[0][0], CHUNK, sh_p[wv], sh_alpha[wv], m_run, z_run, acc);
+  }
+
+  // the wave's sum of head n is spread over the lane groups; its accumulators over the rows of a load.
+  // All lanes of a wave share one running max per head, so these are plain sums.
+  z_run += __shfl_xor(z_run, 16);
+  z_run += __shfl_xor(z_run, 32);
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+#pragma unroll
+    for (int e = 0; e < EPL; ++e) {
+      acc[g][e] += __shfl_xor(acc[g][e], 16);
+      acc[g][e] += __shfl_xor(acc[g][e], 32);
+    }
+    if (lg == 0) {
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) sh_acc[g][wv][n * EPL + e] = acc[g][e];
+    }
+  }
+  if (lg == 0 && n < G) {
+    sh_m[n][wv] = m_run;
+    sh_z[n][wv] = z_run;
+  }
+  __syncthreads();
+
+  for (int idx = tid; idx < G * CHUNK; idx += WG) {
+    const int g = idx / CHUNK, i = idx - g * CHUNK;
+    if (cbeg + i < cend) logit_u[(size_t)g * p.Lcap + cbeg + i] = sh_logit[g][i];
+  }
+
+  constexpr int PSTRIDE = D + 2;
+  for (int idx = tid; idx < G * D; idx += WG) {
+    const int g = idx / D, c = idx - g * D;
+    float mw[WAVES];
+    float mx = neg_inf();
+#pragma unroll
+    for (int i = 0; i < WAVES; ++i) {
+      mw[i] = sh_m[g][i];
+      mx = fmaxf(mx, mw[i]);
+    }
+    const float ms = mx == neg_inf() ? 0.f : mx;
+    float zt = 0.f, at = 0.f;
+#pragma unroll
+    for (int i = 0; i < WAVES; ++i) {
+      const float a = fast_exp2(mw[i] - ms);
+      zt = fmaf(sh_z[g][i], a, zt);
+      at = fmaf(sh_acc[g][i][c], a, at);
+    }
+    float* part = p.partials + ((size_t)(b * p.Hq + hq0 + g) * p.nsplit + split) * PSTRIDE;
+    part[2 + c] = at;
+    if (c == 0) {
+      part[0] = mx;
+      part[1] = zt;
+    }
+  }
+}
+
 // ---------------------------------------------------------------- fused unit kernel (no split)
 //
 // When a launch has at least as many units as the chip has compute units, splitting units buys
@@ -648,28 +882,33 @@ __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, cons
 
 // ---------------------------------------------------------------- record (+ keep flags)
 
-template <int G>
+// RECORD_CHUNKS: 512-slot chunks per workgroup (more keys per workgroup amortize its fixed chain of
+// dependent loads; fewer keep the chip full when the launch has few units)
+template <int G, int RECORD_CHUNKS>
 __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const int D) {
-  constexpr int KPT = CHUNK / WG;  // keys per thread
-  const int split = blockIdx.x;
+  constexpr int RECORD_ROWS = RECORD_CHUNKS * CHUNK;  // keys per workgroup
+  constexpr int KPT = RECORD_ROWS / WG;  // keys per thread
+  constexpr int KPC = CHUNK / WG;        // of which per chunk
+  const int rsplit = blockIdx.x;         // this workgroup covers chunks [rsplit*RECORD_CHUNKS, +RECORD_CHUNKS)
   const int unit = blockIdx.y;
   const UnitLen ul = unit_len(p, unit);
   const int L = ul.L;
   const int tid = threadIdx.x;
-  if (split == 0 && tid == 0 && ul.flags && p.status) atomicOr(p.status, ul.flags);
-  const int nlive = (L + CHUNK - 1) / CHUNK;
-  if (split >= nlive && split != 0) return;
+  if (rsplit == 0 && tid == 0 && ul.flags && p.status) atomicOr(p.status, ul.flags);
+  const int nlive = (L + CHUNK - 1) / CHUNK;                        // attend splits that hold keys
+  const int nwg = max((L + RECORD_ROWS - 1) / RECORD_ROWS, 1);      // record workgroups that have work
+  if (rsplit >= nwg) return;
 
   const int b = unit / p.Hkv;
   const int hkv = unit - b * p.Hkv;
   const int hq0 = hkv * G;
   const int lane = tid & 63, wv = tid >> 6;
   const int PSTRIDE = D + 2;
-  const int cbeg = split * CHUNK;
-  const int cend = min(cbeg + CHUNK, L);
+  const int rbeg = rsplit * RECORD_ROWS;
+  const int rend = min(rbeg + RECORD_ROWS, L);
 
   __shared__ float sh_M[G], sh_Z[G];
-  __shared__ int sh_cnt[WAVES];
+  __shared__ int sh_cnt[RECORD_CHUNKS][WAVES];
 
   // this thread's keys: issue their loads first, they are consumed after the merge below
   const int32_t* posb = p.pos + (size_t)unit * p.Lcap;
@@ -679,7 +918,7 @@ __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const i
   float lg[KPT][G];
 #pragma unroll
   for (int k = 0; k < KPT; ++k) {
-    const int i = min(cbeg + k * WG + tid, max(cend - 1, 0));   // clamped: a live slot (or 0 in an empty unit)
+    const int i = min(rbeg + k * WG + tid, max(rend - 1, 0));   // clamped: a live slot (or 0 in an empty unit)
     my_pos[k] = posb[i];
     my_lh[k] = lhb[i];
 #pragma unroll
@@ -710,36 +949,39 @@ __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const i
   }
   __syncthreads();
 
-  // out (Eq. 1): split 0 merges the accumulators
-  if (split == 0) {
-    for (int idx = tid; idx < G * D; idx += WG) {
-      const int g = idx / D, c = idx - g * D;
-      const float* part0 = p.partials + (size_t)(b * p.Hq + hq0 + g) * p.nsplit * PSTRIDE;
-      const float ms = sh_M[g];
-      float at = 0.f;
-      for (int s = 0; s < nlive; ++s) {
-        const float* ps = part0 + (size_t)s * PSTRIDE;
-        at = fmaf(ps[2 + c], exp2f(ps[0] - ms), at);
-      }
-      p.out[(size_t)(b * p.Hq + hq0 + g) * D + c] = L > 0 ? at / sh_Z[g] : 0.f;
+  // out (Eq. 1): the (head, column) pairs of the unit are dealt round-robin to the waves of its
+  // workgroups; a wave sums one pair over the splits (lane = split) and reduces by shuffles
+  for (int pair = rsplit * WAVES + wv; pair < G * D; pair += nwg * WAVES) {
+    const int g = pair / D, c = pair - g * D;
+    const float* part0 = p.partials + (size_t)(b * p.Hq + hq0 + g) * p.nsplit * PSTRIDE;
+    const float ms = sh_M[g];
+    float at = 0.f;
+    for (int s = lane; s < nlive; s += 64) {
+      const float* ps = part0 + (size_t)s * PSTRIDE;
+      at = fmaf(ps[2 + c], exp2f(ps[0] - ms), at);
     }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) at += __shfl_xor(at, off);
+    if (lane == 0) p.out[(size_t)(b * p.Hq + hq0 + g) * D + c] = L > 0 ? at / sh_Z[g] : 0.f;
   }
-  if (split >= nlive) return;  // an empty unit: nothing to record
+  if (L == 0) return;  // an empty unit: nothing to record
 
-  // record (Def. 3.1) and decide (Def. 4.1 + recent r) for the keys of this chunk
+  // record (Def. 3.1) and decide (Def. 4.1 + recent r) for the keys of this workgroup
   const bool step_ok = tcur >= 1 && tcur <= p.Tcap;
-  if (!step_ok && split == 0 && tid == 0 && p.status) atomicOr(p.status, CORM_DEV_BAD_STEP);
+  if (!step_ok && rsplit == 0 && tid == 0 && p.status) atomicOr(p.status, CORM_DEV_BAD_STEP);
   const int slot = step_ok ? (tcur - 1) % p.w : 0;
   const float thr = importance_threshold(p.thr_scale, step_ok ? tcur : 1);
   const bool full = p.do_evict && step_ok && (tcur - tfirst + 1 >= p.w);
   uint8_t* keepb = p.keep ? p.keep + (size_t)unit * p.Lcap : nullptr;
   unsigned long long* bitsb = p.keepbits + (size_t)unit * p.kb_stride;
 
-  int kept = 0;
+  int kept[RECORD_CHUNKS];
+#pragma unroll
+  for (int c = 0; c < RECORD_CHUNKS; ++c) kept[c] = 0;
 #pragma unroll
   for (int k = 0; k < KPT; ++k) {
-    const int i = cbeg + k * WG + tid;
-    const bool live = i < cend;
+    const int i = rbeg + k * WG + tid;
+    const bool live = i < rend;
     bool keep = false;
     if (live) {
       const bool pos_ok = my_pos[k] >= 0 && my_pos[k] < p.Tcap;
@@ -769,17 +1011,20 @@ __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const i
       if (p.do_evict && keepb) keepb[i] = keep ? 1 : 0;
     }
     const unsigned long long bal = __ballot(keep);
-    if (p.do_evict && lane == 0 && cbeg + k * WG + wv * 64 < cend) bitsb[((cbeg + k * WG) >> 6) + wv] = bal;
-    kept += __popcll(bal);
+    if (p.do_evict && lane == 0 && rbeg + k * WG + wv * 64 < rend) bitsb[((rbeg + k * WG) >> 6) + wv] = bal;
+    kept[k / KPC] += __popcll(bal);
   }
   if (p.do_evict) {
-    if (lane == 0) sh_cnt[wv] = kept;
+    if (lane == 0) {
+#pragma unroll
+      for (int c = 0; c < RECORD_CHUNKS; ++c) sh_cnt[c][wv] = kept[c];
+    }
     __syncthreads();
-    if (tid == 0) {
+    if (tid < RECORD_CHUNKS && rsplit * RECORD_CHUNKS + tid < nlive) {
       int tot = 0;
 #pragma unroll
-      for (int i = 0; i < WAVES; ++i) tot += sh_cnt[i];
-      p.counts[(size_t)unit * p.nsplit + split] = tot;
+      for (int i = 0; i < WAVES; ++i) tot += sh_cnt[tid][i];
+      p.counts[(size_t)unit * p.nsplit + rsplit * RECORD_CHUNKS + tid] = tot;
     }
   }
 }
@@ -941,10 +1186,18 @@ __global__ __launch_bounds__(WG) void corm_compact_local_kernel(const CompactArg
   if (split >= nlive) return;
   const int32_t* cnt = a.counts + (size_t)unit * a.nsplit;
   int R = 0, T = 0;   // survivors before this chunk, survivors of the unit
-  for (int s = 0; s < nlive; ++s) {
-    const int c = cnt[s];
-    if (s < split) R += c;
-    T += c;
+  {
+    const int lane = tid & 63;
+    for (int s = lane; s < nlive; s += 64) {
+      const int c = cnt[s];
+      if (s < split) R += c;
+      T += c;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      R += __shfl_xor(R, off);
+      T += __shfl_xor(T, off);
+    }
   }
   int32_t* idxb = a.kept_idx ? a.kept_idx + (size_t)unit * a.Lcap : nullptr;
   int cbeg = split * CHUNK;
@@ -1023,7 +1276,9 @@ __global__ __launch_bounds__(WG) void corm_compact_boundary_kernel(const Compact
   const int nlive = (L + CHUNK - 1) / CHUNK;
   const int32_t* cnt = a.counts + (size_t)unit * a.nsplit;
   int T = 0;
-  for (int s = 0; s < nlive; ++s) T += cnt[s];
+  for (int s = (tid & 63); s < nlive; s += 64) T += cnt[s];
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) T += __shfl_xor(T, off);
   if (T < L && (L - T) <= STAGE_ROWS) {
     char* Kb = a.K + (size_t)unit * a.Lcap * ROWB;
     char* Vb = a.V + (size_t)unit * a.Lcap * ROWB;
@@ -1218,6 +1473,11 @@ void bind_params(const corm_desc* d, const WorkspaceLayout& wl, void* workspace,
   p.ring_bf16 = d->score_dtype == CORM_BF16;
 }
 
+// 0 = choose by shape, 1 = split kernels (attend + record), 2 = fused unit kernel,
+// 3 = split kernels with q.K^T on the vector ALU even where the MFMA kernel applies
+int g_force_path = 0;
+int g_num_cus = 0;
+
 template <typename DT, int D>
 int launch_attend_g(const Params& p, int G, dim3 grid, hipStream_t s) {
   switch (G) {
@@ -1239,6 +1499,15 @@ int launch_attend(const corm_desc* d, const Params& p, hipStream_t s) {
   int rc;
   if (d->kv_dtype == CORM_F32) {
     rc = d->d == 64 ? launch_attend_g<F32, 64>(p, G, grid, s) : launch_attend_g<F32, 128>(p, G, grid, s);
+  } else if (d->d == 128 && G > 1 && g_force_path != 3) {
+    // grouped queries, bf16, d = 128: q.K^T on the matrix cores
+    switch (G) {
+      case 2: hipLaunchKernelGGL((corm_attend_gqa_kernel<2>), grid, dim3(WG), 0, s, p); break;
+      case 4: hipLaunchKernelGGL((corm_attend_gqa_kernel<4>), grid, dim3(WG), 0, s, p); break;
+      case 8: hipLaunchKernelGGL((corm_attend_gqa_kernel<8>), grid, dim3(WG), 0, s, p); break;
+      default: return CORM_EUNSUPPORTED;
+    }
+    rc = launch_status();
   } else {
     rc = d->d == 64 ? launch_attend_g<BF16, 64>(p, G, grid, s) : launch_attend_g<BF16, 128>(p, G, grid, s);
   }
@@ -1247,9 +1516,6 @@ int launch_attend(const corm_desc* d, const Params& p, hipStream_t s) {
   return CORM_OK;
 }
 
-// 0 = choose by shape, 1 = split kernels (attend + record), 2 = fused unit kernel
-int g_force_path = 0;
-int g_num_cus = 0;
 
 size_t unit_lds_bytes(const corm_desc* d, int* lstride) {
   const int rowb = row_bytes(d);
@@ -1263,7 +1529,7 @@ size_t unit_lds_bytes(const corm_desc* d, int* lstride) {
 bool use_unit_path(const corm_desc* d) {
   int lstride;
   const bool fits = unit_lds_bytes(d, &lstride) <= 48 * 1024 && d->Hq / d->Hkv <= 4;  // G = 8 exceeds the register file
-  if (g_force_path == 1 || !fits) return false;
+  if (g_force_path == 1 || g_force_path == 3 || !fits) return false;
   if (g_force_path == 2) return true;
   if (g_num_cus == 0) {
     int dev = 0, n = 0;
@@ -1309,17 +1575,27 @@ int launch_unit(const corm_desc* d, const Params& p, hipStream_t s) {
 // append (if p.do_append) + attend + record: one fused launch or the attend / record pair
 int launch_attend_record(const corm_desc* d, const Params& p, hipStream_t s);
 
-int launch_record(const corm_desc* d, const Params& p, hipStream_t s) {
+template <int RC>
+int launch_record_rc(const corm_desc* d, const Params& p, hipStream_t s) {
   const int G = d->Hq / d->Hkv;
-  const dim3 grid(p.nsplit, d->B * d->Hkv);
+  const dim3 grid((p.nsplit + RC - 1) / RC, d->B * d->Hkv);
   switch (G) {
-    case 1: hipLaunchKernelGGL((corm_record_kernel<1>), grid, dim3(WG), 0, s, p, d->d); break;
-    case 2: hipLaunchKernelGGL((corm_record_kernel<2>), grid, dim3(WG), 0, s, p, d->d); break;
-    case 4: hipLaunchKernelGGL((corm_record_kernel<4>), grid, dim3(WG), 0, s, p, d->d); break;
-    case 8: hipLaunchKernelGGL((corm_record_kernel<8>), grid, dim3(WG), 0, s, p, d->d); break;
+    case 1: hipLaunchKernelGGL((corm_record_kernel<1, RC>), grid, dim3(WG), 0, s, p, d->d); break;
+    case 2: hipLaunchKernelGGL((corm_record_kernel<2, RC>), grid, dim3(WG), 0, s, p, d->d); break;
+    case 4: hipLaunchKernelGGL((corm_record_kernel<4, RC>), grid, dim3(WG), 0, s, p, d->d); break;
+    case 8: hipLaunchKernelGGL((corm_record_kernel<8, RC>), grid, dim3(WG), 0, s, p, d->d); break;
     default: return CORM_EUNSUPPORTED;
   }
   return launch_status();
+}
+
+int launch_record(const corm_desc* d, const Params& p, hipStream_t s) {
+  // the largest workgroup that still leaves about four workgroups per compute unit
+  const long units = (long)d->B * d->Hkv;
+  const long want = 4L * (g_num_cus > 0 ? g_num_cus : 256);
+  if (units * ((p.nsplit + 3) / 4) >= want) return launch_record_rc<4>(d, p, s);
+  if (units * ((p.nsplit + 1) / 2) >= want) return launch_record_rc<2>(d, p, s);
+  return launch_record_rc<1>(d, p, s);
 }
 
 int launch_attend_record(const corm_desc* d, const Params& p, hipStream_t s) {
@@ -1554,7 +1830,7 @@ int corm_selected_path(const corm_desc* desc) {
 }
 
 int corm_force_path(int path) {
-  if (path < 0 || path > 2) return CORM_EINVAL;
+  if (path < 0 || path > 3) return CORM_EINVAL;
   g_force_path = path;
   return CORM_OK;
 }

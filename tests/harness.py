@@ -77,23 +77,31 @@ def check_unit_state(st: corm.LayerState, b: int, h: int, u: O.UnitCache, t: int
 
 def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_scale=1.0, check_state_every=1,
                           units: Optional[Sequence[Tuple[int, int]]] = None, steps: Optional[int] = None,
-                          use_split_calls=False) -> Dict:
-    """Run replay + decode on the device, slaving one oracle per checked unit.  Returns a report."""
+                          use_split_calls=False, seq_offsets: Optional[Sequence[int]] = None,
+                          Lcap: Optional[int] = None, Tcap: Optional[int] = None) -> Dict:
+    """Run replay + decode on the device, slaving one oracle per checked unit.  Returns a report.
+
+    seq_offsets[b]: sequence b behaves as if o_b tokens preceded its prompt (their keys already evicted):
+    its positions and its step counter t are shifted by o_b, so sequences of one batch sit at different steps."""
     x_cpu = inputs.make_layer(wl, layer, device="cpu")
     x = {k: v.to(device) for k, v in x_cpu.items() if k != "sinks"}
     n_replay = min(wl.w, wl.P)
     n_steps = n_replay + wl.D if steps is None else steps
-    st = make_state(wl, device, thr_scale=thr_scale)
+    offs = np.zeros(wl.B, dtype=np.int64) if seq_offsets is None else np.asarray(seq_offsets, dtype=np.int64)
+    offs_dev = torch.from_numpy(offs).to(device=device, dtype=torch.int32)
+    st = make_state(wl, device, thr_scale=thr_scale, Lcap=Lcap,
+                    Tcap=(wl.P + wl.D + int(offs.max())) if Tcap is None else Tcap)
     G = wl.G
     pre = wl.P - n_replay
     st.preload(x["K0"][:, :, :pre], x["V0"][:, :, :pre])
+    st.pos[:, :, :pre] += offs_dev.view(-1, 1, 1)
     units = [(b, h) for b in range(wl.B) for h in range(wl.Hkv)] if units is None else list(units)
     oracles = {}
     for (b, h) in units:
         u = O.UnitCache(wl.d, G, wl.w, wl.r, thr_scale, score_dtype=wl.dtype)
-        u.preload(_f32(x_cpu["K0"][b, h, :pre]), _f32(x_cpu["V0"][b, h, :pre]))
+        u.preload(_f32(x_cpu["K0"][b, h, :pre]), _f32(x_cpu["V0"][b, h, :pre]), first_position=int(offs[b]))
         oracles[(b, h)] = u
-    t_first = torch.full((wl.B,), pre + 1, dtype=torch.int32, device=device)
+    t_first = (torch.full((wl.B,), pre + 1, dtype=torch.int32, device=device) + offs_dev)
     tol = OUT_TOL[wl.dtype]
     worst_out = 0.0
     worst_score = 0.0
@@ -101,7 +109,7 @@ def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_sca
     evicted_total = 0
     for j in range(n_steps):
         q, k, v, t = step_inputs(wl, x, j, n_replay)
-        t_dev = torch.full((wl.B,), t, dtype=torch.int32, device=device)
+        t_dev = torch.full((wl.B,), t, dtype=torch.int32, device=device) + offs_dev
         if use_split_calls:
             corm.corm_append(st.desc, st.K, st.V, st.lens, st.pos, st.last_hit, k, v, t_dev, st.status)
             corm.corm_decode_attend(st.desc, q, st.K, st.V, st.lens, st.pos, t_dev, st.ring, st.last_hit, st.out,
@@ -118,18 +126,21 @@ def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_sca
             st.step(q, k, v, t_dev, t_first)
         torch.cuda.synchronize()
         assert int(st.status.item()) == 0, ("device status", int(st.status.item()), j)
-        slot = (t - 1) % wl.w
-        ring_row = _f32(st.ring[:, :, slot])                  # [B, Hq, Tcap]
+        ring_all = st.ring
         out = st.out.cpu().numpy()
         keep_d = st.keep.cpu().numpy()
         idx_d = st.kept_idx.cpu().numpy()
         lens_d = st.lens.cpu().numpy()
         qc, kc, vc = _f32(q), _f32(k), _f32(v)
+        ring_rows = {}
         for (b, h) in units:
             u = oracles[(b, h)]
-            live_pos = np.concatenate([u.positions, [t - 1]])
-            recorded = ring_row[b, h * G:(h + 1) * G][:, live_pos]
-            res = u.step(qc[b, h * G:(h + 1) * G], kc[b, h], vc[b, h], t, recorded=recorded)
+            tb = t + int(offs[b])
+            if b not in ring_rows:
+                ring_rows[b] = _f32(ring_all[b, :, (tb - 1) % wl.w])          # [Hq, Tcap]
+            live_pos = np.concatenate([u.positions, [tb - 1]])
+            recorded = ring_rows[b][h * G:(h + 1) * G][:, live_pos]
+            res = u.step(qc[b, h * G:(h + 1) * G], kc[b, h], vc[b, h], tb, recorded=recorded)
             l = len(live_pos)
             assert np.array_equal(keep_d[b, h, :l].astype(bool), res["keep"]), ("keep", j, b, h)
             assert int(lens_d[b, h]) == u.l, ("lens", j, b, h, int(lens_d[b, h]), u.l)
@@ -144,10 +155,10 @@ def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_sca
                 bound = SCORE_RTOL[wl.dtype] * a + SCORE_ATOL_OF_MAX[wl.dtype] * a.max()
                 worst_score = max(worst_score, float((err / bound).max()))
                 assert (err <= bound).all(), ("recorded score", j, b, h, g, float((err / bound).max()))
-            own = O.important(O.round_to_storage(res["alpha"], wl.dtype), t, thr_scale)
-            flips += int((own != O.important(recorded, t, thr_scale)).sum())
+            own = O.important(O.round_to_storage(res["alpha"], wl.dtype), tb, thr_scale)
+            flips += int((own != O.important(recorded, tb, thr_scale)).sum())
             if check_state_every and ((j + 1) % check_state_every == 0 or j == n_steps - 1):
-                check_unit_state(st, b, h, u, t)
+                check_unit_state(st, b, h, u, tb)
     return {"steps": n_steps, "units": len(units), "worst_out_rel_err": worst_out,
             "worst_score_err_over_bound": worst_score, "importance_flips_vs_fp64": flips,
             "evicted_total": evicted_total, "final_lens": st.lens.cpu().numpy().tolist()}

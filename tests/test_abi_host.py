@@ -92,7 +92,7 @@ def test_null_and_misaligned_pointers_are_rejected_on_the_host():
     assert corm.corm_step_attend(d, a, a, a, a, a, a, a, a, None, a, a, a, workspace=a, workspace_bytes=1 << 30,
                                  check=False) == corm.CORM_EINVAL
     assert corm.corm_step_evict(d, a, a, None, a, a, workspace=a, workspace_bytes=1 << 30, check=False) == corm.CORM_EINVAL
-    assert corm.corm_force_path(3, check=False) == corm.CORM_EINVAL
+    assert corm.corm_force_path(4, check=False) == corm.CORM_EINVAL
     assert corm.corm_force_path(0) == corm.CORM_OK
     assert corm.corm_evict_mask(d, a, a, a, a, None, a, check=False) == corm.CORM_EINVAL
     assert corm.corm_append(d, a, a, a, a, a, a + 4, a, a, check=False) == corm.CORM_EINVAL

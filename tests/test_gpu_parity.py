@@ -14,11 +14,11 @@ DEV = "cuda:0"
 W = inputs.WORKLOADS
 
 
-@pytest.fixture(params=["split", "unit"], autouse=True)
+@pytest.fixture(params=["split", "unit", "split_valu"], autouse=True)
 def launch_path(request):
     """Every test runs with both ways of launching attend + record: split kernels (several workgroups
     per unit) and the fused one-workgroup-per-unit kernel."""
-    corm.corm_force_path({"split": 1, "unit": 2}[request.param])
+    corm.corm_force_path({"split": 1, "unit": 2, "split_valu": 3}[request.param])
     yield request.param
     corm.corm_force_path(0)
 
@@ -86,6 +86,24 @@ def test_threshold_extremes(c, expect):
         assert (lens == wl.P + wl.D).all() and rep["evicted_total"] == 0
     else:
         assert (lens == wl.r).all()
+
+
+def test_sequences_at_different_steps():
+    """t is per sequence: one batch whose sequences sit at different absolute steps (different thresholds
+    c/t, different ring slots in the same launch)."""
+    wl = W["tiny_f32"].replace(B=3, Hq=2, Hkv=2, P=140, D=30, w=16, r=16)
+    say("ragged t", wl)
+    rep = harness.run_slaved_trajectory(wl, DEV, check_state_every=2, seq_offsets=[0, 7, 1000])
+    assert rep["evicted_total"] > 0
+
+
+def test_capacity_smaller_than_the_sequence():
+    """Slots per unit (Lcap) far below the number of positions (Tcap): legal as long as eviction keeps the
+    cache short; here c is huge, so every unit holds r (+1) keys once the window is full."""
+    wl = W["tiny_f32"].replace(P=96, D=60, w=8, r=5)
+    say("Lcap << Tcap")
+    rep = harness.run_slaved_trajectory(wl, DEV, thr_scale=1e9, check_state_every=1, Lcap=96, Tcap=96 + 60)
+    assert (np.array(rep["final_lens"]) == wl.r).all()
 
 
 def test_w1_r1():
