@@ -39,6 +39,8 @@ def parse():
                     help="supplementary variant: per-head query means so that eviction happens at w >= 256")
     ap.add_argument("--streams", type=int, default=2, choices=[1, 2, 3, 4],
                     help="layers are issued round-robin on this many streams (they are independent)")
+    ap.add_argument("--path", type=int, default=0, choices=[0, 1, 2, 3],
+                    help="corm_force_path: 0 by shape, 1 split kernels, 2 one workgroup per unit, 3 split without MFMA")
     ap.add_argument("--extra-steps", type=int, default=4, help="untimed single-stream steps after the timed region "
                     "(exclusive measurement of the dominant kernel)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -95,6 +97,7 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     corm.lib()  # fail loudly now if the HIP library is missing
+    corm.corm_force_path(args.path)
 
     wl = inputs.WORKLOADS[args.workload]
     if args.structured:
@@ -252,7 +255,7 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name + ("+structured_queries" if args.structured else ""),
                    "layers": layers, "batch": B, "q_heads": Hq, "kv_heads": Hkv, "head_dim": d,
-                   "prompt": wl.P, "w": wl.w, "r": wl.r, "tokens_per_step": B, "streams": args.streams,
+                   "prompt": wl.P, "w": wl.w, "r": wl.r, "tokens_per_step": B, "streams": args.streams, "path": corm.corm_selected_path(desc),
                    "live_fraction_end": live_end, "keys_evicted_in_timed_region": evicted},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,

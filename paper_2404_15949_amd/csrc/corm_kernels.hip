@@ -1039,17 +1039,17 @@ __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const i
 //             to slot rho -- inside its own chunk, so it reads and writes only its own slots -- in
 //             ascending tiles (every destination <= its source; inside a tile all loads complete
 //             before any store).  Its first survivors, those with rho < a_c ("boundary rows", at most
-//             as many as keys were evicted before the chunk), belong in the tail of earlier chunks,
-//             whose owners may not have read those slots yet: they go to a staging area instead.
-//   boundary  grid (units).  Copies the staged rows to slots [R_c, min(a_c, R_{c+1})): slots no local
-//             workgroup writes, and whose old contents were consumed in the previous launch.  Writes
-//             lens (nobody reads lens of this step after it).
+//             as many as slots were freed before the chunk), belong in earlier chunks, whose owners
+//             may not have read those slots yet: they go to the chunk's staging area instead.
+//   boundary  grid (splits, units).  Workgroup c copies its staged rows to slots
+//             [R_c, min(a_c, R_{c+1})): slots no local workgroup writes, and whose old contents were
+//             consumed in the previous launch.  Workgroup 0 writes lens, the live count and, in lazy
+//             mode, the reset live masks.  The unit's length is handed over through the workspace so
+//             that no workgroup of this launch reads lens.
 //
-// The staging area holds STAGE_ROWS rows per chunk.  A unit that lost more than STAGE_ROWS keys in
-// one step (the bulk eviction at the end of a prompt) is compacted by the workgroup of its chunk 0
-// alone, walking the whole unit in ascending tiles.
-
-constexpr int STAGE_ROWS = 16;
+// Policy (lazy mode): a unit is compacted only when its dead slots reach dead_num/dead_den of its
+// slots (or its slots are about to run out); otherwise both launches leave it alone, its dead rows
+// stay in place and the attend kernels skip them by their live masks.  Exact mode: dead_num = 0.
 
 struct CompactShared {
   int32_t wave_count[WAVES];
@@ -1062,15 +1062,25 @@ struct CompactArgs {
   int32_t* pos;
   int32_t* last_hit;
   int32_t* lens;
-  const uint8_t* keep;      // caller's byte mask (corm_compact only)
-  unsigned long long* keepbits;  // [units, kb_stride] wave ballots
-  int32_t* kept_idx;        // optional
-  const int32_t* counts;    // [units, nsplit]
-  char* stage_k;            // [units, nsplit, STAGE_ROWS, ROWB]
+  const uint8_t* keep;           // caller's byte mask (corm_compact only)
+  unsigned long long* keepbits;  // [units, kb_stride] wave ballots: workspace, or the caller's live masks (lazy mode)
+  int32_t* kept_idx;             // optional
+  const int32_t* counts;         // [units, nsplit]
+  int32_t* unit_len;             // [units] slots of the unit in this step (written by local, read by boundary)
+  int32_t* nlive;                // optional [units]: live keys after the step
+  char* stage_k;                 // [units, nsplit, CHUNK, ROWB]
   char* stage_v;
-  int32_t* stage_meta;      // [units, nsplit, STAGE_ROWS, 2] (pos, last_hit)
+  int32_t* stage_meta;           // [units, nsplit, CHUNK, 2] (pos, last_hit)
   int32_t nsplit, Lcap, do_append, kb_stride;
+  int32_t lazy, dead_num, dead_den;
 };
+
+// does this unit get compacted in this step?  L slots, T survivors
+__device__ __forceinline__ bool compact_now(const CompactArgs& a, int L, int T) {
+  if (T == L) return false;
+  if (!a.lazy) return true;
+  return (long long)(L - T) * a.dead_den >= (long long)L * a.dead_num || L + 1 >= a.Lcap;
+}
 
 // Moves the n_rows survivors listed in src_of (ascending) to consecutive destinations starting at
 // survivor number rho0: slot rho if rho >= own_begin, else staging row (rho - stage_rho0).
@@ -1148,6 +1158,23 @@ __device__ __forceinline__ int compact_unit_len(const CompactArgs& a, int unit) 
   return L;
 }
 
+// survivors before chunk `split` (R) and of the whole unit (T), by one wave-wide pass over the counts
+__device__ __forceinline__ void unit_counts(const int32_t* cnt, int nlive, int split, int* R, int* T) {
+  int r = 0, t = 0;
+  for (int s = (threadIdx.x & 63); s < nlive; s += 64) {
+    const int c = cnt[s];
+    if (s < split) r += c;
+    t += c;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+    r += __shfl_xor(r, off);
+    t += __shfl_xor(t, off);
+  }
+  *R = r;
+  *T = t;
+}
+
 // a caller's byte mask (corm_compact) -> wave ballots and survivors per split
 __global__ __launch_bounds__(WG) void corm_count_kernel(const CompactArgs a, int32_t* counts) {
   __shared__ int sh_cnt[WAVES];
@@ -1182,39 +1209,22 @@ __global__ __launch_bounds__(WG) void corm_compact_local_kernel(const CompactArg
   const int split = blockIdx.x, unit = blockIdx.y;
   const int tid = threadIdx.x;
   const int L = compact_unit_len(a, unit);
+  if (split == 0 && tid == 0) a.unit_len[unit] = L;
   const int nlive = (L + CHUNK - 1) / CHUNK;
   if (split >= nlive) return;
   const int32_t* cnt = a.counts + (size_t)unit * a.nsplit;
-  int R = 0, T = 0;   // survivors before this chunk, survivors of the unit
-  {
-    const int lane = tid & 63;
-    for (int s = lane; s < nlive; s += 64) {
-      const int c = cnt[s];
-      if (s < split) R += c;
-      T += c;
-    }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-      R += __shfl_xor(R, off);
-      T += __shfl_xor(T, off);
-    }
-  }
+  int R, T;   // survivors before this chunk, survivors of the unit
+  unit_counts(cnt, nlive, split, &R, &T);
   int32_t* idxb = a.kept_idx ? a.kept_idx + (size_t)unit * a.Lcap : nullptr;
-  int cbeg = split * CHUNK;
-  int cend = min(cbeg + CHUNK, L);
-  if (T == L) {   // nothing evicted: the cache is already compact
-    if (idxb)
+  const int cbeg = split * CHUNK;
+  const int cend = min(cbeg + CHUNK, L);
+  if (!compact_now(a, L, T)) {   // nothing evicted, or (lazy mode) not enough dead slots yet
+    if (idxb && T == L)
       for (int i = cbeg + tid; i < cend; i += WG) idxb[i] = i;
     return;
   }
-  const bool serial = (L - T) > STAGE_ROWS;   // too many holes for the staging area: chunk 0 walks the unit
-  int own_begin = cbeg;
-  if (serial) {
-    if (split != 0) return;
-    cend = L;
-    own_begin = 0;
-  }
-  if (R == cbeg && cnt[split] == cend - cbeg && !serial) {   // no hole before or inside this chunk
+  const int my_cnt = cnt[split];
+  if (R == cbeg && my_cnt == cend - cbeg) {   // no hole before or inside this chunk
     if (idxb)
       for (int i = cbeg + tid; i < cend; i += WG) idxb[i] = i;
     return;
@@ -1224,17 +1234,16 @@ __global__ __launch_bounds__(WG) void corm_compact_local_kernel(const CompactArg
   int32_t* posb = a.pos + (size_t)unit * a.Lcap;
   int32_t* lhb = a.last_hit + (size_t)unit * a.Lcap;
   const unsigned long long* bitsb = a.keepbits + (size_t)unit * a.kb_stride;
-  const size_t stage_row0 = ((size_t)unit * a.nsplit + split) * STAGE_ROWS;
+  const size_t stage_row0 = ((size_t)unit * a.nsplit + split) * CHUNK;
   char* sk = a.stage_k + stage_row0 * ROWB;
   char* sv = a.stage_v + stage_row0 * ROWB;
   int32_t* sm = a.stage_meta + stage_row0 * 2;
+  // a chunk whose count equals its size lost nothing: its flags are implied (and may be unwritten)
+  const bool chunk_full = my_cnt == cend - cbeg;
 
   int rho_base = R;  // survivor number of the first survivor of the current tile
   for (int tile = cbeg; tile < cend; tile += WG) {
     const int i = tile + tid;
-    // a chunk whose count equals its size lost nothing: its flags are implied (and may be unwritten)
-    const int ch = tile / CHUNK;
-    const bool chunk_full = cnt[ch] == min(CHUNK, L - ch * CHUNK);
     const bool kp = i < cend && (chunk_full || ((bitsb[i >> 6] >> (i & 63)) & 1ull) != 0);
     int my_pos = 0, my_lh = 0;
     if (kp) {
@@ -1248,7 +1257,7 @@ __global__ __launch_bounds__(WG) void corm_compact_local_kernel(const CompactArg
     if (kp) {
       sh_c.src_of[rank] = i;
       if (idxb) idxb[rho] = i;
-      if (rho >= own_begin) {
+      if (rho >= cbeg) {
         if (rho != i) {
           posb[rho] = my_pos;
           lhb[rho] = my_lh;
@@ -1261,7 +1270,7 @@ __global__ __launch_bounds__(WG) void corm_compact_local_kernel(const CompactArg
     __syncthreads();
     const int tile_n = min(WG, cend - tile);
     if (!(rho_base == tile && tile_kept == tile_n))
-      move_rows<ROWB>(Kb, Vb, sk, sv, sh_c.src_of, tile_kept, rho_base, own_begin, R);
+      move_rows<ROWB>(Kb, Vb, sk, sv, sh_c.src_of, tile_kept, rho_base, cbeg, R);
     rho_base += tile_kept;
     __syncthreads();
   }
@@ -1270,44 +1279,50 @@ __global__ __launch_bounds__(WG) void corm_compact_local_kernel(const CompactArg
 template <int ROWB>
 __global__ __launch_bounds__(WG) void corm_compact_boundary_kernel(const CompactArgs a) {
   constexpr int LPR = ROWB / 16;
-  const int unit = blockIdx.x;
+  const int split = blockIdx.x, unit = blockIdx.y;
   const int tid = threadIdx.x;
-  const int L = compact_unit_len(a, unit);
+  const int L = a.unit_len[unit];
   const int nlive = (L + CHUNK - 1) / CHUNK;
+  if (split >= nlive && split != 0) return;
   const int32_t* cnt = a.counts + (size_t)unit * a.nsplit;
-  int T = 0;
-  for (int s = (tid & 63); s < nlive; s += 64) T += cnt[s];
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) T += __shfl_xor(T, off);
-  if (T < L && (L - T) <= STAGE_ROWS) {
-    char* Kb = a.K + (size_t)unit * a.Lcap * ROWB;
-    char* Vb = a.V + (size_t)unit * a.Lcap * ROWB;
-    int32_t* posb = a.pos + (size_t)unit * a.Lcap;
-    int32_t* lhb = a.last_hit + (size_t)unit * a.Lcap;
-    // thread -> (row j of the chunk's staging area, 16-byte column): STAGE_ROWS * LPR threads per chunk
-    const int j = tid / LPR;
-    const size_t col = (size_t)(tid % LPR) * 16;
-    int R = cnt[0];
-    for (int c = 1; c < nlive; ++c) {
-      const int Rn = R + cnt[c];
-      const int nb = min(c * CHUNK, Rn) - R;   // boundary rows of chunk c: survivor numbers [R, R + nb)
-      if (nb > 0) {
-        const size_t stage_row0 = ((size_t)unit * a.nsplit + c) * STAGE_ROWS;
-        for (int jj = j; jj < nb; jj += WG / LPR) {
-          const size_t s = (stage_row0 + jj) * ROWB + col;
-          const size_t d = (size_t)(R + jj) * ROWB + col;
-          *reinterpret_cast<uint4*>(Kb + d) = *reinterpret_cast<const uint4*>(a.stage_k + s);
-          *reinterpret_cast<uint4*>(Vb + d) = *reinterpret_cast<const uint4*>(a.stage_v + s);
-        }
-        if (tid < nb) {
-          posb[R + tid] = a.stage_meta[(stage_row0 + tid) * 2];
-          lhb[R + tid] = a.stage_meta[(stage_row0 + tid) * 2 + 1];
-        }
+  int R, T;
+  unit_counts(cnt, nlive, split, &R, &T);
+  const bool compacted = compact_now(a, L, T);
+  if (compacted && split > 0) {
+    const int nb = min(split * CHUNK, R + cnt[split]) - R;   // boundary rows of this chunk: survivors [R, R + nb)
+    if (nb > 0) {
+      char* Kb = a.K + (size_t)unit * a.Lcap * ROWB;
+      char* Vb = a.V + (size_t)unit * a.Lcap * ROWB;
+      int32_t* posb = a.pos + (size_t)unit * a.Lcap;
+      int32_t* lhb = a.last_hit + (size_t)unit * a.Lcap;
+      const size_t stage_row0 = ((size_t)unit * a.nsplit + split) * CHUNK;
+      const size_t col = (size_t)(tid % LPR) * 16;
+      for (int j = tid / LPR; j < nb; j += WG / LPR) {
+        const size_t s = (stage_row0 + j) * ROWB + col;
+        const size_t d = (size_t)(R + j) * ROWB + col;
+        *reinterpret_cast<uint4*>(Kb + d) = *reinterpret_cast<const uint4*>(a.stage_k + s);
+        *reinterpret_cast<uint4*>(Vb + d) = *reinterpret_cast<const uint4*>(a.stage_v + s);
       }
-      R = Rn;
+      for (int j = tid; j < nb; j += WG) {
+        posb[R + j] = a.stage_meta[(stage_row0 + j) * 2];
+        lhb[R + j] = a.stage_meta[(stage_row0 + j) * 2 + 1];
+      }
     }
   }
-  if (tid == 0) a.lens[unit] = T;
+  if (split == 0) {
+    const int Lnew = compacted ? T : L;
+    if (tid == 0) {
+      a.lens[unit] = Lnew;
+      if (a.nlive) a.nlive[unit] = T;
+    }
+    if (a.lazy && compacted) {   // every slot below T is live again
+      unsigned long long* bitsb = a.keepbits + (size_t)unit * a.kb_stride;
+      for (int wd = tid; wd < a.kb_stride; wd += WG) {
+        const int lo = wd * 64;
+        bitsb[wd] = T >= lo + 64 ? ~0ull : (T > lo ? ((1ull << (T - lo)) - 1ull) : 0ull);
+      }
+    }
+  }
 }
 
 // ---------------------------------------------------------------- standalone kernels
@@ -1400,7 +1415,7 @@ __global__ void corm_fill_i32_kernel(int32_t* p, size_t n, int32_t v) {
 // ---------------------------------------------------------------- host side
 
 struct WorkspaceLayout {
-  size_t counts_off, keepbits_off, partials_off, logits_off, stage_meta_off, stage_k_off, stage_v_off, total;
+  size_t counts_off, unit_len_off, keepbits_off, partials_off, logits_off, stage_meta_off, stage_k_off, stage_v_off, total;
   int nsplit, kb_stride;
 };
 
@@ -1412,10 +1427,11 @@ WorkspaceLayout workspace_layout(const corm_desc& d) {
   WorkspaceLayout w;
   w.nsplit = (d.Lcap + CHUNK - 1) / CHUNK;
   const size_t units = (size_t)d.B * d.Hkv, heads = (size_t)d.B * d.Hq;
-  const size_t stage_rows = units * w.nsplit * STAGE_ROWS;
+  const size_t stage_rows = units * w.nsplit * CHUNK;   // every survivor of a chunk may be a boundary row
   w.counts_off = 0;
   w.kb_stride = (d.Lcap + 63) / 64;
-  w.keepbits_off = align_up(units * w.nsplit * sizeof(int32_t), 256);
+  w.unit_len_off = align_up(units * w.nsplit * sizeof(int32_t), 256);
+  w.keepbits_off = align_up(w.unit_len_off + units * sizeof(int32_t), 256);
   w.partials_off = align_up(w.keepbits_off + units * w.kb_stride * sizeof(unsigned long long), 256);
   w.logits_off = align_up(w.partials_off + heads * w.nsplit * (d.d + 2) * sizeof(float), 256);
   w.stage_meta_off = align_up(w.logits_off + heads * d.Lcap * sizeof(float), 256);
@@ -1605,40 +1621,51 @@ int launch_attend_record(const corm_desc* d, const Params& p, hipStream_t s) {
   return launch_record(d, p, s);
 }
 
+// Policy of the compaction launches: exact mode compacts every unit that lost a key; lazy mode only
+// units whose dead slots reach dead_num / dead_den of their slots.
+struct CompactPolicy {
+  int lazy = 0, dead_num = 0, dead_den = 1;
+  unsigned long long* live = nullptr;   // lazy mode: the caller's live masks take the place of the keep masks
+  int32_t* nlive = nullptr;             // optional output: live keys per unit
+};
+
 // local + boundary launches of the compaction; count_first: derive the per-split counts from the mask
 int launch_compact(const corm_desc* d, const WorkspaceLayout& wl, void* workspace, void* K, void* V, int32_t* pos,
                    int32_t* last_hit, int32_t* lens, const uint8_t* keep, int32_t* kept_idx, int do_append,
-                   bool count_first, hipStream_t s) {
+                   bool count_first, const CompactPolicy& pol, hipStream_t s) {
   char* ws = reinterpret_cast<char*>(workspace);
   CompactArgs a;
   a.K = reinterpret_cast<char*>(K);
   a.V = reinterpret_cast<char*>(V);
   a.pos = pos; a.last_hit = last_hit; a.lens = lens; a.keep = keep; a.kept_idx = kept_idx;
-  a.keepbits = reinterpret_cast<unsigned long long*>(ws + wl.keepbits_off);
+  a.keepbits = pol.live ? pol.live : reinterpret_cast<unsigned long long*>(ws + wl.keepbits_off);
   a.kb_stride = wl.kb_stride;
   int32_t* counts = reinterpret_cast<int32_t*>(ws + wl.counts_off);
   a.counts = counts;
+  a.unit_len = reinterpret_cast<int32_t*>(ws + wl.unit_len_off);
+  a.nlive = pol.nlive;
   a.stage_k = ws + wl.stage_k_off;
   a.stage_v = ws + wl.stage_v_off;
   a.stage_meta = reinterpret_cast<int32_t*>(ws + wl.stage_meta_off);
   a.nsplit = wl.nsplit; a.Lcap = d->Lcap; a.do_append = do_append;
-  const dim3 grid2(wl.nsplit, d->B * d->Hkv), grid1(d->B * d->Hkv);
+  a.lazy = pol.lazy; a.dead_num = pol.dead_num; a.dead_den = pol.dead_den;
+  const dim3 grid(wl.nsplit, d->B * d->Hkv);
   if (count_first) {
-    hipLaunchKernelGGL(corm_count_kernel, grid2, dim3(WG), 0, s, a, counts);
+    hipLaunchKernelGGL(corm_count_kernel, grid, dim3(WG), 0, s, a, counts);
     if (launch_status()) return CORM_EHIP;
   }
   switch (row_bytes(d)) {
     case 128:
-      hipLaunchKernelGGL((corm_compact_local_kernel<128>), grid2, dim3(WG), 0, s, a);
-      hipLaunchKernelGGL((corm_compact_boundary_kernel<128>), grid1, dim3(WG), 0, s, a);
+      hipLaunchKernelGGL((corm_compact_local_kernel<128>), grid, dim3(WG), 0, s, a);
+      hipLaunchKernelGGL((corm_compact_boundary_kernel<128>), grid, dim3(WG), 0, s, a);
       break;
     case 256:
-      hipLaunchKernelGGL((corm_compact_local_kernel<256>), grid2, dim3(WG), 0, s, a);
-      hipLaunchKernelGGL((corm_compact_boundary_kernel<256>), grid1, dim3(WG), 0, s, a);
+      hipLaunchKernelGGL((corm_compact_local_kernel<256>), grid, dim3(WG), 0, s, a);
+      hipLaunchKernelGGL((corm_compact_boundary_kernel<256>), grid, dim3(WG), 0, s, a);
       break;
     case 512:
-      hipLaunchKernelGGL((corm_compact_local_kernel<512>), grid2, dim3(WG), 0, s, a);
-      hipLaunchKernelGGL((corm_compact_boundary_kernel<512>), grid1, dim3(WG), 0, s, a);
+      hipLaunchKernelGGL((corm_compact_local_kernel<512>), grid, dim3(WG), 0, s, a);
+      hipLaunchKernelGGL((corm_compact_boundary_kernel<512>), grid, dim3(WG), 0, s, a);
       break;
     default: return CORM_EUNSUPPORTED;
   }
@@ -1771,7 +1798,7 @@ int corm_compact(const corm_desc* desc, void* K, void* V, int32_t* pos, int32_t*
   WorkspaceLayout wl;
   rc = check_workspace(desc, workspace, workspace_bytes, &wl);
   if (rc) return rc;
-  return launch_compact(desc, wl, workspace, K, V, pos, last_hit, lens, keep, kept_idx, 0, true,
+  return launch_compact(desc, wl, workspace, K, V, pos, last_hit, lens, keep, kept_idx, 0, true, CompactPolicy(),
                         (hipStream_t)stream);
 }
 
@@ -1806,7 +1833,7 @@ int corm_step_evict(const corm_desc* desc, void* K, void* V, int32_t* lens, int3
   WorkspaceLayout wl;
   rc = check_workspace(desc, workspace, workspace_bytes, &wl);
   if (rc) return rc;
-  return launch_compact(desc, wl, workspace, K, V, pos, last_hit, lens, nullptr, kept_idx, 1, false,
+  return launch_compact(desc, wl, workspace, K, V, pos, last_hit, lens, nullptr, kept_idx, 1, false, CompactPolicy(),
                         (hipStream_t)stream);
 }
 

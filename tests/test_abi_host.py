@@ -44,10 +44,10 @@ def test_workspace_size_formula():
     n = corm.corm_workspace_bytes(d)
     nsplit = (1024 + 511) // 512
     units, heads = 2 * 2, 2 * 8
-    stage_rows = units * nsplit * 16
-    need = (units * nsplit * 4 + units * (1024 // 64) * 8 + heads * nsplit * 130 * 4 + heads * 1024 * 4
+    stage_rows = units * nsplit * 512
+    need = (units * nsplit * 4 + units * 4 + units * (1024 // 64) * 8 + heads * nsplit * 130 * 4 + heads * 1024 * 4
             + stage_rows * (8 + 2 * 256))
-    assert need <= n <= need + 7 * 256
+    assert need <= n <= need + 8 * 256
 
 
 @pytest.mark.parametrize("kw,code", [
