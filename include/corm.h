@@ -160,6 +160,30 @@ int corm_step_attend(const corm_desc* desc, const void* q, const void* k_new, co
 int corm_step_evict(const corm_desc* desc, void* K, void* V, int32_t* lens, int32_t* pos, int32_t* last_hit,
                     int32_t* kept_idx, void* workspace, size_t workspace_bytes, void* stream);
 
+/* The fused step with deferred compaction.  Algorithm 1 gathers the surviving keys after every step;
+ * the gather only changes where keys lie, not which keys the next step attends to (Sec. 4.2, Eq. 1 over
+ * the kept set), so it may be postponed: evicted keys stay in their slots as dead rows, marked in
+ * `live`, and a unit is compacted (stably, as in corm_decode_step) only once its dead slots reach
+ * dead_num/dead_den of its slots or its slots are about to run out.  The live keys of a unit, read in
+ * slot order, and out, the ring and last_hit are what corm_decode_step produces; only the slot numbers
+ * differ.  Dead rows are neither loaded nor scored.
+ *   live       device uint64 [B, Hkv, ceil(Lcap/64)], in/out: bit (i % 64) of word (i / 64) = slot i holds a
+ *              live key.  Bits at or above lens are ignored on input.  Initialise to all ones.
+ *   lens       slots in use (live + dead); after a compaction, the number of live keys.
+ *   keep       optional byte mask [B, Hkv, Lcap] of the slots as they were after the append: 1 = live after
+ *              this step.
+ *   nlive      optional device int32 [B, Hkv]: live keys after the step.
+ *   dead_num, dead_den   0 <= dead_num <= dead_den, dead_den >= 1; dead_num = 0 compacts at every
+ *              eviction and reproduces corm_decode_step slot for slot.
+ * The recent-r rule is taken by position (pos >= t - r), which equals the last r live keys whenever
+ * the cache was filled by consecutive steps (Sec. 4.2).  Other arguments, errors and status flags as
+ * corm_decode_step.  CORM_EINVAL for a null or misaligned (8 bytes) live, or a bad fraction. */
+int corm_decode_step_lazy(const corm_desc* desc, const void* q, const void* k_new, const void* v_new, void* K, void* V,
+                          int32_t* lens, uint64_t* live, int32_t* pos, int32_t* last_hit, const int32_t* t,
+                          const int32_t* t_first, void* score_ring, float* out, uint8_t* keep, int32_t* nlive,
+                          int32_t dead_num, int32_t dead_den, void* workspace, size_t workspace_bytes,
+                          int32_t* status, void* stream);
+
 /* Tuning / test knob (host call, process-wide, not thread safe): how attend + record are launched.
  * 0 = choose by shape (default); 1 = split kernels (several workgroups per unit, partials merged by a
  * second launch; grouped bf16 d=128 queries take q.K^T on the matrix cores); 2 = one workgroup per unit

@@ -22,8 +22,8 @@ CORM_DEV_UNIT_FULL, CORM_DEV_BAD_STEP, CORM_DEV_BAD_LENS = 1, 2, 4
 
 EXPORTS = ("corm_version", "corm_strerror", "corm_workspace_bytes", "corm_workspace_init", "corm_append",
            "corm_decode_attend", "corm_evict_mask", "corm_evict_mask_summary", "corm_compact",
-           "corm_decode_step", "corm_step_attend", "corm_step_evict", "corm_force_path", "corm_selected_path", "corm_profile_attend",
-           "corm_threshold")
+           "corm_decode_step", "corm_step_attend", "corm_step_evict", "corm_decode_step_lazy", "corm_force_path",
+           "corm_selected_path", "corm_profile_attend", "corm_threshold")
 
 
 class corm_desc(ctypes.Structure):
@@ -70,6 +70,8 @@ def lib() -> ctypes.CDLL:
         L.corm_selected_path.argtypes = [dp]
         L.corm_decode_step.argtypes = [dp, vp, vp, vp, vp, vp, i32p, i32p, i32p, i32p, i32p, vp, vp, vp, i32p,
                                        vp, sz, i32p, vp]
+        L.corm_decode_step_lazy.argtypes = [dp, vp, vp, vp, vp, vp, i32p, vp, i32p, i32p, i32p, i32p, vp, vp, vp,
+                                            i32p, ctypes.c_int32, ctypes.c_int32, vp, sz, i32p, vp]
         L.corm_threshold.argtypes = [ctypes.c_float, i32p, ctypes.c_int32, vp, vp]
         L.corm_profile_attend.argtypes = [vp, vp]
         for name in EXPORTS:
@@ -217,6 +219,19 @@ def corm_decode_step(desc, q, k_new, v_new, K, V, lens, pos, last_hit, t, t_firs
     return _check(rc, "corm_decode_step") if check else rc
 
 
+def corm_decode_step_lazy(desc, q, k_new, v_new, K, V, lens, live, pos, last_hit, t, t_first, score_ring, out,
+                          keep=None, nlive=None, dead_num=1, dead_den=4, workspace=None, workspace_bytes=None,
+                          status=None, stream=None, check=True) -> int:
+    nbytes = workspace_bytes
+    if nbytes is None:
+        nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib().corm_decode_step_lazy(ctypes.byref(desc), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(K), _ptr(V),
+                                     _ptr(lens), _ptr(live), _ptr(pos), _ptr(last_hit), _ptr(t), _ptr(t_first),
+                                     _ptr(score_ring), _ptr(out), _ptr(keep), _ptr(nlive), dead_num, dead_den,
+                                     _ptr(workspace), nbytes, _ptr(status), _stream(stream))
+    return _check(rc, "corm_decode_step_lazy") if check else rc
+
+
 def corm_profile_attend(start_event, stop_event, check=True) -> int:
     """start_event / stop_event: raw hipEvent_t handles (ints) or None."""
     rc = lib().corm_profile_attend(start_event, stop_event)
@@ -249,6 +264,9 @@ class LayerState:
         self.status = torch.zeros(1, dtype=torch.int32, device=device)
         self.keep = torch.zeros(B, Hkv, Lcap, dtype=torch.uint8, device=device) if want_masks else None
         self.kept_idx = torch.zeros(B, Hkv, Lcap, dtype=torch.int32, device=device) if want_masks else None
+        # deferred compaction (step_lazy): live masks, all ones = every slot below lens holds a live key
+        self.live = torch.full((B, Hkv, (Lcap + 63) // 64), -1, dtype=torch.int64, device=device)
+        self.nlive = torch.zeros(B, Hkv, dtype=torch.int32, device=device)
         if workspace is None:
             workspace = torch.empty(corm_workspace_bytes(self.desc), dtype=torch.uint8, device=device)
             corm_workspace_init(self.desc, workspace)
@@ -276,3 +294,9 @@ class LayerState:
         corm_decode_step(self.desc, q, k_new, v_new, self.K, self.V, self.lens, self.pos, self.last_hit, t, t_first,
                          self.ring, self.out, self.keep, self.kept_idx, self.workspace, status=self.status,
                          stream=stream)
+
+    def step_lazy(self, q, k_new, v_new, t, t_first, dead_num=1, dead_den=4, stream=None, workspace=None) -> None:
+        corm_decode_step_lazy(self.desc, q, k_new, v_new, self.K, self.V, self.lens, self.live, self.pos,
+                              self.last_hit, t, t_first, self.ring, self.out, self.keep, self.nlive, dead_num,
+                              dead_den, self.workspace if workspace is None else workspace, status=self.status,
+                              stream=stream)

@@ -57,6 +57,7 @@ struct Params {
   float thr_scale, scale_log2;
   int32_t do_append, do_evict, ring_bf16;
   int32_t kb_stride;    // 64-bit words per unit in keepbits
+  int32_t lazy;         // lazy mode: keepbits are the caller's persistent live masks; dead slots are skipped
 };
 
 // ---------------------------------------------------------------- small device helpers
@@ -188,6 +189,9 @@ __device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t r, uint32_
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// byte offset beyond any descriptor: the load returns zeros without touching memory
+constexpr uint32_t DEAD_OFFSET = 0x7ffffff0u;
+
 // 2^x by the hardware instruction alone (results below the normal range flush to zero: such
 // probabilities vanish against a sum that is >= 1)
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -206,16 +210,35 @@ struct Attend {
   struct Stage {
     uint4 k[U];
     uint4 v[U];
+    uint32_t live;   // lazy mode: bit j = the row of load j holds a live key
   };
 
   // Unrolled load j of a stage: the workgroup reads LOAD_ROWS consecutive rows per load.
-  // off0 = byte offset of this lane's slice in row (wv*RPL + sub) of the stage.
+  // off = byte offset of this lane's slice in its row of load 0.  Lazy mode: sh_live holds the live
+  // masks (LDS), lrow is this lane's row of load 0 relative to the first slot sh_live covers; the
+  // loads of dead rows get an out-of-range offset (zeros, no memory traffic).
+  template <bool LAZY>
   __device__ static __forceinline__ void load(Stage& st, __amdgpu_buffer_rsrc_t rk, __amdgpu_buffer_rsrc_t rv,
-                                              uint32_t off) {
+                                              uint32_t off, const unsigned long long* sh_live, int lrow) {
+    st.live = (1u << U) - 1u;
+    if (LAZY) {
+      st.live = 0u;
 #pragma unroll
-    for (int j = 0; j < U; ++j) st.k[j] = buffer_load16(rk, off + (uint32_t)(j * LOAD_ROWS * ROWB));
+      for (int j = 0; j < U; ++j) {
+        const int r = lrow + j * LOAD_ROWS;
+        st.live |= (uint32_t)((sh_live[r >> 6] >> (r & 63)) & 1ull) << j;
+      }
+    }
 #pragma unroll
-    for (int j = 0; j < U; ++j) st.v[j] = buffer_load16(rv, off + (uint32_t)(j * LOAD_ROWS * ROWB));
+    for (int j = 0; j < U; ++j) {
+      const uint32_t o = (!LAZY || ((st.live >> j) & 1u)) ? off + (uint32_t)(j * LOAD_ROWS * ROWB) : DEAD_OFFSET;
+      st.k[j] = buffer_load16(rk, o);
+    }
+#pragma unroll
+    for (int j = 0; j < U; ++j) {
+      const uint32_t o = (!LAZY || ((st.live >> j) & 1u)) ? off + (uint32_t)(j * LOAD_ROWS * ROWB) : DEAD_OFFSET;
+      st.v[j] = buffer_load16(rv, o);
+    }
   }
 
   // row0 = this lane's row in unrolled load 0, lrel0 = its index in the logit staging array
@@ -233,7 +256,7 @@ struct Attend {
         const int row = row0 + j * LOAD_ROWS;
         const float part = DT::dot(st.k[j], qreg[g]);
         const float tot = row_allreduce_sum<LPR>(part) * scale_log2;
-        s[j] = row < cend ? tot : neg_inf();
+        s[j] = (row < cend && ((st.live >> j) & 1u)) ? tot : neg_inf();
         if (cl == j) my_logit = tot;
       }
       // lane cl == j keeps the logit of the row of load j: staged in LDS, written out once per chunk
@@ -261,7 +284,29 @@ struct Attend {
   }
 };
 
-template <typename DT, int D, int G>
+// Lazy mode, shared by the attend kernels: the live masks of slots [first, first + 64*nwords) go to
+// LDS; the appended slot's bit is set there and, by its owner, in the caller's array.  Bits at or
+// above the unit's length read as dead.  Ends with a barrier.
+__device__ __forceinline__ void stage_live_masks(const Params& p, int unit, const UnitLen& ul, int first, int nwords,
+                                                 bool owns_new_slot, unsigned long long* sh_live) {
+  unsigned long long* bitsb = p.keepbits + (size_t)unit * p.kb_stride;
+  for (int wd = threadIdx.x; wd < nwords; wd += blockDim.x) {
+    const int lo = first + wd * 64;   // first slot of this word
+    unsigned long long w = 0ull;
+    if (lo < ul.L0) {
+      w = bitsb[lo >> 6];
+      if (ul.L0 - lo < 64) w &= (1ull << (ul.L0 - lo)) - 1ull;   // slots that never held a key
+    }
+    if (ul.appended && ul.L0 >= lo && ul.L0 < lo + 64) {
+      w |= 1ull << (ul.L0 - lo);
+      if (owns_new_slot) bitsb[lo >> 6] = w;
+    }
+    sh_live[wd] = w;
+  }
+  __syncthreads();
+}
+
+template <typename DT, int D, int G, bool LAZY>
 __global__ __launch_bounds__(WG) void corm_attend_kernel(const Params p) {
   using A = Attend<DT, D, G, WAVES>;
   constexpr int EPL = A::EPL, ROWB = A::ROWB, LPR = A::LPR, RPL = A::RPL;
@@ -282,6 +327,7 @@ __global__ __launch_bounds__(WG) void corm_attend_kernel(const Params p) {
   __shared__ float sh_z[G][WAVES];
   __shared__ float sh_acc[G][WAVES][D];
   __shared__ float sh_logit[G][CHUNK];   // raw logits of the chunk, stored to the workspace at the end
+  __shared__ unsigned long long sh_live[LAZY ? CHUNK / 64 : 1];
 
   char* Kb = reinterpret_cast<char*>(p.K) + (size_t)unit * p.Lcap * ROWB;
   char* Vb = reinterpret_cast<char*>(p.V) + (size_t)unit * p.Lcap * ROWB;
@@ -308,6 +354,8 @@ __global__ __launch_bounds__(WG) void corm_attend_kernel(const Params p) {
     }
     __syncthreads();
   }
+
+  if (LAZY) stage_live_masks(p, unit, ul, cbeg, CHUNK / 64, ul.appended && ul.L0 >= cbeg, sh_live);
 
   // this lane's slice of the G queries
   uint4 qreg[G];
@@ -340,15 +388,18 @@ __global__ __launch_bounds__(WG) void corm_attend_kernel(const Params p) {
   constexpr int PAIRS = CHUNK / (2 * A::STAGE_ROWS);
   static_assert(PAIRS >= 1 && CHUNK % (2 * A::STAGE_ROWS) == 0, "CHUNK must hold whole stage pairs");
   typename A::Stage s0, s1;
-  A::load(s0, rk, rv, off);
+  A::template load<LAZY>(s0, rk, rv, off, sh_live, lane_row);
 #pragma unroll
   for (int i = 0; i < PAIRS; ++i) {
     const int it = cbeg + i * 2 * A::STAGE_ROWS;
     if (it >= cend) break;
-    A::load(s1, rk, rv, off + (uint32_t)(2 * i + 1) * STAGE_BYTES);
+    A::template load<LAZY>(s1, rk, rv, off + (uint32_t)(2 * i + 1) * STAGE_BYTES, sh_live,
+                           (2 * i + 1) * A::STAGE_ROWS + lane_row);
     A::compute(s0, it + lane_row, it - cbeg + lane_row, cend, cl, qreg, p.scale_log2, &sh_logit[0][0], CHUNK, m_run,
                z_run, acc);
-    if (i + 1 < PAIRS) A::load(s0, rk, rv, off + (uint32_t)(2 * i + 2) * STAGE_BYTES);
+    if (i + 1 < PAIRS)
+      A::template load<LAZY>(s0, rk, rv, off + (uint32_t)(2 * i + 2) * STAGE_BYTES, sh_live,
+                             (2 * i + 2) * A::STAGE_ROWS + lane_row);
     A::compute(s1, it + A::STAGE_ROWS + lane_row, it - cbeg + A::STAGE_ROWS + lane_row, cend, cl, qreg,
                p.scale_log2, &sh_logit[0][0], CHUNK, m_run, z_run, acc);
   }
@@ -439,14 +490,25 @@ struct AttendGqa {
   struct Stage {
     uint4 k[4];  // A operand, k-blocks 0..3
     uint4 v[4];  // rows 4*j + lane/16 of the tile, this lane's 16-byte column slice
+    uint32_t live;   // lazy mode: bit i = key i of the tile is live
   };
 
+  // Lazy mode: sh_live holds the live masks (LDS), trow is the tile's first key relative to the first
+  // slot sh_live covers (a multiple of 16); the loads of dead keys get an out-of-range offset.
+  template <bool LAZY>
   __device__ static __forceinline__ void load(Stage& st, __amdgpu_buffer_rsrc_t rk, __amdgpu_buffer_rsrc_t rv,
-                                              uint32_t koff, uint32_t voff) {
+                                              uint32_t koff, uint32_t voff, const unsigned long long* sh_live,
+                                              int trow, int n, int lg) {
+    st.live = 0xffffu;
+    if (LAZY) st.live = (uint32_t)(sh_live[trow >> 6] >> (trow & 63)) & 0xffffu;
+    const bool klive = !LAZY || ((st.live >> n) & 1u);
 #pragma unroll
-    for (int kb = 0; kb < 4; ++kb) st.k[kb] = buffer_load16(rk, koff + (uint32_t)(64 * kb));
+    for (int kb = 0; kb < 4; ++kb) st.k[kb] = buffer_load16(rk, klive ? koff + (uint32_t)(64 * kb) : DEAD_OFFSET);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) st.v[j] = buffer_load16(rv, voff + (uint32_t)(j * 4 * ROWB));
+    for (int j = 0; j < 4; ++j) {
+      const bool vlive = !LAZY || ((st.live >> (4 * j + lg)) & 1u);
+      st.v[j] = buffer_load16(rv, vlive ? voff + (uint32_t)(j * 4 * ROWB) : DEAD_OFFSET);
+    }
   }
 
   // row0: first key of this wave's tile; lrel0: its index in the logit staging array
@@ -465,7 +527,7 @@ struct AttendGqa {
     for (int r = 0; r < 4; ++r) {
       const float v = d[r] * scale_log2;
       d[r] = v;
-      s[r] = (row0 + 4 * lg + r) < cend ? v : neg_inf();
+      s[r] = ((row0 + 4 * lg + r) < cend && ((st.live >> (4 * lg + r)) & 1u)) ? v : neg_inf();
       tmax = fmaxf(tmax, s[r]);
     }
     // the 16 keys of head n are spread over the four lane groups
@@ -506,7 +568,7 @@ struct AttendGqa {
   }
 };
 
-template <int G>
+template <int G, bool LAZY>
 __global__ __launch_bounds__(WG) void corm_attend_gqa_kernel(const Params p) {
   using A = AttendGqa<G>;
   constexpr int D = A::D, ROWB = A::ROWB, EPL = A::EPL, LPR = 16;
@@ -529,6 +591,7 @@ __global__ __launch_bounds__(WG) void corm_attend_gqa_kernel(const Params p) {
   __shared__ float sh_logit[G][CHUNK];
   __shared__ __attribute__((aligned(16))) float sh_p[WAVES][A::TILE * G];
   __shared__ __attribute__((aligned(16))) float sh_alpha[WAVES][G];
+  __shared__ unsigned long long sh_live[LAZY ? CHUNK / 64 : 1];
 
   char* Kb = reinterpret_cast<char*>(p.K) + (size_t)unit * p.Lcap * ROWB;
   char* Vb = reinterpret_cast<char*>(p.V) + (size_t)unit * p.Lcap * ROWB;
@@ -553,6 +616,8 @@ __global__ __launch_bounds__(WG) void corm_attend_gqa_kernel(const Params p) {
     }
     __syncthreads();
   }
+
+  if (LAZY) stage_live_masks(p, unit, ul, cbeg, CHUNK / 64, ul.appended && ul.L0 >= cbeg, sh_live);
 
   // B operand: column n < G holds query head n, elements 32*kb + 8*lg .. +8 in block kb
   uint4 qb[4];
@@ -582,16 +647,20 @@ __global__ __launch_bounds__(WG) void corm_attend_gqa_kernel(const Params p) {
   static_assert(PAIRS >= 1 && CHUNK % (2 * A::STAGE_ROWS) == 0, "CHUNK must hold whole stage pairs");
 
   typename A::Stage s0, s1;
-  A::load(s0, rk, rv, koff, voff);
+  A::template load<LAZY>(s0, rk, rv, koff, voff, sh_live, wv * A::TILE, n, lg);
 #pragma unroll
   for (int i = 0; i < PAIRS; ++i) {
     const int it = cbeg + i * 2 * A::STAGE_ROWS;
     if (it >= cend) break;
-    A::load(s1, rk, rv, koff + (uint32_t)(2 * i + 1) * STAGE_BYTES, voff + (uint32_t)(2 * i + 1) * STAGE_BYTES);
+    A::template load<LAZY>(s1, rk, rv, koff + (uint32_t)(2 * i + 1) * STAGE_BYTES,
+                           voff + (uint32_t)(2 * i + 1) * STAGE_BYTES, sh_live,
+                           (2 * i + 1) * A::STAGE_ROWS + wv * A::TILE, n, lg);
     A::compute(s0, it + wv * A::TILE, it - cbeg + wv * A::TILE, cend, n, lg, qb, p.scale_log2, &sh_logit[0][0],
                CHUNK, sh_p[wv], sh_alpha[wv], m_run, z_run, acc);
     if (i + 1 < PAIRS)
-      A::load(s0, rk, rv, koff + (uint32_t)(2 * i + 2) * STAGE_BYTES, voff + (uint32_t)(2 * i + 2) * STAGE_BYTES);
+      A::template load<LAZY>(s0, rk, rv, koff + (uint32_t)(2 * i + 2) * STAGE_BYTES,
+                             voff + (uint32_t)(2 * i + 2) * STAGE_BYTES, sh_live,
+                             (2 * i + 2) * A::STAGE_ROWS + wv * A::TILE, n, lg);
     A::compute(s1, it + A::STAGE_ROWS + wv * A::TILE, it - cbeg + A::STAGE_ROWS + wv * A::TILE, cend, n, lg, qb,
                p.scale_log2, &sh_logit[0][0], CHUNK, sh_p[wv], sh_alpha[wv], m_run, z_run, acc);
   }
@@ -663,7 +732,7 @@ constexpr int UNIT_WAVES = UNIT_WG / 64;
 constexpr int UNIT_MAX_TILES = 24;   // 48 KiB of logits hold at most 12288 slots = 24 tiles of 512
 static_assert(UNIT_WG == CHUNK, "the unit kernel reports survivors per CHUNK slots, one tile each");
 
-template <typename DT, int D, int G>
+template <typename DT, int D, int G, bool LAZY>
 __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, const int lstride) {
   using A = Attend<DT, D, G, UNIT_WAVES>;
   constexpr int EPL = A::EPL, ROWB = A::ROWB, LPR = A::LPR, RPL = A::RPL;
@@ -674,6 +743,9 @@ __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, cons
   __shared__ float sh_acc[G][UNIT_WAVES][D];
   __shared__ float sh_M[G], sh_Z[G];
   __shared__ int sh_tilecnt[UNIT_MAX_TILES];
+  // live masks of every slot the pipeline may touch: it runs up to one super-chunk past the unit's end
+  constexpr int LIVE_WORDS = (UNIT_MAX_TILES * CHUNK + 2048) / 64;
+  __shared__ unsigned long long sh_live[LAZY ? LIVE_WORDS : 1];
 
   const int unit = blockIdx.x;
   const UnitLen ul = unit_len(p, unit);
@@ -716,6 +788,8 @@ __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, cons
     __syncthreads();
   }
 
+  if (LAZY) stage_live_masks(p, unit, ul, 0, LIVE_WORDS, true, sh_live);
+
   // metadata of the first record tile, fetched now and used after the stream
   int pos_next = posb[min(tid, L - 1)];
   int lh_next = lhb[min(tid, L - 1)];
@@ -746,16 +820,20 @@ __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, cons
   // pipeline drains between super-chunks; the other waves of the compute unit cover that gap.
   constexpr int PAIRS_U = 4;
   constexpr int SUPER_ROWS = 2 * PAIRS_U * A::STAGE_ROWS;
+  static_assert(SUPER_ROWS <= 2048, "sh_live covers one super-chunk past the last tile");
   typename A::Stage s0, s1;
   for (int c0 = 0; c0 < L; c0 += SUPER_ROWS) {
-    A::load(s0, rk, rv, off);
+    A::template load<LAZY>(s0, rk, rv, off, sh_live, c0 + lane_row);
 #pragma unroll
     for (int i = 0; i < PAIRS_U; ++i) {
       const int it = c0 + i * 2 * A::STAGE_ROWS;
       if (it >= L) break;
-      A::load(s1, rk, rv, off + (uint32_t)(2 * i + 1) * STAGE_BYTES);
+      A::template load<LAZY>(s1, rk, rv, off + (uint32_t)(2 * i + 1) * STAGE_BYTES, sh_live,
+                             it + A::STAGE_ROWS + lane_row);
       A::compute(s0, it + lane_row, it + lane_row, L, cl, qreg, p.scale_log2, sh_logit, lstride, m_run, z_run, acc);
-      if (i + 1 < PAIRS_U) A::load(s0, rk, rv, off + (uint32_t)(2 * i + 2) * STAGE_BYTES);
+      if (i + 1 < PAIRS_U)
+        A::template load<LAZY>(s0, rk, rv, off + (uint32_t)(2 * i + 2) * STAGE_BYTES, sh_live,
+                               it + 2 * A::STAGE_ROWS + lane_row);
       A::compute(s1, it + A::STAGE_ROWS + lane_row, it + A::STAGE_ROWS + lane_row, L, cl, qreg, p.scale_log2,
                  sh_logit, lstride, m_run, z_run, acc);
     }
@@ -830,7 +908,8 @@ __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, cons
     const int tile = kt * UNIT_WG;
     if (tile >= L) break;
     const int i = tile + tid;
-    const bool live = i < L;
+    // (lazy mode: a slot whose key was evicted earlier takes no part: nothing recorded, stays dead)
+    const bool live = i < L && (!LAZY || ((sh_live[i >> 6] >> (i & 63)) & 1ull));
     const int my_pos = pos_next;
     int lh = lh_next;
     if (kt + 1 < UNIT_MAX_TILES) {   // clamped index: always a live slot, no branch around the load
@@ -862,9 +941,11 @@ __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, cons
         lh = tcur;
         lhb[i] = tcur;
       }
-      keep = !full || (lh > tcur - p.w) || (i >= L - p.r);
-      if (p.do_evict && keepb) keepb[i] = keep ? 1 : 0;
+      // the r newest keys: the last r slots, or (lazy mode, where dead slots lie between) by position
+      const bool recent = LAZY ? (my_pos >= tcur - p.r) : (i >= L - p.r);
+      keep = !full || (lh > tcur - p.w) || recent;
     }
+    if (p.do_evict && keepb && i < L) keepb[i] = keep ? 1 : 0;
     if (p.do_evict) {
       const unsigned long long bal = __ballot(keep);
       if (lane == 0 && tile + wv * 64 < L) {
@@ -914,13 +995,16 @@ __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const i
   const int32_t* posb = p.pos + (size_t)unit * p.Lcap;
   int32_t* lhb = p.last_hit + (size_t)unit * p.Lcap;
   const float* logit_u = p.logits + (size_t)(b * p.Hq + hq0) * p.Lcap;
+  unsigned long long* bitsb = p.keepbits + (size_t)unit * p.kb_stride;
   int my_pos[KPT], my_lh[KPT];
+  bool my_live[KPT];   // lazy mode: the slot holds a key that was not evicted earlier
   float lg[KPT][G];
 #pragma unroll
   for (int k = 0; k < KPT; ++k) {
     const int i = min(rbeg + k * WG + tid, max(rend - 1, 0));   // clamped: a live slot (or 0 in an empty unit)
     my_pos[k] = posb[i];
     my_lh[k] = lhb[i];
+    my_live[k] = p.lazy ? ((bitsb[i >> 6] >> (i & 63)) & 1ull) != 0 : true;
 #pragma unroll
     for (int g = 0; g < G; ++g) lg[k][g] = logit_u[(size_t)g * p.Lcap + i];
   }
@@ -973,7 +1057,6 @@ __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const i
   const float thr = importance_threshold(p.thr_scale, step_ok ? tcur : 1);
   const bool full = p.do_evict && step_ok && (tcur - tfirst + 1 >= p.w);
   uint8_t* keepb = p.keep ? p.keep + (size_t)unit * p.Lcap : nullptr;
-  unsigned long long* bitsb = p.keepbits + (size_t)unit * p.kb_stride;
 
   int kept[RECORD_CHUNKS];
 #pragma unroll
@@ -981,7 +1064,7 @@ __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const i
 #pragma unroll
   for (int k = 0; k < KPT; ++k) {
     const int i = rbeg + k * WG + tid;
-    const bool live = i < rend;
+    const bool live = i < rend && my_live[k];
     bool keep = false;
     if (live) {
       const bool pos_ok = my_pos[k] >= 0 && my_pos[k] < p.Tcap;
@@ -1007,9 +1090,11 @@ __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const i
         lh = tcur;
         lhb[i] = tcur;
       }
-      keep = !full || (lh > tcur - p.w) || (i >= L - p.r);
-      if (p.do_evict && keepb) keepb[i] = keep ? 1 : 0;
+      // the r newest keys: the last r slots, or (lazy mode, where dead slots lie between) by position
+      const bool recent = p.lazy ? (my_pos[k] >= tcur - p.r) : (i >= L - p.r);
+      keep = !full || (lh > tcur - p.w) || recent;
     }
+    if (p.do_evict && keepb && i < rend) keepb[i] = keep ? 1 : 0;
     const unsigned long long bal = __ballot(keep);
     if (p.do_evict && lane == 0 && rbeg + k * WG + wv * 64 < rend) bitsb[((rbeg + k * WG) >> 6) + wv] = bal;
     kept[k / KPC] += __popcll(bal);
@@ -1494,16 +1579,36 @@ void bind_params(const corm_desc* d, const WorkspaceLayout& wl, void* workspace,
 int g_force_path = 0;
 int g_num_cus = 0;
 
-template <typename DT, int D>
+template <typename DT, int D, bool LAZY>
 int launch_attend_g(const Params& p, int G, dim3 grid, hipStream_t s) {
   switch (G) {
-    case 1: hipLaunchKernelGGL((corm_attend_kernel<DT, D, 1>), grid, dim3(WG), 0, s, p); break;
-    case 2: hipLaunchKernelGGL((corm_attend_kernel<DT, D, 2>), grid, dim3(WG), 0, s, p); break;
-    case 4: hipLaunchKernelGGL((corm_attend_kernel<DT, D, 4>), grid, dim3(WG), 0, s, p); break;
-    case 8: hipLaunchKernelGGL((corm_attend_kernel<DT, D, 8>), grid, dim3(WG), 0, s, p); break;
+    case 1: hipLaunchKernelGGL((corm_attend_kernel<DT, D, 1, LAZY>), grid, dim3(WG), 0, s, p); break;
+    case 2: hipLaunchKernelGGL((corm_attend_kernel<DT, D, 2, LAZY>), grid, dim3(WG), 0, s, p); break;
+    case 4: hipLaunchKernelGGL((corm_attend_kernel<DT, D, 4, LAZY>), grid, dim3(WG), 0, s, p); break;
+    case 8: hipLaunchKernelGGL((corm_attend_kernel<DT, D, 8, LAZY>), grid, dim3(WG), 0, s, p); break;
     default: return CORM_EUNSUPPORTED;
   }
   return launch_status();
+}
+
+template <bool LAZY>
+int launch_attend_gqa(const Params& p, int G, dim3 grid, hipStream_t s) {
+  switch (G) {
+    case 2: hipLaunchKernelGGL((corm_attend_gqa_kernel<2, LAZY>), grid, dim3(WG), 0, s, p); break;
+    case 4: hipLaunchKernelGGL((corm_attend_gqa_kernel<4, LAZY>), grid, dim3(WG), 0, s, p); break;
+    case 8: hipLaunchKernelGGL((corm_attend_gqa_kernel<8, LAZY>), grid, dim3(WG), 0, s, p); break;
+    default: return CORM_EUNSUPPORTED;
+  }
+  return launch_status();
+}
+
+template <bool LAZY>
+int launch_attend_dt(const corm_desc* d, const Params& p, int G, dim3 grid, hipStream_t s) {
+  if (d->kv_dtype == CORM_F32)
+    return d->d == 64 ? launch_attend_g<F32, 64, LAZY>(p, G, grid, s) : launch_attend_g<F32, 128, LAZY>(p, G, grid, s);
+  // grouped queries, bf16, d = 128: q.K^T on the matrix cores
+  if (d->d == 128 && G > 1 && g_force_path != 3) return launch_attend_gqa<LAZY>(p, G, grid, s);
+  return d->d == 64 ? launch_attend_g<BF16, 64, LAZY>(p, G, grid, s) : launch_attend_g<BF16, 128, LAZY>(p, G, grid, s);
 }
 
 int launch_attend(const corm_desc* d, const Params& p, hipStream_t s) {
@@ -1512,21 +1617,7 @@ int launch_attend(const corm_desc* d, const Params& p, hipStream_t s) {
   const hipEvent_t ev0 = g_prof_start, ev1 = g_prof_stop;
   g_prof_start = g_prof_stop = nullptr;
   if (ev0 && hipEventRecord(ev0, s) != hipSuccess) return CORM_EHIP;
-  int rc;
-  if (d->kv_dtype == CORM_F32) {
-    rc = d->d == 64 ? launch_attend_g<F32, 64>(p, G, grid, s) : launch_attend_g<F32, 128>(p, G, grid, s);
-  } else if (d->d == 128 && G > 1 && g_force_path != 3) {
-    // grouped queries, bf16, d = 128: q.K^T on the matrix cores
-    switch (G) {
-      case 2: hipLaunchKernelGGL((corm_attend_gqa_kernel<2>), grid, dim3(WG), 0, s, p); break;
-      case 4: hipLaunchKernelGGL((corm_attend_gqa_kernel<4>), grid, dim3(WG), 0, s, p); break;
-      case 8: hipLaunchKernelGGL((corm_attend_gqa_kernel<8>), grid, dim3(WG), 0, s, p); break;
-      default: return CORM_EUNSUPPORTED;
-    }
-    rc = launch_status();
-  } else {
-    rc = d->d == 64 ? launch_attend_g<BF16, 64>(p, G, grid, s) : launch_attend_g<BF16, 128>(p, G, grid, s);
-  }
+  const int rc = p.lazy ? launch_attend_dt<true>(d, p, G, grid, s) : launch_attend_dt<false>(d, p, G, grid, s);
   if (rc) return rc;
   if (ev1 && hipEventRecord(ev1, s) != hipSuccess) return CORM_EHIP;
   return CORM_OK;
@@ -1557,15 +1648,30 @@ bool use_unit_path(const corm_desc* d) {
   return d->B * d->Hkv >= g_num_cus;
 }
 
-template <typename DT, int D>
+template <typename DT, int D, bool LAZY>
 int launch_unit_g(const Params& p, int G, int units, size_t lds, int lstride, hipStream_t s) {
   switch (G) {
-    case 1: hipLaunchKernelGGL((corm_unit_kernel<DT, D, 1>), dim3(units), dim3(UNIT_WG), lds, s, p, lstride); break;
-    case 2: hipLaunchKernelGGL((corm_unit_kernel<DT, D, 2>), dim3(units), dim3(UNIT_WG), lds, s, p, lstride); break;
-    case 4: hipLaunchKernelGGL((corm_unit_kernel<DT, D, 4>), dim3(units), dim3(UNIT_WG), lds, s, p, lstride); break;
+    case 1:
+      hipLaunchKernelGGL((corm_unit_kernel<DT, D, 1, LAZY>), dim3(units), dim3(UNIT_WG), lds, s, p, lstride);
+      break;
+    case 2:
+      hipLaunchKernelGGL((corm_unit_kernel<DT, D, 2, LAZY>), dim3(units), dim3(UNIT_WG), lds, s, p, lstride);
+      break;
+    case 4:
+      hipLaunchKernelGGL((corm_unit_kernel<DT, D, 4, LAZY>), dim3(units), dim3(UNIT_WG), lds, s, p, lstride);
+      break;
     default: return CORM_EUNSUPPORTED;
   }
   return launch_status();
+}
+
+template <bool LAZY>
+int launch_unit_dt(const corm_desc* d, const Params& p, int G, int units, size_t lds, int lstride, hipStream_t s) {
+  if (d->kv_dtype == CORM_F32)
+    return d->d == 64 ? launch_unit_g<F32, 64, LAZY>(p, G, units, lds, lstride, s)
+                      : launch_unit_g<F32, 128, LAZY>(p, G, units, lds, lstride, s);
+  return d->d == 64 ? launch_unit_g<BF16, 64, LAZY>(p, G, units, lds, lstride, s)
+                    : launch_unit_g<BF16, 128, LAZY>(p, G, units, lds, lstride, s);
 }
 
 int launch_unit(const corm_desc* d, const Params& p, hipStream_t s) {
@@ -1575,14 +1681,8 @@ int launch_unit(const corm_desc* d, const Params& p, hipStream_t s) {
   const hipEvent_t ev0 = g_prof_start, ev1 = g_prof_stop;
   g_prof_start = g_prof_stop = nullptr;
   if (ev0 && hipEventRecord(ev0, s) != hipSuccess) return CORM_EHIP;
-  int rc;
-  if (d->kv_dtype == CORM_F32) {
-    rc = d->d == 64 ? launch_unit_g<F32, 64>(p, G, units, lds, lstride, s)
-                    : launch_unit_g<F32, 128>(p, G, units, lds, lstride, s);
-  } else {
-    rc = d->d == 64 ? launch_unit_g<BF16, 64>(p, G, units, lds, lstride, s)
-                    : launch_unit_g<BF16, 128>(p, G, units, lds, lstride, s);
-  }
+  const int rc = p.lazy ? launch_unit_dt<true>(d, p, G, units, lds, lstride, s)
+                        : launch_unit_dt<false>(d, p, G, units, lds, lstride, s);
   if (rc) return rc;
   if (ev1 && hipEventRecord(ev1, s) != hipSuccess) return CORM_EHIP;
   return CORM_OK;
@@ -1848,6 +1948,38 @@ int corm_decode_step(const corm_desc* desc, const void* q, const void* k_new, co
                         workspace, workspace_bytes, status, stream);
   if (rc) return rc;
   return corm_step_evict(desc, K, V, lens, pos, last_hit, kept_idx, workspace, workspace_bytes, stream);
+}
+
+int corm_decode_step_lazy(const corm_desc* desc, const void* q, const void* k_new, const void* v_new, void* K, void* V,
+                          int32_t* lens, uint64_t* live, int32_t* pos, int32_t* last_hit, const int32_t* t,
+                          const int32_t* t_first, void* score_ring, float* out, uint8_t* keep, int32_t* nlive,
+                          int32_t dead_num, int32_t dead_den, void* workspace, size_t workspace_bytes,
+                          int32_t* status, void* stream) {
+  int rc = validate_desc(desc);
+  if (rc) return rc;
+  rc = check_step_pointers(q, k_new, v_new, K, V, lens, pos, last_hit, t, t_first, score_ring, out, nlive, status);
+  if (rc) return rc;
+  if (!live || (reinterpret_cast<uintptr_t>(live) & 7u)) return CORM_EINVAL;
+  if (dead_num < 0 || dead_den < 1 || dead_num > dead_den) return CORM_EINVAL;
+  WorkspaceLayout wl;
+  rc = check_workspace(desc, workspace, workspace_bytes, &wl);
+  if (rc) return rc;
+  Params p = {};
+  p.q = q; p.k_new = k_new; p.v_new = v_new; p.K = K; p.V = V; p.lens = lens; p.pos = pos;
+  p.last_hit = last_hit; p.t = t; p.t_first = t_first; p.ring = score_ring; p.out = out; p.keep = keep;
+  p.status = status;
+  p.do_append = 1; p.do_evict = 1;
+  bind_params(desc, wl, workspace, p);
+  p.lazy = 1;
+  p.keepbits = reinterpret_cast<unsigned long long*>(live);   // the live masks are read, then replaced by the new ones
+  rc = launch_attend_record(desc, p, (hipStream_t)stream);
+  if (rc) return rc;
+  CompactPolicy pol;
+  pol.lazy = 1; pol.dead_num = dead_num; pol.dead_den = dead_den;
+  pol.live = reinterpret_cast<unsigned long long*>(live);
+  pol.nlive = nlive;
+  return launch_compact(desc, wl, workspace, K, V, pos, last_hit, lens, nullptr, nullptr, 1, false, pol,
+                        (hipStream_t)stream);
 }
 
 int corm_selected_path(const corm_desc* desc) {

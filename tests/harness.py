@@ -56,17 +56,37 @@ def _f32(t: torch.Tensor) -> np.ndarray:
     return t.detach().float().cpu().numpy()
 
 
-def check_unit_state(st: corm.LayerState, b: int, h: int, u: O.UnitCache, t: int) -> None:
-    """Device cache of unit (b,h) == the oracle's, bit for bit (rows, order, positions, lens)."""
+def live_slots(st: corm.LayerState, b: int, h: int) -> np.ndarray:
+    """Slots of unit (b,h) below lens whose live bit is set (deferred compaction), ascending."""
     l = int(st.lens[b, h].item())
-    assert l == u.l, (b, h, l, u.l)
-    assert np.array_equal(st.pos[b, h, :l].cpu().numpy().astype(np.int64), u.positions), (b, h)
-    Kd = _f32(st.K[b, h, :l]).astype(np.float64)
-    Vd = _f32(st.V[b, h, :l]).astype(np.float64)
+    words = st.live[b, h].cpu().numpy()
+    bits = np.unpackbits(words.view(np.uint8), bitorder="little")[:l]
+    return np.nonzero(bits)[0]
+
+
+def check_unit_state(st: corm.LayerState, b: int, h: int, u: O.UnitCache, t: int, lazy: bool = False) -> None:
+    """Device cache of unit (b,h) == the oracle's, bit for bit (rows, order, positions, lens).
+
+    lazy: the device defers compaction; its live slots, read in slot order, must be the oracle's cache."""
+    if lazy:
+        sl = live_slots(st, b, h)
+        assert len(sl) == u.l, (b, h, len(sl), u.l)
+        assert int(st.nlive[b, h].item()) == u.l, (b, h, "nlive")
+        sel = torch.from_numpy(sl).to(st.K.device)
+        pos_d, K_d, V_d = st.pos[b, h].index_select(0, sel), st.K[b, h].index_select(0, sel), st.V[b, h].index_select(0, sel)
+        lh_d = st.last_hit[b, h].index_select(0, sel)
+        l = u.l
+    else:
+        l = int(st.lens[b, h].item())
+        assert l == u.l, (b, h, l, u.l)
+        pos_d, K_d, V_d, lh_d = st.pos[b, h, :l], st.K[b, h, :l], st.V[b, h, :l], st.last_hit[b, h, :l]
+    assert np.array_equal(pos_d.cpu().numpy().astype(np.int64), u.positions), (b, h)
+    Kd = _f32(K_d).astype(np.float64)
+    Vd = _f32(V_d).astype(np.float64)
     assert np.array_equal(Kd, u.keys), (b, h, "K rows")
     assert np.array_equal(Vd, u.values), (b, h, "V rows")
     # last_hit summary vs the oracle's message window
-    lh = st.last_hit[b, h, :l].cpu().numpy()
+    lh = lh_d.cpu().numpy()
     m = u.message.shape[0]
     steps = np.asarray(u.row_steps[-m:], dtype=np.int64) if m else np.zeros((0,), dtype=np.int64)
     hit_any = u.message.any(axis=1) if m else np.zeros((0, l), dtype=bool)       # [m, l]
@@ -78,11 +98,16 @@ def check_unit_state(st: corm.LayerState, b: int, h: int, u: O.UnitCache, t: int
 def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_scale=1.0, check_state_every=1,
                           units: Optional[Sequence[Tuple[int, int]]] = None, steps: Optional[int] = None,
                           use_split_calls=False, seq_offsets: Optional[Sequence[int]] = None,
-                          Lcap: Optional[int] = None, Tcap: Optional[int] = None) -> Dict:
+                          Lcap: Optional[int] = None, Tcap: Optional[int] = None,
+                          lazy: Optional[Tuple[int, int]] = None) -> Dict:
     """Run replay + decode on the device, slaving one oracle per checked unit.  Returns a report.
 
     seq_offsets[b]: sequence b behaves as if o_b tokens preceded its prompt (their keys already evicted):
-    its positions and its step counter t are shifted by o_b, so sequences of one batch sit at different steps."""
+    its positions and its step counter t are shifted by o_b, so sequences of one batch sit at different steps.
+
+    lazy = (dead_num, dead_den): run corm_decode_step_lazy with that compaction policy; the oracle (which
+    compacts at every step, as Algorithm 1 does) is compared with the device's live slots in slot order, and
+    the policy itself (when a unit was compacted) is checked against its definition."""
     x_cpu = inputs.make_layer(wl, layer, device="cpu")
     x = {k: v.to(device) for k, v in x_cpu.items() if k != "sinks"}
     n_replay = min(wl.w, wl.P)
@@ -107,6 +132,10 @@ def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_sca
     worst_score = 0.0
     flips = 0
     evicted_total = 0
+    compactions = 0
+    cap = st.Lcap
+    slots_before = {u: np.arange(pre) for u in units}     # lazy mode: live slots and slots in use before a step
+    used_before = {u: pre for u in units}
     for j in range(n_steps):
         q, k, v, t = step_inputs(wl, x, j, n_replay)
         t_dev = torch.full((wl.B,), t, dtype=torch.int32, device=device) + offs_dev
@@ -122,6 +151,8 @@ def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_sca
                 lb = int(lens_before[b, h])
                 assert torch.equal(keep_lit[b, h, :lb], st.keep[b, h, :lb]), ("literal vs summary mask", j, b, h)
             corm.corm_compact(st.desc, st.K, st.V, st.pos, st.last_hit, st.lens, st.keep, st.kept_idx, st.workspace)
+        elif lazy is not None:
+            st.step_lazy(q, k, v, t_dev, t_first, dead_num=lazy[0], dead_den=lazy[1])
         else:
             st.step(q, k, v, t_dev, t_first)
         torch.cuda.synchronize()
@@ -142,9 +173,24 @@ def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_sca
             recorded = ring_rows[b][h * G:(h + 1) * G][:, live_pos]
             res = u.step(qc[b, h * G:(h + 1) * G], kc[b, h], vc[b, h], tb, recorded=recorded)
             l = len(live_pos)
-            assert np.array_equal(keep_d[b, h, :l].astype(bool), res["keep"]), ("keep", j, b, h)
-            assert int(lens_d[b, h]) == u.l, ("lens", j, b, h, int(lens_d[b, h]), u.l)
-            assert np.array_equal(idx_d[b, h, :u.l].astype(np.int64), res["indices"]), ("kept_idx", j, b, h)
+            if lazy is None:
+                assert np.array_equal(keep_d[b, h, :l].astype(bool), res["keep"]), ("keep", j, b, h)
+                assert int(lens_d[b, h]) == u.l, ("lens", j, b, h, int(lens_d[b, h]), u.l)
+                assert np.array_equal(idx_d[b, h, :u.l].astype(np.int64), res["indices"]), ("kept_idx", j, b, h)
+            else:
+                L = used_before[(b, h)] + 1                                   # slots in use after the append
+                sl = np.concatenate([slots_before[(b, h)], [L - 1]])           # slots of the oracle's keys
+                kd = keep_d[b, h, :L].astype(bool)
+                assert np.array_equal(kd[sl], res["keep"]), ("keep (live slots)", j, b, h)
+                assert int(kd.sum()) == int(res["keep"].sum()), ("a dead slot was revived", j, b, h)
+                T = u.l
+                want_compact = T < L and ((L - T) * lazy[1] >= L * lazy[0] or L + 1 >= cap)
+                assert int(lens_d[b, h]) == (T if want_compact else L), ("lens / policy", j, b, h, L, T)
+                compactions += int(want_compact)
+                now = live_slots(st, b, h)
+                assert np.array_equal(now, np.arange(T) if want_compact else sl[res["keep"]]), ("live", j, b, h)
+                slots_before[(b, h)] = now
+                used_before[(b, h)] = int(lens_d[b, h])
             evicted_total += l - u.l
             for g in range(G):
                 e = out_rel_err(out[b, h * G + g].astype(np.float64), res["out"][g])
@@ -158,8 +204,8 @@ def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_sca
             own = O.important(O.round_to_storage(res["alpha"], wl.dtype), tb, thr_scale)
             flips += int((own != O.important(recorded, tb, thr_scale)).sum())
             if check_state_every and ((j + 1) % check_state_every == 0 or j == n_steps - 1):
-                check_unit_state(st, b, h, u, tb)
-    return {"steps": n_steps, "units": len(units), "worst_out_rel_err": worst_out,
+                check_unit_state(st, b, h, u, tb, lazy=lazy is not None)
+    return {"compactions": compactions, "steps": n_steps, "units": len(units), "worst_out_rel_err": worst_out,
             "worst_score_err_over_bound": worst_score, "importance_flips_vs_fp64": flips,
             "evicted_total": evicted_total, "final_lens": st.lens.cpu().numpy().tolist()}
 

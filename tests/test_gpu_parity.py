@@ -66,6 +66,96 @@ def test_slaved_trajectory(name):
         assert rep["evicted_total"] > 0, "nothing was evicted: compaction not exercised"
 
 
+# deferred compaction: the same trajectories, the oracle still compacting at every step
+LAZY = {
+    "tiny_f32": (1, 4),          # compact at 25 % dead slots
+    "bf16_mha": (1, 8),
+    "bf16_gqa4": (1, 4),
+    "bf16_gqa8": (1, 16),
+    "f32_d128": (1, 2),
+    "bf16_d64": (1, 4),
+    "r_lt_w": (1, 3),
+    "structured": (1, 4),
+    "sparse_layer": (1, 1),      # never by fraction: dead slots pile up until the unit is all dead rows or full
+}
+
+
+@pytest.mark.parametrize("name", list(LAZY))
+def test_lazy_trajectory(name):
+    """corm_decode_step_lazy: live keys in slot order, out, recorded scores and last_hit equal the
+    oracle's at every step, dead slots stay dead, and units are compacted exactly when the policy says."""
+    wl, every = TRAJ[name]
+    layer = 2 if name == "sparse_layer" else 0
+    say("lazy trajectory", name, LAZY[name], wl)
+    rep = harness.run_slaved_trajectory(wl, DEV, layer=layer, check_state_every=every, lazy=LAZY[name])
+    say("report", name, {k: v for k, v in rep.items() if k != "final_lens"})
+    assert rep["evicted_total"] > 0
+    if name != "sparse_layer":
+        assert rep["compactions"] > 0, "no unit was ever compacted: the policy branch is not exercised"
+
+
+def test_lazy_with_zero_fraction_is_the_exact_step():
+    """dead_num = 0 compacts at every eviction: slot for slot the state corm_decode_step leaves."""
+    wl, _ = TRAJ["bf16_mha"]
+    x = {k: v.to(DEV) for k, v in inputs.make_layer(wl, 0, device="cpu").items() if k != "sinks"}
+    n_replay = min(wl.w, wl.P)
+    pre = wl.P - n_replay
+    sts = [harness.make_state(wl, DEV), harness.make_state(wl, DEV)]
+    for st in sts:
+        st.preload(x["K0"][:, :, :pre], x["V0"][:, :, :pre])
+    tf = torch.full((wl.B,), pre + 1, dtype=torch.int32, device=DEV)
+    for j in range(n_replay + wl.D):
+        q, k, v, t = harness.step_inputs(wl, x, j, n_replay)
+        td = torch.full((wl.B,), t, dtype=torch.int32, device=DEV)
+        sts[0].step(q, k, v, td, tf)
+        sts[1].step_lazy(q, k, v, td, tf, dead_num=0, dead_den=1)
+        torch.cuda.synchronize()
+        assert torch.equal(sts[0].lens, sts[1].lens), j
+        assert torch.equal(sts[0].lens, sts[1].nlive), j
+        assert torch.equal(sts[0].out, sts[1].out), j
+        assert torch.equal(sts[0].keep, sts[1].keep), j
+    for name in ("K", "V", "pos", "last_hit", "ring"):
+        a, b = getattr(sts[0], name), getattr(sts[1], name)
+        for bb in range(wl.B):
+            for h in range(wl.Hkv):
+                l = int(sts[0].lens[bb, h].item())
+                if name == "ring":
+                    continue
+                assert torch.equal(a[bb, h, :l], b[bb, h, :l]), (name, bb, h)
+    assert torch.equal(sts[0].ring, sts[1].ring)
+    assert int(sts[1].status.item()) == 0
+
+
+def test_lazy_unit_out_of_slots_compacts_or_flags():
+    """A capacity far below the sequence length: deferred compaction must compact in time (slots about to
+    run out), and the status flag is raised only when the live keys themselves no longer fit."""
+    wl = W["tiny_f32"].replace(P=96, D=60, w=8, r=5)
+    say("lazy, Lcap << Tcap")
+    rep = harness.run_slaved_trajectory(wl, DEV, thr_scale=1e9, check_state_every=1, Lcap=100, Tcap=96 + 60,
+                                        lazy=(1, 1))
+    say("report", rep)
+    # the fraction alone never triggers (dead < slots): every unit is compacted once, when its slots run out
+    assert rep["compactions"] == wl.B * wl.Hkv and rep["evicted_total"] > 0
+
+
+def test_lazy_bad_arguments():
+    wl = W["tiny_f32"]
+    st = harness.make_state(wl, DEV)
+    q = torch.zeros(wl.B, wl.Hq, wl.d, device=DEV)
+    k = torch.zeros(wl.B, wl.Hkv, wl.d, device=DEV)
+    t = torch.ones(wl.B, dtype=torch.int32, device=DEV)
+    args = (st.desc, q, k, k, st.K, st.V, st.lens)
+    rest = (st.pos, st.last_hit, t, t, st.ring, st.out)
+    kw = dict(workspace=st.workspace, status=st.status, check=False)
+    assert corm.corm_decode_step_lazy(*args, None, *rest, **kw) == corm.CORM_EINVAL
+    assert corm.corm_decode_step_lazy(*args, st.live.data_ptr() + 4, *rest, **kw) == corm.CORM_EINVAL
+    assert corm.corm_decode_step_lazy(*args, st.live, *rest, dead_num=-1, **kw) == corm.CORM_EINVAL
+    assert corm.corm_decode_step_lazy(*args, st.live, *rest, dead_num=3, dead_den=2, **kw) == corm.CORM_EINVAL
+    assert corm.corm_decode_step_lazy(*args, st.live, *rest, dead_num=1, dead_den=0, **kw) == corm.CORM_EINVAL
+    torch.cuda.synchronize()
+    assert int(st.lens.sum().item()) == 0   # nothing ran
+
+
 def test_split_calls_equal_the_fused_step():
     """append + decode_attend + evict_mask (literal, also == summary) + compact: the same bits
     as the fused step, checked against the same oracle."""
