@@ -41,6 +41,9 @@ def parse():
                     help="layers are issued round-robin on this many streams (they are independent)")
     ap.add_argument("--path", type=int, default=0, choices=[0, 1, 2, 3],
                     help="corm_force_path: 0 by shape, 1 split kernels, 2 one workgroup per unit, 3 split without MFMA")
+    ap.add_argument("--lazy-frac", default=None, metavar="NUM/DEN",
+                    help="deferred compaction (corm_decode_step_lazy): a unit is compacted once NUM/DEN of its "
+                         "slots are dead; default: compact at every step (corm_decode_step)")
     ap.add_argument("--extra-steps", type=int, default=4, help="untimed single-stream steps after the timed region "
                     "(exclusive measurement of the dominant kernel)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -116,6 +119,8 @@ def main():
     ws = torch.empty(corm.corm_workspace_bytes(desc), dtype=torch.uint8, device=dev)
     corm.corm_workspace_init(desc, ws)
     lens_all = torch.zeros(layers, B, Hkv, dtype=torch.int32, device=dev)
+    lazy = tuple(int(v) for v in args.lazy_frac.split("/")) if args.lazy_frac else None
+    nlive_all = torch.zeros(layers, B, Hkv, dtype=torch.int32, device=dev)   # lazy mode: live keys per unit
     states, Qs, Kns, Vns = [], [], [], []
     pre = wl.P - n_replay
     t_all = (torch.arange(n_replay + n_dec, dtype=torch.int32, device=dev) + (pre + 1)).view(-1, 1).repeat(1, B)
@@ -123,6 +128,7 @@ def main():
     for l in range(layers):
         st = corm.LayerState(B, Hq, Hkv, d, Lcap, Tcap, wl.w, wl.r, wl.dtype, device=dev, workspace=ws)
         st.lens = lens_all[l]
+        st.nlive = nlive_all[l]
         x = inputs.make_layer(wl, l, device=dev, n_decode=n_dec, n_replay=n_replay)
         st.preload(x["K0"][:, :, :pre], x["V0"][:, :, :pre])
         # keys/values of the replayed prompt tail in step-major layout, then the decode tokens
@@ -147,16 +153,23 @@ def main():
     for extra in streams[1:]:
         extra.wait_stream(main)
 
+    def layer_step(l, j, tj, wsk, stream):
+        st = states[l]
+        if lazy:
+            corm.corm_decode_step_lazy(st.desc, Qs[l][j], Kns[l][j], Vns[l][j], st.K, st.V, st.lens, st.live, st.pos,
+                                       st.last_hit, tj, t_first, st.ring, st.out, None, st.nlive, lazy[0], lazy[1],
+                                       wsk, status=st.status, stream=stream)
+        else:
+            corm.corm_decode_step(st.desc, Qs[l][j], Kns[l][j], Vns[l][j], st.K, st.V, st.lens, st.pos, st.last_hit,
+                                  tj, t_first, st.ring, st.out, None, None, wsk, status=st.status, stream=stream)
+
     def run_step(j, probe_layer=-1, probe_events=None):
         tj = t_all[j]
         for l in range(layers):
-            st = states[l]
             if l == probe_layer:
                 corm.corm_profile_attend(probe_events[0], probe_events[1])
             k = l % len(streams)
-            corm.corm_decode_step(st.desc, Qs[l][j], Kns[l][j], Vns[l][j], st.K, st.V, st.lens, st.pos, st.last_hit,
-                                  tj, t_first, st.ring, st.out, None, None, wss[k], status=st.status,
-                                  stream=streams[k])
+            layer_step(l, j, tj, wss[k], streams[k])
 
     def join():
         for extra in streams[1:]:
@@ -171,13 +184,15 @@ def main():
         run_step(j)
     join()
     torch.cuda.synchronize()
+    # keys_all: the live keys per unit (what the next step attends to); lens_all also counts dead slots
+    keys_all = nlive_all if lazy else lens_all
     log(f"prompt replay ({n_replay} positions) {time.time() - t0:.1f}s; "
-        f"live fraction after the prompt {lens_all.float().mean().item() / wl.P:.4f}")
+        f"live fraction after the prompt {keys_all.float().mean().item() / wl.P:.4f}")
     assert all(int(s.status.item()) == 0 for s in states)
 
     # ---------------- CPU baseline: the oracle, timed on a bounded sample of the same workload
     cpu_baseline = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not lazy:   # (the oracle is rebuilt from compacted device snapshots)
         cpu_baseline = cpu_baseline_leg(args, wl, states, Qs, Kns, Vns, n_replay, pre, layers)
 
     if args.calibrate_copy:
@@ -192,7 +207,7 @@ def main():
         run_step(j)
     join()
     lens_hist = torch.empty(K_steps + 1, layers, B, Hkv, dtype=torch.int32, device=dev)
-    lens_hist[0].copy_(lens_all)
+    lens_hist[0].copy_(keys_all)
     # HIP events around the attend kernel of ONE launch per step (layer k mod layers), recorded by the
     # library on the stream it launches on: the dominant kernel's duration, measured inside the timed region
     hip = HipEvents()
@@ -204,7 +219,7 @@ def main():
     for k in range(K_steps):
         run_step(n_replay + W_steps + k, probe_layer=k % layers, probe_events=pairs[k])
         join()                             # the step ends when every stream has finished it
-        lens_hist[k + 1].copy_(lens_all)   # one tiny copy per step: the live lengths the next step starts from
+        lens_hist[k + 1].copy_(keys_all)   # one tiny copy per step: the live lengths the next step starts from
         fork()
     ev1.record()
     torch.cuda.synchronize()
@@ -227,13 +242,11 @@ def main():
     for s in range(n_probe_steps):
         j = n_replay + W_steps + K_steps + s
         tj = t_all[j]
-        lens_now = lens_all.clone()
+        lens_now = keys_all.clone()
         for l in range(layers):
-            st = states[l]
             pr = (hip.create(), hip.create())
             corm.corm_profile_attend(pr[0], pr[1])
-            corm.corm_decode_step(st.desc, Qs[l][j], Kns[l][j], Vns[l][j], st.K, st.V, st.lens, st.pos, st.last_hit,
-                                  tj, t_first, st.ring, st.out, None, None, wss[0], status=st.status, stream=main)
+            layer_step(l, j, tj, wss[0], main)
             probe_pairs.append(pr)
             probe_bytes.append(algorithmic_bytes(lens_now[l], wl, esz, ssz, "attend"))
     torch.cuda.synchronize()
@@ -256,6 +269,8 @@ def main():
         "config": {"workload": wl.name + ("+structured_queries" if args.structured else ""),
                    "layers": layers, "batch": B, "q_heads": Hq, "kv_heads": Hkv, "head_dim": d,
                    "prompt": wl.P, "w": wl.w, "r": wl.r, "tokens_per_step": B, "streams": args.streams, "path": corm.corm_selected_path(desc),
+                   "compaction": f"deferred until {lazy[0]}/{lazy[1]} of a unit's slots are dead" if lazy
+                   else "at every step",
                    "live_fraction_end": live_end, "keys_evicted_in_timed_region": evicted},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,

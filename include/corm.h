@@ -184,6 +184,32 @@ int corm_decode_step_lazy(const corm_desc* desc, const void* q, const void* k_ne
                           int32_t dead_num, int32_t dead_den, void* workspace, size_t workspace_bytes,
                           int32_t* status, void* stream);
 
+/* Seeds the recent-query window from a prompt, in place of replaying its last m tokens through
+ * corm_decode_step.  The paper starts Algorithm 1 from an existing message and does not say how a prompt
+ * fills it; the reading taken is that prompt tokens are ordinary steps: the query at step tau (1-based)
+ * attends causally to positions 0..tau-1 (Eq. 2), its scores are thresholded at c/tau (Def. 3.1) and
+ * recorded, and the first eviction (Def. 4.1 + recent r, Algorithm 1's gather) fires once w rows exist.
+ * Only the last m <= w queries can still be in the window when the prompt ends, so only they are needed.
+ *   q_tail     device [B, Hq, m, d], kv_dtype: the prompt's last m queries, oldest first; query j belongs to
+ *              step tau_j = t[b] - m + 1 + j.
+ *   K, V, lens, pos   the cache already holding every prompt key (lens[b,h] slots, ascending positions);
+ *              a key is visible to query j iff pos <= tau_j - 1.
+ *   t          device int32 [B]: step of the last prompt token (the prompt's length, plus any offset).
+ *   t_first    device int32 [B], OUT: t[b] - m + 1, as the decode calls expect it afterwards.
+ *   last_hit   in/out: raised to the latest step at which a recorded score of the key reached the threshold.
+ *   score_ring the rows of steps tau_0..tau_{m-1} are written at the keys' positions (16-byte aligned base).
+ *   keep, kept_idx   optional, as in corm_compact: the decision per slot and the old slot of each survivor.
+ * If m == w the units are then compacted exactly as corm_decode_step would after its w-th recorded step;
+ * if m < w nothing is evicted yet.  Result: the state m calls of corm_decode_step would leave (same keep
+ * decisions for the same recorded scores; the scores themselves agree within fp32 rounding), without `out`.
+ * q.K^T runs on the matrix cores (bf16: v_mfma_f32_16x16x32_bf16, fp32: v_mfma_f32_16x16x4_f32).
+ * Errors: CORM_EINVAL also for m < 1 or m > w; device status CORM_DEV_BAD_STEP if t[b] - m < 0,
+ * t[b] > Tcap, or a position lies outside [0, Tcap). */
+int corm_prefill_seed(const corm_desc* desc, const void* q_tail, int32_t m, void* K, void* V, int32_t* lens,
+                      int32_t* pos, int32_t* last_hit, const int32_t* t, int32_t* t_first, void* score_ring,
+                      uint8_t* keep, int32_t* kept_idx, void* workspace, size_t workspace_bytes, int32_t* status,
+                      void* stream);
+
 /* Tuning / test knob (host call, process-wide, not thread safe): how attend + record are launched.
  * 0 = choose by shape (default); 1 = split kernels (several workgroups per unit, partials merged by a
  * second launch; grouped bf16 d=128 queries take q.K^T on the matrix cores); 2 = one workgroup per unit

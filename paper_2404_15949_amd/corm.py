@@ -22,7 +22,7 @@ CORM_DEV_UNIT_FULL, CORM_DEV_BAD_STEP, CORM_DEV_BAD_LENS = 1, 2, 4
 
 EXPORTS = ("corm_version", "corm_strerror", "corm_workspace_bytes", "corm_workspace_init", "corm_append",
            "corm_decode_attend", "corm_evict_mask", "corm_evict_mask_summary", "corm_compact",
-           "corm_decode_step", "corm_step_attend", "corm_step_evict", "corm_decode_step_lazy", "corm_force_path",
+           "corm_decode_step", "corm_step_attend", "corm_step_evict", "corm_decode_step_lazy", "corm_prefill_seed", "corm_force_path",
            "corm_selected_path", "corm_profile_attend", "corm_threshold")
 
 
@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
                                        vp, sz, i32p, vp]
         L.corm_decode_step_lazy.argtypes = [dp, vp, vp, vp, vp, vp, i32p, vp, i32p, i32p, i32p, i32p, vp, vp, vp,
                                             i32p, ctypes.c_int32, ctypes.c_int32, vp, sz, i32p, vp]
+        L.corm_prefill_seed.argtypes = [dp, vp, ctypes.c_int32, vp, vp, i32p, i32p, i32p, i32p, i32p, vp, vp, i32p,
+                                        vp, sz, i32p, vp]
         L.corm_threshold.argtypes = [ctypes.c_float, i32p, ctypes.c_int32, vp, vp]
         L.corm_profile_attend.argtypes = [vp, vp]
         for name in EXPORTS:
@@ -232,6 +234,17 @@ def corm_decode_step_lazy(desc, q, k_new, v_new, K, V, lens, live, pos, last_hit
     return _check(rc, "corm_decode_step_lazy") if check else rc
 
 
+def corm_prefill_seed(desc, q_tail, m, K, V, lens, pos, last_hit, t, t_first, score_ring, keep=None, kept_idx=None,
+                      workspace=None, workspace_bytes=None, status=None, stream=None, check=True) -> int:
+    nbytes = workspace_bytes
+    if nbytes is None:
+        nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib().corm_prefill_seed(ctypes.byref(desc), _ptr(q_tail), m, _ptr(K), _ptr(V), _ptr(lens), _ptr(pos),
+                                 _ptr(last_hit), _ptr(t), _ptr(t_first), _ptr(score_ring), _ptr(keep), _ptr(kept_idx),
+                                 _ptr(workspace), nbytes, _ptr(status), _stream(stream))
+    return _check(rc, "corm_prefill_seed") if check else rc
+
+
 def corm_profile_attend(start_event, stop_event, check=True) -> int:
     """start_event / stop_event: raw hipEvent_t handles (ints) or None."""
     rc = lib().corm_profile_attend(start_event, stop_event)
@@ -300,3 +313,9 @@ class LayerState:
                               self.last_hit, t, t_first, self.ring, self.out, self.keep, self.nlive, dead_num,
                               dead_den, self.workspace if workspace is None else workspace, status=self.status,
                               stream=stream)
+
+    def prefill_seed(self, q_tail, t, t_first, stream=None, workspace=None) -> None:
+        """q_tail [B,Hq,m,d]; the cache must already hold the whole prompt (preload)."""
+        corm_prefill_seed(self.desc, q_tail, q_tail.shape[2], self.K, self.V, self.lens, self.pos, self.last_hit, t,
+                          t_first, self.ring, self.keep, self.kept_idx,
+                          self.workspace if workspace is None else workspace, status=self.status, stream=stream)

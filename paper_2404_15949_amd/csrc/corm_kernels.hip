@@ -1410,6 +1410,335 @@ __global__ __launch_bounds__(WG) void corm_compact_boundary_kernel(const Compact
   }
 }
 
+// ---------------------------------------------------------------- prompt seeding (dense, matrix cores)
+//
+// The prompt's last m queries (steps tau_j = t - m + 1 + j) against all its keys: the causal rows of
+// Eq. 2, thresholded (Def. 3.1) into last_hit and stored in the ring exactly where m decode steps would
+// have put them.  [m x L] logits per head are a dense contraction, so q.K^T runs on the MFMA units; the
+// elementwise tail (exp, rounding, compare) and the ring store bound the rest.
+//
+// Key-major decomposition, the same inner loop twice:
+//   pass 1   workgroup = 256 (128) keys of a unit, loops over all query tiles: per query the max and the
+//            sum of exp over its keys -> partials [head, key block, query]
+//   merge    per query: max and 1/sum over the key blocks
+//   pass 2   same loop; p = exp2(s - max) / sum, stored to the ring row of the query's step at the key's
+//            position, and per key the latest step whose stored score reaches the threshold
+// The workgroup keeps its keys in registers as the A operand (lane l: key l%16 of a 16-key tile, the
+// 16 bytes 64*c + 16*(l/16) .. of each 64-byte chunk c of the row); a tile of 16 queries is the B
+// operand, loaded the same way.  D: lane l holds query l%16, keys 4*(l/16) .. +3 of the tile.
+
+struct PrefillArgs {
+  const void* q_tail;   // [B, Hq, m, d]
+  const void* K;
+  const int32_t* lens;
+  const int32_t* pos;
+  int32_t* last_hit;
+  const int32_t* t;
+  void* ring;
+  float2* part;    // [B*Hq, nkb, w]  (max, sum) per key block
+  float2* stats;   // [B*Hq, w]       (max, 1/sum)
+  int32_t* status;
+  int32_t Hq, Hkv, Lcap, Tcap, w, m, nkb, ring_bf16;
+  float thr_scale, scale_log2;
+};
+
+template <typename DT> struct PrefillMma;
+template <> struct PrefillMma<BF16> {
+  __device__ static __forceinline__ f32x4_t mma(const uint4& a, const uint4& b, f32x4_t c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c,
+                                                   0, 0, 0);
+  }
+};
+template <> struct PrefillMma<F32> {
+  // four k-steps of v_mfma_f32_16x16x4_f32: lane group l/16 supplies element 4*(l/16) + e of the chunk in step e
+  __device__ static __forceinline__ f32x4_t mma(const uint4& a, const uint4& b, f32x4_t c) {
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.z), __uint_as_float(b.z), c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
+    return c;
+  }
+};
+
+constexpr int PREFILL_SEG = 1024;   // queries whose pass-1 partials a workgroup holds in LDS at a time
+
+template <int ROWB>
+struct PrefillGeom {
+  static constexpr int NCH = ROWB / 64;            // 64-byte chunks of a row
+  static constexpr int T = NCH <= 4 ? 4 : 2;       // 16-key tiles per wave
+  static constexpr int KB = WAVES * T * 16;        // keys per workgroup
+};
+
+template <typename DT, int D, int PASS>
+__global__ __launch_bounds__(WG) void corm_prefill_kernel(const PrefillArgs a) {
+  constexpr int ROWB = D * DT::ESZ;
+  using Geo = PrefillGeom<ROWB>;
+  constexpr int NCH = Geo::NCH, T = Geo::T, KB = Geo::KB;
+  constexpr int NEVER = 0x7fffffff;   // position of a slot that holds no key: visible to no query
+
+  const int kb = blockIdx.x, unit = blockIdx.y;
+  const int b = unit / a.Hkv, hkv = unit - b * a.Hkv;
+  const int G = a.Hq / a.Hkv;
+  int L = a.lens[unit];
+  L = L < 0 ? 0 : (L > a.Lcap ? a.Lcap : L);
+  const int key_blk = kb * KB;
+  if (key_blk >= L) return;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int n = lane & 15, lg = lane >> 4;
+  const int tcur = a.t[b];
+  const int tau0 = tcur - a.m + 1;   // step of tail query 0
+  if (tau0 < 1 || tcur > a.Tcap) {
+    if (tid == 0 && a.status) atomicOr(a.status, CORM_DEV_BAD_STEP);
+    return;
+  }
+  const int s0 = (tau0 - 1) % a.w;   // ring slot of tail query 0
+
+  const char* Kb = reinterpret_cast<const char*>(a.K) + (size_t)unit * a.Lcap * ROWB;
+  const int32_t* posb = a.pos + (size_t)unit * a.Lcap;
+  const __amdgpu_buffer_rsrc_t rk = make_rsrc(Kb, (uint32_t)L * ROWB);
+  const int wkey0 = key_blk + wv * (T * 16);   // first key of this wave
+
+  uint4 ka[T][NCH];
+  int kp[T][4];      // positions of this lane's keys 4*lg .. 4*lg+3 of each tile
+  bool quad[T];      // the four are consecutive positions: one vector store per query
+#pragma unroll
+  for (int tl = 0; tl < T; ++tl) {
+#pragma unroll
+    for (int c = 0; c < NCH; ++c)
+      ka[tl][c] = buffer_load16(rk, (uint32_t)(wkey0 + tl * 16 + n) * ROWB + (uint32_t)(c * 64 + 16 * lg));
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int key = wkey0 + tl * 16 + 4 * lg + r;
+      int pk = key < L ? posb[key] : NEVER;
+      if (key < L && (pk < 0 || pk >= a.Tcap)) {
+        if (a.status) atomicOr(a.status, CORM_DEV_BAD_STEP);
+        pk = NEVER;
+      }
+      kp[tl][r] = pk;
+    }
+    quad[tl] = kp[tl][3] != NEVER && kp[tl][1] == kp[tl][0] + 1 && kp[tl][2] == kp[tl][0] + 2 &&
+               kp[tl][3] == kp[tl][0] + 3;
+  }
+  // Positions ascend with the slot, so queries before the one that sees the block's first key see none of it.
+  const int pfirst = posb[key_blk];
+  const int jt_first = max(pfirst - tau0 + 1, 0) / 16;
+
+  __shared__ float2 sh_part[PASS == 1 ? WAVES : 1][PASS == 1 ? PREFILL_SEG : 1];
+  int hm[T][4];   // pass 2: latest step at which one of the group's queries found the key important
+#pragma unroll
+  for (int tl = 0; tl < T; ++tl)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) hm[tl][r] = 0;
+
+  for (int g = 0; g < G; ++g) {
+    const int head = b * a.Hq + hkv * G + g;
+    const char* qh = reinterpret_cast<const char*>(a.q_tail) + (size_t)head * a.m * ROWB;
+    const __amdgpu_buffer_rsrc_t rq = make_rsrc(qh, (uint32_t)a.m * ROWB);
+    const float2* stats = a.stats + (size_t)head * a.w;
+
+    for (int seg0 = 0; seg0 < a.m; seg0 += PREFILL_SEG) {
+      const int seg1 = min(seg0 + PREFILL_SEG, a.m);
+      if (PASS == 1) {
+        for (int i = tid; i < WAVES * PREFILL_SEG; i += WG) (&sh_part[0][0])[i] = make_float2(neg_inf(), 0.f);
+        __syncthreads();
+      }
+      const int jt0 = max(jt_first, seg0 / 16);
+      uint4 qb[NCH];
+      float2 st = make_float2(0.f, 0.f);
+      if (jt0 * 16 < seg1) {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+          qb[c] = buffer_load16(rq, (uint32_t)(jt0 * 16 + n) * ROWB + (uint32_t)(c * 64 + 16 * lg));
+        if (PASS == 2 && jt0 * 16 + n < a.m) st = stats[jt0 * 16 + n];
+      }
+      for (int jt = jt0; jt * 16 < seg1; ++jt) {
+        // the next tile's operand is fetched while this one is worked on
+        uint4 qn[NCH];
+        float2 stn = make_float2(0.f, 0.f);
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)   // (past the last query the descriptor's range check returns zeros)
+          qn[c] = buffer_load16(rq, (uint32_t)((jt + 1) * 16 + n) * ROWB + (uint32_t)(c * 64 + 16 * lg));
+        if (PASS == 2 && (jt + 1) * 16 + n < a.m) stn = stats[(jt + 1) * 16 + n];
+
+        f32x4_t d[T];
+#pragma unroll
+        for (int tl = 0; tl < T; ++tl) {
+          d[tl] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int c = 0; c < NCH; ++c) d[tl] = PrefillMma<DT>::mma(ka[tl][c], qb[c], d[tl]);
+        }
+        const int j = jt * 16 + n;                 // this lane's query
+        const int tau = tau0 + j;
+        const int vis = j < a.m ? tau - 1 : -1;   // the query sees positions <= vis
+
+        if (PASS == 1) {
+          float mx = neg_inf();
+#pragma unroll
+          for (int tl = 0; tl < T; ++tl)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              d[tl][r] = kp[tl][r] <= vis ? d[tl][r] * a.scale_log2 : neg_inf();
+              mx = fmaxf(mx, d[tl][r]);
+            }
+          mx = fmaxf(mx, __shfl_xor(mx, 16));
+          mx = fmaxf(mx, __shfl_xor(mx, 32));
+          const float ms = mx == neg_inf() ? 0.f : mx;
+          float z = 0.f;
+#pragma unroll
+          for (int tl = 0; tl < T; ++tl)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) z += fast_exp2(d[tl][r] - ms);
+          z += __shfl_xor(z, 16);
+          z += __shfl_xor(z, 32);
+          if (lg == 0 && j < seg1) sh_part[wv][j - seg0] = make_float2(mx, z);
+        } else {
+          const float thr = importance_threshold(a.thr_scale, j < a.m ? tau : 1);
+          int slot = s0 + j;
+          if (slot >= a.w) slot -= a.w;
+          const size_t rowbase = ((size_t)head * a.w + (size_t)(j < a.m ? slot : 0)) * a.Tcap;
+#pragma unroll
+          for (int tl = 0; tl < T; ++tl) {
+            float pv[4];
+            bool seen[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              seen[r] = kp[tl][r] <= vis;
+              const float e = fast_exp2(d[tl][r] * a.scale_log2 - st.x) * st.y;
+              pv[r] = seen[r] ? e : 0.f;
+            }
+            if (a.ring_bf16) {
+              uint16_t hb[4];
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                hb[r] = f32_to_bf16_rne(pv[r]);
+                const float stored = __uint_as_float((uint32_t)hb[r] << 16);
+                hm[tl][r] = max(hm[tl][r], (seen[r] && stored >= thr) ? tau : 0);
+              }
+              uint16_t* row = reinterpret_cast<uint16_t*>(a.ring) + rowbase;
+              if (quad[tl] && seen[3] && ((rowbase + (size_t)kp[tl][0]) & 3) == 0) {
+                *reinterpret_cast<uint2*>(row + kp[tl][0]) =
+                    make_uint2((uint32_t)hb[0] | ((uint32_t)hb[1] << 16), (uint32_t)hb[2] | ((uint32_t)hb[3] << 16));
+              } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                  if (seen[r]) row[kp[tl][r]] = hb[r];
+              }
+            } else {
+#pragma unroll
+              for (int r = 0; r < 4; ++r) hm[tl][r] = max(hm[tl][r], (seen[r] && pv[r] >= thr) ? tau : 0);
+              float* row = reinterpret_cast<float*>(a.ring) + rowbase;
+              if (quad[tl] && seen[3] && ((rowbase + (size_t)kp[tl][0]) & 3) == 0) {
+                *reinterpret_cast<float4*>(row + kp[tl][0]) = make_float4(pv[0], pv[1], pv[2], pv[3]);
+              } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                  if (seen[r]) row[kp[tl][r]] = pv[r];
+              }
+            }
+          }
+        }
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) qb[c] = qn[c];
+        st = stn;
+      }
+      if (PASS == 1) {
+        __syncthreads();
+        float2* part = a.part + ((size_t)head * a.nkb + kb) * a.w;
+        for (int j = seg0 + tid; j < seg1; j += WG) {
+          float mx = neg_inf();
+#pragma unroll
+          for (int i = 0; i < WAVES; ++i) mx = fmaxf(mx, sh_part[i][j - seg0].x);
+          const float ms = mx == neg_inf() ? 0.f : mx;
+          float z = 0.f;
+#pragma unroll
+          for (int i = 0; i < WAVES; ++i) z = fmaf(sh_part[i][j - seg0].y, fast_exp2(sh_part[i][j - seg0].x - ms), z);
+          part[j] = make_float2(mx, z);
+        }
+        __syncthreads();
+      }
+    }
+  }
+
+  if (PASS == 2) {
+    int32_t* lhb = a.last_hit + (size_t)unit * a.Lcap;
+#pragma unroll
+    for (int tl = 0; tl < T; ++tl)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        int v = hm[tl][r];
+        v = max(v, __shfl_xor(v, 1));
+        v = max(v, __shfl_xor(v, 2));
+        v = max(v, __shfl_xor(v, 4));
+        v = max(v, __shfl_xor(v, 8));
+        const int key = wkey0 + tl * 16 + 4 * lg + r;
+        if (n == 0 && key < L && v > lhb[key]) lhb[key] = v;
+      }
+  }
+}
+
+// per query: max and 1/sum over the key blocks of its unit
+__global__ __launch_bounds__(256) void corm_prefill_merge_kernel(const PrefillArgs a, const int KB) {
+  const int head = blockIdx.y;
+  const int j = blockIdx.x * 256 + threadIdx.x;
+  if (j >= a.m) return;
+  const int unit = (head / a.Hq) * a.Hkv + (head % a.Hq) / (a.Hq / a.Hkv);
+  int L = a.lens[unit];
+  L = L < 0 ? 0 : (L > a.Lcap ? a.Lcap : L);
+  const int nblk = (L + KB - 1) / KB;
+  const float2* part = a.part + (size_t)head * a.nkb * a.w + j;
+  float mx = neg_inf();
+  for (int k = 0; k < nblk; ++k) mx = fmaxf(mx, part[(size_t)k * a.w].x);
+  const float ms = mx == neg_inf() ? 0.f : mx;
+  float z = 0.f;
+  for (int k = 0; k < nblk; ++k) {
+    const float2 pk = part[(size_t)k * a.w];
+    z = fmaf(pk.y, exp2f(pk.x - ms), z);
+  }
+  a.stats[(size_t)head * a.w + j] = make_float2(ms, z > 0.f ? 1.0f / z : 0.f);
+}
+
+// Def. 4.1 + recent r from last_hit for whole units (no append): wave ballots and survivors per chunk
+// for the compaction launches, optionally one byte per slot; writes t_first.
+__global__ __launch_bounds__(WG) void corm_decide_kernel(const int32_t* lens, const int32_t* last_hit, const int32_t* t,
+                                                         int32_t* t_first, unsigned long long* keepbits,
+                                                         int32_t* counts, uint8_t* keep, int Hkv, int Lcap, int nsplit,
+                                                         int kb_stride, int w, int r, int m) {
+  __shared__ int sh_cnt[WAVES];
+  const int split = blockIdx.x, unit = blockIdx.y;
+  const int b = unit / Hkv;
+  const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+  const int tcur = t[b];
+  if (split == 0 && unit % Hkv == 0 && tid == 0) t_first[b] = tcur - m + 1;
+  int L = lens[unit];
+  L = L < 0 ? 0 : (L > Lcap ? Lcap : L);
+  const int cbeg = split * CHUNK;
+  if (cbeg >= L) return;
+  const int cend = min(cbeg + CHUNK, L);
+  const bool full = m >= w;
+  const int32_t* lhb = last_hit + (size_t)unit * Lcap;
+  unsigned long long* bitsb = keepbits + (size_t)unit * kb_stride;
+  int kept = 0;
+  for (int i0 = cbeg; i0 < cbeg + CHUNK; i0 += WG) {
+    const int i = i0 + tid;
+    bool k = false;
+    if (i < cend) {
+      k = !full || lhb[i] > tcur - w || i >= L - r;
+      if (keep) keep[(size_t)unit * Lcap + i] = k ? 1 : 0;
+    }
+    const unsigned long long bal = __ballot(k);
+    if (lane == 0 && i0 + wv * 64 < cend) bitsb[(i0 >> 6) + wv] = bal;
+    kept += __popcll(bal);
+  }
+  if (lane == 0) sh_cnt[wv] = kept;
+  __syncthreads();
+  if (tid == 0) {
+    int tot = 0;
+#pragma unroll
+    for (int i = 0; i < WAVES; ++i) tot += sh_cnt[i];
+    counts[(size_t)unit * nsplit + split] = tot;
+  }
+}
+
 // ---------------------------------------------------------------- standalone kernels
 
 __global__ __launch_bounds__(64) void corm_append_kernel(char* K, char* V, int32_t* lens, int32_t* pos,
@@ -1500,8 +1829,10 @@ __global__ void corm_fill_i32_kernel(int32_t* p, size_t n, int32_t v) {
 // ---------------------------------------------------------------- host side
 
 struct WorkspaceLayout {
-  size_t counts_off, unit_len_off, keepbits_off, partials_off, logits_off, stage_meta_off, stage_k_off, stage_v_off, total;
+  size_t counts_off, unit_len_off, keepbits_off, partials_off, logits_off, stage_meta_off, stage_k_off, stage_v_off;
+  size_t seed_part_off, seed_stats_off, total;
   int nsplit, kb_stride;
+  int seed_kb, seed_nkb;   // prompt seeding: keys per workgroup, key blocks per unit
 };
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -1522,7 +1853,11 @@ WorkspaceLayout workspace_layout(const corm_desc& d) {
   w.stage_meta_off = align_up(w.logits_off + heads * d.Lcap * sizeof(float), 256);
   w.stage_k_off = align_up(w.stage_meta_off + stage_rows * 2 * sizeof(int32_t), 256);
   w.stage_v_off = align_up(w.stage_k_off + stage_rows * row_bytes(&d), 256);
-  w.total = align_up(w.stage_v_off + stage_rows * row_bytes(&d), 256);
+  w.seed_kb = row_bytes(&d) / 64 <= 4 ? PrefillGeom<256>::KB : PrefillGeom<512>::KB;
+  w.seed_nkb = (d.Lcap + w.seed_kb - 1) / w.seed_kb;
+  w.seed_part_off = align_up(w.stage_v_off + stage_rows * row_bytes(&d), 256);
+  w.seed_stats_off = align_up(w.seed_part_off + heads * w.seed_nkb * d.w * sizeof(float2), 256);
+  w.total = align_up(w.seed_stats_off + heads * d.w * sizeof(float2), 256);
   return w;
 }
 
@@ -1772,6 +2107,14 @@ int launch_compact(const corm_desc* d, const WorkspaceLayout& wl, void* workspac
   return launch_status();
 }
 
+template <typename DT, int D>
+int launch_prefill_dt(const PrefillArgs& a, dim3 grid, dim3 mgrid, int KB, hipStream_t s) {
+  hipLaunchKernelGGL((corm_prefill_kernel<DT, D, 1>), grid, dim3(WG), 0, s, a);
+  hipLaunchKernelGGL(corm_prefill_merge_kernel, mgrid, dim3(256), 0, s, a, KB);
+  hipLaunchKernelGGL((corm_prefill_kernel<DT, D, 2>), grid, dim3(WG), 0, s, a);
+  return launch_status();
+}
+
 int check_step_pointers(const void* q, const void* k_new, const void* v_new, const void* K, const void* V,
                         const int32_t* lens, const int32_t* pos, const int32_t* last_hit, const int32_t* t,
                         const int32_t* t_first, const void* score_ring, const float* out, const int32_t* kept_idx,
@@ -1980,6 +2323,49 @@ int corm_decode_step_lazy(const corm_desc* desc, const void* q, const void* k_ne
   pol.nlive = nlive;
   return launch_compact(desc, wl, workspace, K, V, pos, last_hit, lens, nullptr, nullptr, 1, false, pol,
                         (hipStream_t)stream);
+}
+
+int corm_prefill_seed(const corm_desc* desc, const void* q_tail, int32_t m, void* K, void* V, int32_t* lens,
+                      int32_t* pos, int32_t* last_hit, const int32_t* t, int32_t* t_first, void* score_ring,
+                      uint8_t* keep, int32_t* kept_idx, void* workspace, size_t workspace_bytes, int32_t* status,
+                      void* stream) {
+  int rc = validate_desc(desc);
+  if (rc) return rc;
+  if (!q_tail || !K || !V || !lens || !pos || !last_hit || !t || !t_first || !score_ring) return CORM_EINVAL;
+  if (misaligned16(q_tail) || misaligned16(K) || misaligned16(V) || misaligned16(score_ring)) return CORM_EINVAL;
+  if (misaligned4(lens) || misaligned4(pos) || misaligned4(last_hit) || misaligned4(t) || misaligned4(t_first) ||
+      misaligned4(kept_idx) || misaligned4(status))
+    return CORM_EINVAL;
+  if (m < 1 || m > desc->w) return CORM_EINVAL;
+  WorkspaceLayout wl;
+  rc = check_workspace(desc, workspace, workspace_bytes, &wl);
+  if (rc) return rc;
+  char* ws = reinterpret_cast<char*>(workspace);
+  hipStream_t s = (hipStream_t)stream;
+  PrefillArgs a;
+  a.q_tail = q_tail; a.K = K; a.lens = lens; a.pos = pos; a.last_hit = last_hit; a.t = t; a.ring = score_ring;
+  a.part = reinterpret_cast<float2*>(ws + wl.seed_part_off);
+  a.stats = reinterpret_cast<float2*>(ws + wl.seed_stats_off);
+  a.status = status;
+  a.Hq = desc->Hq; a.Hkv = desc->Hkv; a.Lcap = desc->Lcap; a.Tcap = desc->Tcap; a.w = desc->w; a.m = m;
+  a.nkb = wl.seed_nkb; a.ring_bf16 = desc->score_dtype == CORM_BF16;
+  a.thr_scale = desc->thr_scale;
+  a.scale_log2 = (desc->sm_scale > 0.f ? desc->sm_scale : 1.0f / sqrtf((float)desc->d)) * LOG2E;
+  const int units = desc->B * desc->Hkv;
+  const dim3 grid(wl.seed_nkb, units), mgrid((m + 255) / 256, desc->B * desc->Hq);
+  if (desc->kv_dtype == CORM_F32)
+    rc = desc->d == 64 ? launch_prefill_dt<F32, 64>(a, grid, mgrid, wl.seed_kb, s)
+                       : launch_prefill_dt<F32, 128>(a, grid, mgrid, wl.seed_kb, s);
+  else
+    rc = desc->d == 64 ? launch_prefill_dt<BF16, 64>(a, grid, mgrid, wl.seed_kb, s)
+                       : launch_prefill_dt<BF16, 128>(a, grid, mgrid, wl.seed_kb, s);
+  if (rc) return rc;
+  hipLaunchKernelGGL(corm_decide_kernel, dim3(wl.nsplit, units), dim3(WG), 0, s, lens, last_hit, t, t_first,
+                     reinterpret_cast<unsigned long long*>(ws + wl.keepbits_off),
+                     reinterpret_cast<int32_t*>(ws + wl.counts_off), keep, desc->Hkv, desc->Lcap, wl.nsplit,
+                     wl.kb_stride, desc->w, desc->r, m);
+  if (launch_status()) return CORM_EHIP;
+  return launch_compact(desc, wl, workspace, K, V, pos, last_hit, lens, nullptr, kept_idx, 0, false, CompactPolicy(), s);
 }
 
 int corm_selected_path(const corm_desc* desc) {

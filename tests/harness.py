@@ -99,7 +99,7 @@ def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_sca
                           units: Optional[Sequence[Tuple[int, int]]] = None, steps: Optional[int] = None,
                           use_split_calls=False, seq_offsets: Optional[Sequence[int]] = None,
                           Lcap: Optional[int] = None, Tcap: Optional[int] = None,
-                          lazy: Optional[Tuple[int, int]] = None) -> Dict:
+                          lazy: Optional[Tuple[int, int]] = None, seed_kernel: bool = False) -> Dict:
     """Run replay + decode on the device, slaving one oracle per checked unit.  Returns a report.
 
     seq_offsets[b]: sequence b behaves as if o_b tokens preceded its prompt (their keys already evicted):
@@ -107,7 +107,11 @@ def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_sca
 
     lazy = (dead_num, dead_den): run corm_decode_step_lazy with that compaction policy; the oracle (which
     compacts at every step, as Algorithm 1 does) is compared with the device's live slots in slot order, and
-    the policy itself (when a unit was compacted) is checked against its definition."""
+    the policy itself (when a unit was compacted) is checked against its definition.
+
+    seed_kernel: the prompt tail is not replayed step by step; the whole prompt is preloaded and one
+    corm_prefill_seed call records its last min(w, P) queries.  The oracle still replays those positions as
+    ordinary steps (fed the scores the device wrote into the ring), and must end in the same state."""
     x_cpu = inputs.make_layer(wl, layer, device="cpu")
     x = {k: v.to(device) for k, v in x_cpu.items() if k != "sinks"}
     n_replay = min(wl.w, wl.P)
@@ -118,8 +122,9 @@ def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_sca
                     Tcap=(wl.P + wl.D + int(offs.max())) if Tcap is None else Tcap)
     G = wl.G
     pre = wl.P - n_replay
-    st.preload(x["K0"][:, :, :pre], x["V0"][:, :, :pre])
-    st.pos[:, :, :pre] += offs_dev.view(-1, 1, 1)
+    n_pre = wl.P if seed_kernel else pre
+    st.preload(x["K0"][:, :, :n_pre], x["V0"][:, :, :n_pre])
+    st.pos[:, :, :n_pre] += offs_dev.view(-1, 1, 1)
     units = [(b, h) for b in range(wl.B) for h in range(wl.Hkv)] if units is None else list(units)
     oracles = {}
     for (b, h) in units:
@@ -136,7 +141,13 @@ def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_sca
     cap = st.Lcap
     slots_before = {u: np.arange(pre) for u in units}     # lazy mode: live slots and slots in use before a step
     used_before = {u: pre for u in units}
-    for j in range(n_steps):
+    j_first = 0
+    if seed_kernel:
+        assert lazy is None and not use_split_calls and n_steps >= n_replay
+        j_first = n_replay
+        worst_score = _seed_with_kernel(wl, st, x, x_cpu, oracles, units, offs, offs_dev, n_replay, t_first, thr_scale)
+        evicted_total += sum(wl.P - oracles[u].l for u in units)
+    for j in range(j_first, n_steps):
         q, k, v, t = step_inputs(wl, x, j, n_replay)
         t_dev = torch.full((wl.B,), t, dtype=torch.int32, device=device) + offs_dev
         if use_split_calls:
@@ -208,6 +219,46 @@ def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_sca
     return {"compactions": compactions, "steps": n_steps, "units": len(units), "worst_out_rel_err": worst_out,
             "worst_score_err_over_bound": worst_score, "importance_flips_vs_fp64": flips,
             "evicted_total": evicted_total, "final_lens": st.lens.cpu().numpy().tolist()}
+
+
+def _seed_with_kernel(wl, st, x, x_cpu, oracles, units, offs, offs_dev, n_replay, t_first, thr_scale) -> float:
+    """One corm_prefill_seed call against the oracle replaying the same prompt positions as steps."""
+    dev = st.K.device
+    G = wl.G
+    q_tail = x["Q"][:n_replay].permute(1, 2, 0, 3).contiguous()                   # [B, Hq, m, d]
+    t_dev = torch.full((wl.B,), wl.P, dtype=torch.int32, device=dev) + offs_dev
+    tf_out = torch.zeros(wl.B, dtype=torch.int32, device=dev)
+    st.prefill_seed(q_tail, t_dev, tf_out)
+    torch.cuda.synchronize()
+    assert int(st.status.item()) == 0, ("device status", int(st.status.item()))
+    assert torch.equal(tf_out, t_first), "t_first"
+    worst = 0.0
+    keep_d = st.keep.cpu().numpy()
+    idx_d = st.kept_idx.cpu().numpy()
+    ring_b = {}
+    for (b, h) in units:
+        u = oracles[(b, h)]
+        if b not in ring_b:
+            ring_b[b] = _f32(st.ring[b])                                          # [Hq, w, Tcap]
+        res = None
+        for j in range(n_replay):
+            p = wl.P - n_replay + j
+            tb = p + 1 + int(offs[b])
+            live_pos = np.concatenate([u.positions, [tb - 1]])
+            recorded = ring_b[b][h * G:(h + 1) * G, (tb - 1) % wl.w][:, live_pos]
+            res = u.step(_f32(x_cpu["Q"][j, b, h * G:(h + 1) * G]), _f32(x_cpu["K0"][b, h, p]),
+                         _f32(x_cpu["V0"][b, h, p]), tb, recorded=recorded)
+            for g in range(G):
+                a = res["alpha"][g]
+                err = np.abs(recorded[g].astype(np.float64) - a)
+                bound = SCORE_RTOL[wl.dtype] * a + SCORE_ATOL_OF_MAX[wl.dtype] * a.max()
+                worst = max(worst, float((err / bound).max()))
+                assert (err <= bound).all(), ("seeded score", j, b, h, g, float((err / bound).max()))
+        assert np.array_equal(keep_d[b, h, :wl.P].astype(bool), res["keep"]), ("keep after seeding", b, h)
+        assert int(st.lens[b, h].item()) == u.l, ("lens after seeding", b, h)
+        assert np.array_equal(idx_d[b, h, :u.l].astype(np.int64), res["indices"]), ("kept_idx after seeding", b, h)
+        check_unit_state(st, b, h, u, wl.P + int(offs[b]))
+    return worst
 
 
 # ------------------------------------------------------------------ snapshot mode

@@ -156,6 +156,56 @@ def test_lazy_bad_arguments():
     assert int(st.lens.sum().item()) == 0   # nothing ran
 
 
+# prompt seeding by the dense kernel, then ordinary decode steps on the state it left
+SEEDED = ["tiny_f32", "bf16_mha", "bf16_gqa4", "bf16_gqa8", "f32_d128", "bf16_d64", "f32_gqa4", "r_lt_w", "structured"]
+
+
+@pytest.mark.parametrize("name", SEEDED)
+def test_prefill_seed_then_decode(name):
+    """corm_prefill_seed leaves the state the oracle reaches by taking the prompt's last w positions as
+    ordinary steps of Algorithm 1 (fed the scores the kernel recorded): ring rows within tolerance, keep
+    mask, kept indices, compacted rows, lens and last_hit bit for bit; the decode steps that follow agree
+    as in the replayed trajectories."""
+    wl, every = TRAJ[name]
+    say("prefill seed", name, wl)
+    rep = harness.run_slaved_trajectory(wl, DEV, check_state_every=every, seed_kernel=True)
+    say("report", name, {k: v for k, v in rep.items() if k != "final_lens"})
+    assert rep["evicted_total"] > 0
+
+
+def test_prefill_seed_offsets_and_short_tail():
+    """Sequences at different steps (positions shifted, so ring rows start at unaligned columns), and a
+    prompt shorter than the window (m = P < w: rows recorded, nothing evicted yet)."""
+    wl = W["tiny_f32"].replace(B=3, P=300, D=12, w=32, r=32)
+    harness.run_slaved_trajectory(wl, DEV, check_state_every=4, seq_offsets=[0, 7, 1000], seed_kernel=True)
+    wl = W["llama7b_1layer"].replace(B=1, Hq=2, Hkv=2, P=40, D=30, w=64, r=4, key_scale=3.0)
+    rep = harness.run_slaved_trajectory(wl, DEV, check_state_every=1, seed_kernel=True)
+    assert rep["evicted_total"] > 0   # the window fills during decode
+
+
+def test_prefill_seed_bad_arguments():
+    wl = W["tiny_f32"]
+    st = harness.make_state(wl, DEV)
+    q = torch.zeros(wl.B, wl.Hq, wl.w, wl.d, device=DEV)
+    t = torch.full((wl.B,), wl.P, dtype=torch.int32, device=DEV)
+    tf = torch.zeros_like(t)
+    kw = dict(workspace=st.workspace, status=st.status, check=False)
+    args = (st.K, st.V, st.lens, st.pos, st.last_hit, t, tf, st.ring)
+    assert corm.corm_prefill_seed(st.desc, q, 0, *args, **kw) == corm.CORM_EINVAL
+    assert corm.corm_prefill_seed(st.desc, q, wl.w + 1, *args, **kw) == corm.CORM_EINVAL
+    assert corm.corm_prefill_seed(st.desc, None, wl.w, *args, **kw) == corm.CORM_EINVAL
+    assert corm.corm_prefill_seed(st.desc, q.data_ptr() + 4, wl.w, *args, **kw) == corm.CORM_EINVAL
+    # a tail longer than the prompt so far: flagged on the device, nothing written
+    st.lens.fill_(8)
+    st.pos[:, :, :8] = torch.arange(8, dtype=torch.int32, device=DEV)
+    t8 = torch.full((wl.B,), 8, dtype=torch.int32, device=DEV)
+    assert corm.corm_prefill_seed(st.desc, q, wl.w, st.K, st.V, st.lens, st.pos, st.last_hit, t8, tf, st.ring,
+                                  **kw) == corm.CORM_OK
+    torch.cuda.synchronize()
+    assert int(st.status.item()) & corm.CORM_DEV_BAD_STEP
+    assert float(st.ring.abs().sum().item()) == 0.0
+
+
 def test_split_calls_equal_the_fused_step():
     """append + decode_attend + evict_mask (literal, also == summary) + compact: the same bits
     as the fused step, checked against the same oracle."""

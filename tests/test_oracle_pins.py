@@ -293,6 +293,36 @@ def test_huge_c_reduces_to_sliding_window():
         np.testing.assert_allclose(out["out"][0], ref, rtol=1e-11, atol=1e-13)
 
 
+@pytest.mark.parametrize("G", [1, 2])
+def test_prompt_seeding_equals_the_causal_attention_matrix(G):
+    """Seeding by replaying prompt positions is pinned to the dense form: the last w rows of the causally
+    masked softmax(Q K^T / sqrt(d)) from a library routine, thresholded row by row at c/(p+1), OR-ed over the
+    window and the group, plus the r newest positions."""
+    wl = inputs.WORKLOADS["tiny_f32"].replace(Hq=2 * G, Hkv=2, P=80, D=4, w=12, r=5)
+    K0, V0, Kn, Vn, Q = _unit_inputs(wl, h=1)
+    n = Q.shape[0] - Kn.shape[0]
+    P = K0.shape[0]
+    assert n == wl.w
+    u = O.UnitCache(wl.d, G, wl.w, wl.r, score_dtype="f32")
+    res = O.seed_from_prompt(u, K0, V0, Q[:n])
+    K64 = K0.astype(np.float64)
+    keep = np.zeros(P, dtype=bool)
+    keep[P - wl.r:] = True
+    for j in range(n):
+        p = P - n + j                                        # 0-based position of the query
+        for g in range(G):
+            logits = (K64 @ Q[j, g].astype(np.float64)) / np.sqrt(wl.d)
+            logits[p + 1:] = -np.inf                         # causal mask
+            row = scipy.special.softmax(logits)
+            np.testing.assert_allclose(res[j]["alpha"][g], row[:p + 1], rtol=1e-12, atol=1e-300)
+            keep |= row.astype(np.float32) >= np.float32(1.0) / np.float32(p + 1)
+    assert not keep.all(), "nothing evicted: vacuous"
+    assert u.positions.tolist() == np.nonzero(keep)[0].tolist()
+    assert np.array_equal(res[-1]["keep"], keep)
+    for j in range(n - 1):
+        assert res[j]["keep"].all()                          # no eviction before the w-th recorded row
+
+
 def test_w1_r1_keeps_exactly_the_currently_important_keys():
     rng = np.random.default_rng(5)
     d = 16
