@@ -44,13 +44,16 @@ def parse():
     ap.add_argument("--lazy-frac", default=None, metavar="NUM/DEN",
                     help="deferred compaction (corm_decode_step_lazy): a unit is compacted once NUM/DEN of its "
                          "slots are dead; default: compact at every step (corm_decode_step)")
+    ap.add_argument("--seed", default="kernel", choices=["kernel", "replay"],
+                    help="how the prompt fills the recent-query window before decoding (untimed set-up): one "
+                         "corm_prefill_seed call per layer, or its last w tokens replayed through corm_decode_step")
     ap.add_argument("--extra-steps", type=int, default=4, help="untimed single-stream steps after the timed region "
                     "(exclusive measurement of the dominant kernel)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference dispatch for rocprofv3 byte counters)")
-    ap.add_argument("--cpu-units", type=int, default=48)
-    ap.add_argument("--cpu-steps", type=int, default=8)
+    ap.add_argument("--cpu-units", type=int, default=128)
+    ap.add_argument("--cpu-steps", type=int, default=16)
     return ap.parse_args()
 
 
@@ -130,15 +133,21 @@ def main():
         st.lens = lens_all[l]
         st.nlive = nlive_all[l]
         x = inputs.make_layer(wl, l, device=dev, n_decode=n_dec, n_replay=n_replay)
-        st.preload(x["K0"][:, :, :pre], x["V0"][:, :, :pre])
-        # keys/values of the replayed prompt tail in step-major layout, then the decode tokens
-        Kt = x["K0"][:, :, pre:].permute(2, 0, 1, 3).contiguous()
-        Vt = x["V0"][:, :, pre:].permute(2, 0, 1, 3).contiguous()
-        Kns.append(torch.cat([Kt, x["Kn"]], dim=0))
-        Vns.append(torch.cat([Vt, x["Vn"]], dim=0))
+        if args.seed == "kernel":
+            st.preload(x["K0"], x["V0"])          # the whole prompt; the seeding call comes below
+            Kns.append(x["Kn"])
+            Vns.append(x["Vn"])
+        else:
+            st.preload(x["K0"][:, :, :pre], x["V0"][:, :, :pre])
+            # keys/values of the replayed prompt tail in step-major layout, then the decode tokens
+            Kt = x["K0"][:, :, pre:].permute(2, 0, 1, 3).contiguous()
+            Vt = x["V0"][:, :, pre:].permute(2, 0, 1, 3).contiguous()
+            Kns.append(torch.cat([Kt, x["Kn"]], dim=0))
+            Vns.append(torch.cat([Vt, x["Vn"]], dim=0))
+            del Kt, Vt
         Qs.append(x["Q"])
         states.append(st)
-        del x, Kt, Vt
+        del x
     torch.cuda.synchronize()
     log(f"allocated + generated {layers} layers in {time.time() - t0:.1f}s; "
         f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB resident")
@@ -153,14 +162,17 @@ def main():
     for extra in streams[1:]:
         extra.wait_stream(main)
 
+    kv_off = n_replay if args.seed == "kernel" else 0   # Kns / Vns start at the first decode token
+
     def layer_step(l, j, tj, wsk, stream):
         st = states[l]
+        kn, vn = Kns[l][j - kv_off], Vns[l][j - kv_off]
         if lazy:
-            corm.corm_decode_step_lazy(st.desc, Qs[l][j], Kns[l][j], Vns[l][j], st.K, st.V, st.lens, st.live, st.pos,
+            corm.corm_decode_step_lazy(st.desc, Qs[l][j], kn, vn, st.K, st.V, st.lens, st.live, st.pos,
                                        st.last_hit, tj, t_first, st.ring, st.out, None, st.nlive, lazy[0], lazy[1],
                                        wsk, status=st.status, stream=stream)
         else:
-            corm.corm_decode_step(st.desc, Qs[l][j], Kns[l][j], Vns[l][j], st.K, st.V, st.lens, st.pos, st.last_hit,
+            corm.corm_decode_step(st.desc, Qs[l][j], kn, vn, st.K, st.V, st.lens, st.pos, st.last_hit,
                                   tj, t_first, st.ring, st.out, None, None, wsk, status=st.status, stream=stream)
 
     def run_step(j, probe_layer=-1, probe_events=None):
@@ -180,20 +192,43 @@ def main():
             extra.wait_stream(main)
 
     t0 = time.time()
-    for j in range(n_replay):          # prompt tail: seeds the recent-query window; bulk eviction at its end
-        run_step(j)
-    join()
-    torch.cuda.synchronize()
+    seeding = {"how": "replay of the last w prompt tokens through corm_decode_step"}
+    if args.seed == "kernel":
+        # one dense call per layer: ring rows and last_hit of the last w prompt queries, then the bulk eviction
+        t_last = torch.full((B,), wl.P, dtype=torch.int32, device=dev)
+        tf_out = torch.zeros_like(t_first)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(layers + 1)]
+        ev[0].record()
+        for l in range(layers):
+            q_tail = Qs[l][:n_replay].permute(1, 2, 0, 3).contiguous()
+            st = states[l]
+            corm.corm_prefill_seed(st.desc, q_tail, n_replay, st.K, st.V, st.lens, st.pos, st.last_hit, t_last, tf_out,
+                                   st.ring, None, None, ws, status=st.status)
+            ev[l + 1].record()
+            del q_tail
+        torch.cuda.synchronize()
+        assert torch.equal(tf_out, t_first)
+        ms = sorted(ev[l].elapsed_time(ev[l + 1]) for l in range(layers))
+        pairs = n_replay * wl.P - n_replay * (n_replay - 1) // 2     # (query, visible key) pairs per head
+        seeding = {"how": "corm_prefill_seed, one call per layer (layout copy of the queries included)",
+                   "median_ms_per_layer": ms[len(ms) // 2],
+                   "algorithmic_tflops": 2.0 * d * pairs * B * Hq / (ms[len(ms) // 2] * 1e-3) / 1e12,
+                   "ring_gb_written_per_layer": pairs * B * Hq * esz / 1e9}
+    else:
+        for j in range(n_replay):          # prompt tail: seeds the recent-query window; bulk eviction at its end
+            run_step(j)
+        join()
+        torch.cuda.synchronize()
     # keys_all: the live keys per unit (what the next step attends to); lens_all also counts dead slots
     keys_all = nlive_all if lazy else lens_all
-    log(f"prompt replay ({n_replay} positions) {time.time() - t0:.1f}s; "
+    log(f"prompt seeding ({args.seed}, last {n_replay} positions) {time.time() - t0:.1f}s; "
         f"live fraction after the prompt {keys_all.float().mean().item() / wl.P:.4f}")
     assert all(int(s.status.item()) == 0 for s in states)
 
     # ---------------- CPU baseline: the oracle, timed on a bounded sample of the same workload
     cpu_baseline = None
     if not args.no_cpu_baseline and not lazy:   # (the oracle is rebuilt from compacted device snapshots)
-        cpu_baseline = cpu_baseline_leg(args, wl, states, Qs, Kns, Vns, n_replay, pre, layers)
+        cpu_baseline = cpu_baseline_leg(args, wl, states, Qs, Kns, Vns, n_replay, pre, layers, kv_off)
 
     if args.calibrate_copy:
         src = torch.ones(2 ** 28, dtype=torch.float32, device=dev)   # 1 GiB read + 1 GiB written
@@ -284,6 +319,7 @@ def main():
                        "avg_layer_step_ms": ms_total / n_launch, "layer_steps": n_launch,
                        "note": "algorithmic bytes of all launches / wall time of the timed region "
                                "(every kernel of the step, launch gaps included)"},
+        "prompt_seeding_untimed": seeding,
         "cpu_baseline": cpu_baseline,
     }
     if cpu_baseline:
@@ -314,7 +350,7 @@ class HipEvents:
         return ms.value
 
 
-def cpu_baseline_leg(args, wl, states, Qs, Kns, Vns, n_replay, pre, layers):
+def cpu_baseline_leg(args, wl, states, Qs, Kns, Vns, n_replay, pre, layers, kv_off):
     """Time the oracle (as it stands) on a sample of units of the workload's first decode steps, starting
     from copies of the device state after the prompt.  The device state is not touched."""
     import numpy as np
@@ -333,8 +369,8 @@ def cpu_baseline_leg(args, wl, states, Qs, Kns, Vns, n_replay, pre, layers):
         u = unit_from_device_arrays(st.K, st.V, st.pos, st.lens, st.ring, b, h, G, wl.w, wl.r, t_prev, pre + 1,
                                     wl.dtype, 1.0)
         q = Qs[l][n_replay:n_replay + n_steps, b, h * G:(h + 1) * G].float().cpu().numpy()
-        k = Kns[l][n_replay:n_replay + n_steps, b, h].float().cpu().numpy()
-        v = Vns[l][n_replay:n_replay + n_steps, b, h].float().cpu().numpy()
+        k = Kns[l][n_replay - kv_off:n_replay - kv_off + n_steps, b, h].float().cpu().numpy()
+        v = Vns[l][n_replay - kv_off:n_replay - kv_off + n_steps, b, h].float().cpu().numpy()
         work.append((u, q, k, v))
     cores = min(os.cpu_count() or 1, 16)
 

@@ -102,3 +102,77 @@ def test_config5_gqa_structured_evicts():
     wl = W["gqa_llama3"].replace(q_mean_scales=(3.0, 5.0), key_scale=1.5)
     n_replay = wl.w
     _run(wl, 0, 4, {n_replay, n_replay + 3}, _sample_units(wl, 3, seed=2), expect_path=1, expect_evictions=True)
+
+
+# ------------------------------------------------------------------ prompt seeding at full size
+
+def _seed_check(wl, layer, units, rows_per_unit=5, expect_evictions=False):
+    """corm_prefill_seed on the full prompt of one layer, checked on sampled units: Def. 4.1 evaluated
+    literally by the oracle on the rows the kernel recorded must give the kernel's keep mask, kept
+    indices, compacted rows and lens bit for bit; sampled rows of recorded scores are compared with the
+    oracle's causal attention rows within tolerance."""
+    from oracle import corm_oracle as O
+    say("seed full size", wl.name, "layer", layer, "B", wl.B, "Hq/Hkv", wl.Hq, wl.Hkv, "P", wl.P, "w", wl.w)
+    m = min(wl.w, wl.P)
+    x = inputs.make_layer(wl, layer, device=DEV, n_decode=1, n_replay=m)
+    st = harness.make_state(wl, DEV, Lcap=wl.P + 8, Tcap=wl.P + 8)
+    st.preload(x["K0"], x["V0"])
+    q_tail = x["Q"][:m].permute(1, 2, 0, 3).contiguous()
+    t = torch.full((wl.B,), wl.P, dtype=torch.int32, device=DEV)
+    tf = torch.zeros_like(t)
+    st.prefill_seed(q_tail, t, tf)
+    torch.cuda.synchronize()
+    assert int(st.status.item()) == 0
+    assert int(tf.min().item()) == int(tf.max().item()) == wl.P - m + 1
+    G, P = wl.G, wl.P
+    rng = np.random.default_rng(11)
+    steps = np.arange(P - m + 1, P + 1)                      # tau_j
+    evicted = 0
+    for (b, h) in units:
+        ring = st.ring[b, h * G:(h + 1) * G, :, :P].float().cpu().numpy()      # [G, w, P], slot-major
+        scores = np.stack([ring[:, (tau - 1) % wl.w] for tau in steps])        # [m, G, P]
+        born = np.arange(P)[None, :] <= (steps - 1)[:, None]                   # key visible to query j
+        scores = np.where(born[:, None, :], scores, 0.0)
+        keep = O.keep_from_score_window(scores, steps.tolist(), wl.w, wl.r)
+        idx = O.stable_compact(keep)
+        assert np.array_equal(st.keep[b, h, :P].cpu().numpy().astype(bool), keep), ("keep", b, h)
+        l = int(st.lens[b, h].item())
+        assert l == len(idx), ("lens", b, h, l, len(idx))
+        assert np.array_equal(st.kept_idx[b, h, :l].cpu().numpy().astype(np.int64), idx), ("kept_idx", b, h)
+        assert np.array_equal(st.pos[b, h, :l].cpu().numpy().astype(np.int64), idx), ("pos", b, h)
+        sel = torch.from_numpy(idx).to(DEV)
+        assert torch.equal(st.K[b, h, :l], x["K0"][b, h].index_select(0, sel)), ("K rows", b, h)
+        assert torch.equal(st.V[b, h, :l], x["V0"][b, h].index_select(0, sel)), ("V rows", b, h)
+        hit = np.stack([O.important(scores[j], int(steps[j])) for j in range(m)]).any(axis=1) & born   # [m, P]
+        last = np.where(hit, steps[:, None], 0).max(axis=0)[idx]
+        lh = st.last_hit[b, h, :l].cpu().numpy()
+        assert np.array_equal(np.where(lh > P - wl.w, lh, 0), last), ("last_hit", b, h)
+        evicted += P - l
+        K64 = x["K0"][b, h].float().cpu().numpy().astype(np.float64)
+        for j in sorted({0, m - 1, *rng.integers(0, m, rows_per_unit).tolist()}):
+            p = P - m + j
+            for g in range(G):
+                a = O.attention_scores(x["Q"][j, b, h * G + g].float().cpu().numpy(), K64[:p + 1])
+                err = np.abs(scores[j, g, :p + 1].astype(np.float64) - a)
+                bound = harness.SCORE_RTOL[wl.dtype] * a + harness.SCORE_ATOL_OF_MAX[wl.dtype] * a.max()
+                assert (err <= bound).all(), ("seeded score", b, h, j, g, float((err / bound).max()))
+    say("evicted in sampled units", evicted, "of", len(units) * P)
+    if expect_evictions:
+        assert evicted > 0
+
+
+def test_config3_prompt_seeding():
+    wl = W["llama7b_b16"]
+    _seed_check(wl, 2, _sample_units(wl, 3, seed=3))
+    _seed_check(wl.replace(q_mean_scales=inputs.STRUCTURED_Q_MEAN), 2, _sample_units(wl, 4, seed=4),
+                expect_evictions=True)
+
+
+def test_config5_prompt_seeding_gqa():
+    wl = W["gqa_llama3"].replace(q_mean_scales=(3.0, 5.0), key_scale=1.5)
+    _seed_check(wl, 0, _sample_units(wl, 2, seed=6), expect_evictions=True)
+
+
+def test_config4_prompt_seeding_long_context():
+    wl = W["long32k"]
+    _seed_check(wl, 0, [(3, 31)], rows_per_unit=3)
