@@ -1436,7 +1436,7 @@ struct PrefillArgs {
   const int32_t* t;
   void* ring;
   float2* part;    // [B*Hq, nkb, w]  (max, sum) per key block
-  float2* stats;   // [B*Hq, w]       (max, 1/sum)
+  float4* stats;   // [B*Hq, w]       (max, 1/sum, threshold of the query's step, unused)
   int32_t* status;
   int32_t Hq, Hkv, Lcap, Tcap, w, m, nkb, ring_bf16;
   float thr_scale, scale_log2;
@@ -1459,6 +1459,67 @@ template <> struct PrefillMma<F32> {
     return c;
   }
 };
+
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+// two fp32 -> two bf16 (round to nearest even) in one word, first value in the low half
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
+// Pass 1 on one wave tile (16 queries x 16*T keys): per query, max of the scaled logits and the sum of
+// exp2 relative to it, over the keys the query sees.  MASKED = false when every query sees every key.
+template <bool MASKED, int T>
+__device__ __forceinline__ void prefill_stats_tile(const f32x4_t (&d)[T], const int (&kp)[T][4], int vis,
+                                                   float scale_log2, float& mx_out, float& z_out) {
+  float mx = neg_inf();   // of the raw logits: the scale is positive and keeps their order
+#pragma unroll
+  for (int tl = 0; tl < T; ++tl)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) mx = fmaxf(mx, (!MASKED || kp[tl][r] <= vis) ? d[tl][r] : neg_inf());
+  mx = fmaxf(mx, __shfl_xor(mx, 16));
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  const float ms = mx == neg_inf() ? 0.f : mx * scale_log2;
+  float z = 0.f;
+#pragma unroll
+  for (int tl = 0; tl < T; ++tl)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const float e = fast_exp2(fmaf(d[tl][r], scale_log2, -ms));
+      z += (!MASKED || kp[tl][r] <= vis) ? e : 0.f;
+    }
+  z += __shfl_xor(z, 16);
+  z += __shfl_xor(z, 32);
+  mx_out = mx == neg_inf() ? mx : ms;
+  z_out = z;
+}
+
+// Pass 2 on one wave tile, bf16 ring: the stored scores (packed) and, per key, the step of this query
+// where its stored score reaches the threshold.  st = (max, 1/sum) of this lane's query.
+template <bool MASKED, int T>
+__device__ __forceinline__ void prefill_scores_bf16(const f32x4_t (&d)[T], const int (&kp)[T][4], int vis,
+                                                    float scale_log2, float4 st, float thr, int tau,
+                                                    uint32_t (&pk)[T][2], int (&hmg)[T][4]) {
+#pragma unroll
+  for (int tl = 0; tl < T; ++tl) {
+    float pv[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const float e = fast_exp2(fmaf(d[tl][r], scale_log2, -st.x)) * st.y;
+      pv[r] = (!MASKED || kp[tl][r] <= vis) ? e : 0.f;
+    }
+    pk[tl][0] = pack_bf16x2(pv[0], pv[1]);
+    pk[tl][1] = pack_bf16x2(pv[2], pv[3]);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const uint32_t w = pk[tl][r >> 1];
+      const float stored = __uint_as_float((r & 1) ? (w & 0xffff0000u) : (w << 16));
+      const bool hit = stored >= thr && (!MASKED || kp[tl][r] <= vis);
+      hmg[tl][r] = hit ? tau : hmg[tl][r];
+    }
+  }
+}
 
 constexpr int PREFILL_SEG = 1024;   // queries whose pass-1 partials a workgroup holds in LDS at a time
 
@@ -1524,6 +1585,24 @@ __global__ __launch_bounds__(WG) void corm_prefill_kernel(const PrefillArgs a) {
   const int jt_first = max(pfirst - tau0 + 1, 0) / 16;
 
   __shared__ float2 sh_part[PASS == 1 ? WAVES : 1][PASS == 1 ? PREFILL_SEG : 1];
+  // Pass 2, bf16 ring: a wave's 16 x 64 tile of stored scores is turned through LDS so that every query's
+  // 64 consecutive positions leave as one 128-byte piece of its ring row (16 bytes per lane) instead of
+  // sixteen 8-byte pieces.  Rows are padded to 144 bytes.
+  constexpr int TROW = 72;
+  __shared__ __attribute__((aligned(16))) uint16_t sh_t[PASS == 2 ? WAVES : 1][PASS == 2 ? 16 : 1][TROW];
+  // ... possible when the wave's 64 slots hold consecutive positions starting at a multiple of 8 (and rows
+  // of the ring start at multiples of 8 elements), for query tiles that see all of them
+  bool wave_rows = false;
+  // every slot of the wave holds a key (then pos_wlast is the largest position among them)
+  const bool wave_whole = wkey0 + T * 16 <= L;
+  const int pos_w0 = __shfl(kp[0][0], 0);
+  const int pos_wlast = __shfl(kp[T - 1][3], 63);
+  if (PASS == 2 && T == 4) {
+    bool ok = true;
+#pragma unroll
+    for (int tl = 0; tl < T; ++tl) ok = ok && quad[tl] && kp[tl][0] == pos_w0 + tl * 16 + 4 * lg;
+    wave_rows = __all(ok) && a.ring_bf16 && (pos_w0 & 7) == 0 && (a.Tcap & 7) == 0;
+  }
   int hm[T][4];   // pass 2: latest step at which one of the group's queries found the key important
 #pragma unroll
   for (int tl = 0; tl < T; ++tl)
@@ -1532,9 +1611,14 @@ __global__ __launch_bounds__(WG) void corm_prefill_kernel(const PrefillArgs a) {
 
   for (int g = 0; g < G; ++g) {
     const int head = b * a.Hq + hkv * G + g;
+    int hmg[T][4];   // the same for this head alone (its steps ascend, so the last hit is the latest)
+#pragma unroll
+    for (int tl = 0; tl < T; ++tl)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) hmg[tl][r] = 0;
     const char* qh = reinterpret_cast<const char*>(a.q_tail) + (size_t)head * a.m * ROWB;
     const __amdgpu_buffer_rsrc_t rq = make_rsrc(qh, (uint32_t)a.m * ROWB);
-    const float2* stats = a.stats + (size_t)head * a.w;
+    const float4* stats = a.stats + (size_t)head * a.w;
 
     for (int seg0 = 0; seg0 < a.m; seg0 += PREFILL_SEG) {
       const int seg1 = min(seg0 + PREFILL_SEG, a.m);
@@ -1544,7 +1628,7 @@ __global__ __launch_bounds__(WG) void corm_prefill_kernel(const PrefillArgs a) {
       }
       const int jt0 = max(jt_first, seg0 / 16);
       uint4 qb[NCH];
-      float2 st = make_float2(0.f, 0.f);
+      float4 st = make_float4(0.f, 0.f, 0.f, 0.f);
       if (jt0 * 16 < seg1) {
 #pragma unroll
         for (int c = 0; c < NCH; ++c)
@@ -1554,7 +1638,7 @@ __global__ __launch_bounds__(WG) void corm_prefill_kernel(const PrefillArgs a) {
       for (int jt = jt0; jt * 16 < seg1; ++jt) {
         // the next tile's operand is fetched while this one is worked on
         uint4 qn[NCH];
-        float2 stn = make_float2(0.f, 0.f);
+        float4 stn = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
         for (int c = 0; c < NCH; ++c)   // (past the last query the descriptor's range check returns zeros)
           qn[c] = buffer_load16(rq, (uint32_t)((jt + 1) * 16 + n) * ROWB + (uint32_t)(c * 64 + 16 * lg));
@@ -1570,69 +1654,71 @@ __global__ __launch_bounds__(WG) void corm_prefill_kernel(const PrefillArgs a) {
         const int j = jt * 16 + n;                 // this lane's query
         const int tau = tau0 + j;
         const int vis = j < a.m ? tau - 1 : -1;   // the query sees positions <= vis
+        // (uniform over the wave) every query of the tile exists and sees every key of the wave: no masking
+        const bool all_seen = wave_whole && jt * 16 + 15 < a.m && pos_wlast <= tau0 + jt * 16 - 1;
 
         if (PASS == 1) {
-          float mx = neg_inf();
-#pragma unroll
-          for (int tl = 0; tl < T; ++tl)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              d[tl][r] = kp[tl][r] <= vis ? d[tl][r] * a.scale_log2 : neg_inf();
-              mx = fmaxf(mx, d[tl][r]);
-            }
-          mx = fmaxf(mx, __shfl_xor(mx, 16));
-          mx = fmaxf(mx, __shfl_xor(mx, 32));
-          const float ms = mx == neg_inf() ? 0.f : mx;
-          float z = 0.f;
-#pragma unroll
-          for (int tl = 0; tl < T; ++tl)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) z += fast_exp2(d[tl][r] - ms);
-          z += __shfl_xor(z, 16);
-          z += __shfl_xor(z, 32);
+          float mx, z;
+          if (all_seen) prefill_stats_tile<false, T>(d, kp, vis, a.scale_log2, mx, z);
+          else prefill_stats_tile<true, T>(d, kp, vis, a.scale_log2, mx, z);
           if (lg == 0 && j < seg1) sh_part[wv][j - seg0] = make_float2(mx, z);
         } else {
-          const float thr = importance_threshold(a.thr_scale, j < a.m ? tau : 1);
+          const float thr = st.z;
           int slot = s0 + j;
           if (slot >= a.w) slot -= a.w;
           const size_t rowbase = ((size_t)head * a.w + (size_t)(j < a.m ? slot : 0)) * a.Tcap;
+          const bool rows_now = wave_rows && all_seen;
+          if (a.ring_bf16) {
+            uint32_t pk[T][2];   // stored scores, two bf16 per word
+            if (all_seen) prefill_scores_bf16<false, T>(d, kp, vis, a.scale_log2, st, thr, tau, pk, hmg);
+            else prefill_scores_bf16<true, T>(d, kp, vis, a.scale_log2, st, thr, tau, pk, hmg);
+            uint16_t* row = reinterpret_cast<uint16_t*>(a.ring) + rowbase;
+            if (rows_now) {
 #pragma unroll
-          for (int tl = 0; tl < T; ++tl) {
-            float pv[4];
-            bool seen[4];
+              for (int tl = 0; tl < T; ++tl)
+                *reinterpret_cast<uint2*>(&sh_t[wv][n][tl * 16 + 4 * lg]) = make_uint2(pk[tl][0], pk[tl][1]);
+              __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // LDS is in order within a wave
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-              seen[r] = kp[tl][r] <= vis;
-              const float e = fast_exp2(d[tl][r] * a.scale_log2 - st.x) * st.y;
-              pv[r] = seen[r] ? e : 0.f;
-            }
-            if (a.ring_bf16) {
-              uint16_t hb[4];
-#pragma unroll
-              for (int r = 0; r < 4; ++r) {
-                hb[r] = f32_to_bf16_rne(pv[r]);
-                const float stored = __uint_as_float((uint32_t)hb[r] << 16);
-                hm[tl][r] = max(hm[tl][r], (seen[r] && stored >= thr) ? tau : 0);
+              for (int hh = 0; hh < 2; ++hh) {
+                const int qi = hh * 8 + (lane >> 3), ch = lane & 7;   // query of the tile, 16-byte piece of its row
+                const uint4 v = *reinterpret_cast<const uint4*>(&sh_t[wv][qi][ch * 8]);
+                int sl = s0 + jt * 16 + qi;
+                if (sl >= a.w) sl -= a.w;
+                uint16_t* dst =
+                    reinterpret_cast<uint16_t*>(a.ring) + ((size_t)head * a.w + sl) * a.Tcap + pos_w0 + ch * 8;
+                *reinterpret_cast<uint4*>(dst) = v;
               }
-              uint16_t* row = reinterpret_cast<uint16_t*>(a.ring) + rowbase;
-              if (quad[tl] && seen[3] && ((rowbase + (size_t)kp[tl][0]) & 3) == 0) {
-                *reinterpret_cast<uint2*>(row + kp[tl][0]) =
-                    make_uint2((uint32_t)hb[0] | ((uint32_t)hb[1] << 16), (uint32_t)hb[2] | ((uint32_t)hb[3] << 16));
-              } else {
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                  if (seen[r]) row[kp[tl][r]] = hb[r];
-              }
+              __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             } else {
 #pragma unroll
-              for (int r = 0; r < 4; ++r) hm[tl][r] = max(hm[tl][r], (seen[r] && pv[r] >= thr) ? tau : 0);
-              float* row = reinterpret_cast<float*>(a.ring) + rowbase;
-              if (quad[tl] && seen[3] && ((rowbase + (size_t)kp[tl][0]) & 3) == 0) {
+              for (int tl = 0; tl < T; ++tl) {
+                if (quad[tl] && kp[tl][3] <= vis && ((rowbase + (size_t)kp[tl][0]) & 3) == 0) {
+                  *reinterpret_cast<uint2*>(row + kp[tl][0]) = make_uint2(pk[tl][0], pk[tl][1]);
+                } else {
+#pragma unroll
+                  for (int r = 0; r < 4; ++r)
+                    if (kp[tl][r] <= vis) row[kp[tl][r]] = (uint16_t)(pk[tl][r >> 1] >> (16 * (r & 1)));
+                }
+              }
+            }
+          } else {
+            float* row = reinterpret_cast<float*>(a.ring) + rowbase;
+#pragma unroll
+            for (int tl = 0; tl < T; ++tl) {
+              float pv[4];
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                const bool seen = kp[tl][r] <= vis;
+                const float e = fast_exp2(fmaf(d[tl][r], a.scale_log2, -st.x)) * st.y;
+                pv[r] = seen ? e : 0.f;
+                hmg[tl][r] = (seen && pv[r] >= thr) ? tau : hmg[tl][r];
+              }
+              if (quad[tl] && kp[tl][3] <= vis && ((rowbase + (size_t)kp[tl][0]) & 3) == 0) {
                 *reinterpret_cast<float4*>(row + kp[tl][0]) = make_float4(pv[0], pv[1], pv[2], pv[3]);
               } else {
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                  if (seen[r]) row[kp[tl][r]] = pv[r];
+                  if (kp[tl][r] <= vis) row[kp[tl][r]] = pv[r];
               }
             }
           }
@@ -1657,6 +1743,10 @@ __global__ __launch_bounds__(WG) void corm_prefill_kernel(const PrefillArgs a) {
         __syncthreads();
       }
     }
+#pragma unroll
+    for (int tl = 0; tl < T; ++tl)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) hm[tl][r] = max(hm[tl][r], hmg[tl][r]);
   }
 
   if (PASS == 2) {
@@ -1694,7 +1784,9 @@ __global__ __launch_bounds__(256) void corm_prefill_merge_kernel(const PrefillAr
     const float2 pk = part[(size_t)k * a.w];
     z = fmaf(pk.y, exp2f(pk.x - ms), z);
   }
-  a.stats[(size_t)head * a.w + j] = make_float2(ms, z > 0.f ? 1.0f / z : 0.f);
+  const int tau = a.t[head / a.Hq] - a.m + 1 + j;
+  a.stats[(size_t)head * a.w + j] =
+      make_float4(ms, z > 0.f ? 1.0f / z : 0.f, importance_threshold(a.thr_scale, tau >= 1 ? tau : 1), 0.f);
 }
 
 // Def. 4.1 + recent r from last_hit for whole units (no append): wave ballots and survivors per chunk
@@ -1857,7 +1949,7 @@ WorkspaceLayout workspace_layout(const corm_desc& d) {
   w.seed_nkb = (d.Lcap + w.seed_kb - 1) / w.seed_kb;
   w.seed_part_off = align_up(w.stage_v_off + stage_rows * row_bytes(&d), 256);
   w.seed_stats_off = align_up(w.seed_part_off + heads * w.seed_nkb * d.w * sizeof(float2), 256);
-  w.total = align_up(w.seed_stats_off + heads * d.w * sizeof(float2), 256);
+  w.total = align_up(w.seed_stats_off + heads * d.w * sizeof(float4), 256);
   return w;
 }
 
@@ -2345,7 +2437,7 @@ int corm_prefill_seed(const corm_desc* desc, const void* q_tail, int32_t m, void
   PrefillArgs a;
   a.q_tail = q_tail; a.K = K; a.lens = lens; a.pos = pos; a.last_hit = last_hit; a.t = t; a.ring = score_ring;
   a.part = reinterpret_cast<float2*>(ws + wl.seed_part_off);
-  a.stats = reinterpret_cast<float2*>(ws + wl.seed_stats_off);
+  a.stats = reinterpret_cast<float4*>(ws + wl.seed_stats_off);
   a.status = status;
   a.Hq = desc->Hq; a.Hkv = desc->Hkv; a.Lcap = desc->Lcap; a.Tcap = desc->Tcap; a.w = desc->w; a.m = m;
   a.nkb = wl.seed_nkb; a.ring_bf16 = desc->score_dtype == CORM_BF16;
