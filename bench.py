@@ -291,7 +291,8 @@ def main():
     achieved = bytes_per_launch / (avg_attend_ms * 1e-3) / 1e9
     live_end = lens_hist[-1].float().mean().item() / (wl.P + W_steps + K_steps)
     unit_path = corm.corm_selected_path(desc) == 2
-    kernel_name = "corm_unit_kernel" if unit_path else "corm_attend_kernel"
+    gqa_mfma = wl.dtype == "bf16" and d == 128 and wl.G > 1 and args.path != 3
+    kernel_name = "corm_unit_kernel" if unit_path else ("corm_attend_gqa_kernel" if gqa_mfma else "corm_attend_kernel")
     evicted = int((lens_hist[:-1].long() + 1 - lens_hist[1:].long()).sum().item())
 
     result = {
