@@ -47,6 +47,9 @@ def parse():
     ap.add_argument("--seed", default="kernel", choices=["kernel", "replay"],
                     help="how the prompt fills the recent-query window before decoding (untimed set-up): one "
                          "corm_prefill_seed call per layer, or its last w tokens replayed through corm_decode_step")
+    ap.add_argument("--no-ring", action="store_true",
+                    help="summary-only state: no score ring is allocated or written (score_ring = NULL); decisions "
+                         "come from last_hit alone and are bit-identical")
     ap.add_argument("--extra-steps", type=int, default=4, help="untimed single-stream steps after the timed region "
                     "(exclusive measurement of the dominant kernel)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -129,7 +132,8 @@ def main():
     t_all = (torch.arange(n_replay + n_dec, dtype=torch.int32, device=dev) + (pre + 1)).view(-1, 1).repeat(1, B)
     t_first = torch.full((B,), pre + 1, dtype=torch.int32, device=dev)
     for l in range(layers):
-        st = corm.LayerState(B, Hq, Hkv, d, Lcap, Tcap, wl.w, wl.r, wl.dtype, device=dev, workspace=ws)
+        st = corm.LayerState(B, Hq, Hkv, d, Lcap, Tcap, wl.w, wl.r, wl.dtype, device=dev, workspace=ws,
+                             want_ring=not args.no_ring)
         st.lens = lens_all[l]
         st.nlive = nlive_all[l]
         x = inputs.make_layer(wl, l, device=dev, n_decode=n_dec, n_replay=n_replay)
@@ -213,7 +217,7 @@ def main():
         seeding = {"how": "corm_prefill_seed, one call per layer (layout copy of the queries included)",
                    "median_ms_per_layer": ms[len(ms) // 2],
                    "algorithmic_tflops": 2.0 * d * pairs * B * Hq / (ms[len(ms) // 2] * 1e-3) / 1e12,
-                   "ring_gb_written_per_layer": pairs * B * Hq * esz / 1e9}
+                   "ring_gb_written_per_layer": 0.0 if args.no_ring else pairs * B * Hq * esz / 1e9}
     else:
         for j in range(n_replay):          # prompt tail: seeds the recent-query window; bulk eviction at its end
             run_step(j)
@@ -227,7 +231,8 @@ def main():
 
     # ---------------- CPU baseline: the oracle, timed on a bounded sample of the same workload
     cpu_baseline = None
-    if not args.no_cpu_baseline and not lazy:   # (the oracle is rebuilt from compacted device snapshots)
+    # (the oracle is rebuilt from compacted device snapshots and from the recorded score window)
+    if not args.no_cpu_baseline and not lazy and not args.no_ring:
         cpu_baseline = cpu_baseline_leg(args, wl, states, Qs, Kns, Vns, n_replay, pre, layers, kv_off)
 
     if args.calibrate_copy:
@@ -263,7 +268,7 @@ def main():
 
     ms_per_step = ms_total / K_steps
     n_launch = K_steps * layers
-    ssz = esz
+    ssz = 0 if args.no_ring else esz
     # the whole step (every launch of every layer) against its algorithmic bytes
     total_bytes = sum(algorithmic_bytes(lens_hist[k], wl, esz, ssz) for k in range(K_steps))
     step_gbs = total_bytes / (ms_total * 1e-3) / 1e9
@@ -305,6 +310,7 @@ def main():
         "config": {"workload": wl.name + ("+structured_queries" if args.structured else ""),
                    "layers": layers, "batch": B, "q_heads": Hq, "kv_heads": Hkv, "head_dim": d,
                    "prompt": wl.P, "w": wl.w, "r": wl.r, "tokens_per_step": B, "streams": args.streams, "path": corm.corm_selected_path(desc),
+                   "score_ring": "none (summary-only state)" if args.no_ring else f"{wl.dtype} probabilities",
                    "compaction": f"deferred until {lazy[0]}/{lazy[1]} of a unit's slots are dead" if lazy
                    else "at every step",
                    "live_fraction_end": live_end, "keys_evicted_in_timed_region": evicted},

@@ -210,6 +210,14 @@ int corm_prefill_seed(const corm_desc* desc, const void* q_tail, int32_t m, void
                       uint8_t* keep, int32_t* kept_idx, void* workspace, size_t workspace_bytes, int32_t* status,
                       void* stream);
 
+/* Summary-only state.  corm_decode_attend, corm_step_attend, corm_decode_step, corm_decode_step_lazy and
+ * corm_prefill_seed accept score_ring == NULL: the scores are still formed, rounded to score_dtype and
+ * compared with c/t (Def. 3.1), and last_hit is updated, but no row is recorded.  last_hit alone decides
+ * Def. 4.1 (a key is kept iff its last important step lies inside the window), so every later decision,
+ * lens, K, V and out are bit for bit what the same calls produce with a ring; only corm_evict_mask, which
+ * reads the ring, is then unavailable.  Saves B*Hq*w*Tcap score elements of memory (the paper's own
+ * message is w x l booleans; this keeps one int32 per key instead). */
+
 /* Tuning / test knob (host call, process-wide, not thread safe): how attend + record are launched.
  * 0 = choose by shape (default); 1 = split kernels (several workgroups per unit, partials merged by a
  * second launch; grouped bf16 d=128 queries take q.K^T on the matrix cores); 2 = one workgroup per unit

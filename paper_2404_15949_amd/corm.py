@@ -262,7 +262,7 @@ class LayerState:
     """The device arrays of one layer, allocated with torch, in the layouts corm.h documents."""
 
     def __init__(self, B, Hq, Hkv, d, Lcap, Tcap, w, r, dtype, thr_scale=1.0, device="cuda",
-                 workspace: Optional[torch.Tensor] = None, want_masks=False):
+                 workspace: Optional[torch.Tensor] = None, want_masks=False, want_ring=True):
         tdt = {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
         self.desc = make_desc(B, Hq, Hkv, d, Lcap, Tcap, w, r, dtype, thr_scale=thr_scale)
         self.B, self.Hq, self.Hkv, self.d, self.Lcap, self.Tcap, self.w, self.r = B, Hq, Hkv, d, Lcap, Tcap, w, r
@@ -272,7 +272,8 @@ class LayerState:
         self.lens = torch.zeros(B, Hkv, dtype=torch.int32, device=device)
         self.pos = torch.zeros(B, Hkv, Lcap, dtype=torch.int32, device=device)
         self.last_hit = torch.zeros(B, Hkv, Lcap, dtype=torch.int32, device=device)
-        self.ring = torch.zeros(B, Hq, w, Tcap, dtype=tdt, device=device)
+        # want_ring=False: summary-only state (score_ring == NULL in every call)
+        self.ring = torch.zeros(B, Hq, w, Tcap, dtype=tdt, device=device) if want_ring else None
         self.out = torch.zeros(B, Hq, d, dtype=torch.float32, device=device)
         self.status = torch.zeros(1, dtype=torch.int32, device=device)
         self.keep = torch.zeros(B, Hkv, Lcap, dtype=torch.uint8, device=device) if want_masks else None

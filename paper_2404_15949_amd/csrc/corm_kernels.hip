@@ -930,10 +930,10 @@ __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, cons
         if (p.ring_bf16) {
           const uint16_t hb = f32_to_bf16_rne(sc);
           stored = __uint_as_float((uint32_t)hb << 16);
-          if (step_ok && pos_ok) reinterpret_cast<uint16_t*>(p.ring)[ri] = hb;
+          if (step_ok && pos_ok && p.ring) reinterpret_cast<uint16_t*>(p.ring)[ri] = hb;
         } else {
           stored = sc;
-          if (step_ok && pos_ok) reinterpret_cast<float*>(p.ring)[ri] = sc;
+          if (step_ok && pos_ok && p.ring) reinterpret_cast<float*>(p.ring)[ri] = sc;
         }
         hit |= (stored >= thr);
       }
@@ -1078,10 +1078,10 @@ __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const i
         if (p.ring_bf16) {
           const uint16_t hb = f32_to_bf16_rne(sc);
           stored = __uint_as_float((uint32_t)hb << 16);
-          if (step_ok && pos_ok) reinterpret_cast<uint16_t*>(p.ring)[ri] = hb;
+          if (step_ok && pos_ok && p.ring) reinterpret_cast<uint16_t*>(p.ring)[ri] = hb;
         } else {
           stored = sc;
-          if (step_ok && pos_ok) reinterpret_cast<float*>(p.ring)[ri] = sc;
+          if (step_ok && pos_ok && p.ring) reinterpret_cast<float*>(p.ring)[ri] = sc;
         }
         hit |= (stored >= thr);
       }
@@ -1673,7 +1673,9 @@ __global__ __launch_bounds__(WG) void corm_prefill_kernel(const PrefillArgs a) {
             if (all_seen) prefill_scores_bf16<false, T>(d, kp, vis, a.scale_log2, st, thr, tau, pk, hmg);
             else prefill_scores_bf16<true, T>(d, kp, vis, a.scale_log2, st, thr, tau, pk, hmg);
             uint16_t* row = reinterpret_cast<uint16_t*>(a.ring) + rowbase;
-            if (rows_now) {
+            if (!a.ring) {
+              // summary-only state: nothing is recorded but last_hit
+            } else if (rows_now) {
 #pragma unroll
               for (int tl = 0; tl < T; ++tl)
                 *reinterpret_cast<uint2*>(&sh_t[wv][n][tl * 16 + 4 * lg]) = make_uint2(pk[tl][0], pk[tl][1]);
@@ -1713,7 +1715,8 @@ __global__ __launch_bounds__(WG) void corm_prefill_kernel(const PrefillArgs a) {
                 pv[r] = seen ? e : 0.f;
                 hmg[tl][r] = (seen && pv[r] >= thr) ? tau : hmg[tl][r];
               }
-              if (quad[tl] && kp[tl][3] <= vis && ((rowbase + (size_t)kp[tl][0]) & 3) == 0) {
+              if (!a.ring) {
+              } else if (quad[tl] && kp[tl][3] <= vis && ((rowbase + (size_t)kp[tl][0]) & 3) == 0) {
                 *reinterpret_cast<float4*>(row + kp[tl][0]) = make_float4(pv[0], pv[1], pv[2], pv[3]);
               } else {
 #pragma unroll
@@ -2211,8 +2214,8 @@ int check_step_pointers(const void* q, const void* k_new, const void* v_new, con
                         const int32_t* lens, const int32_t* pos, const int32_t* last_hit, const int32_t* t,
                         const int32_t* t_first, const void* score_ring, const float* out, const int32_t* kept_idx,
                         const int32_t* status) {
-  if (!q || !k_new || !v_new || !K || !V || !lens || !pos || !last_hit || !t || !t_first || !score_ring || !out)
-    return CORM_EINVAL;
+  if (!q || !k_new || !v_new || !K || !V || !lens || !pos || !last_hit || !t || !t_first || !out)
+    return CORM_EINVAL;   // (score_ring may be null: summary-only state)
   if (misaligned16(q) || misaligned16(k_new) || misaligned16(v_new) || misaligned16(K) || misaligned16(V) ||
       misaligned4(out) || misaligned4(score_ring))
     return CORM_EINVAL;
@@ -2423,7 +2426,7 @@ int corm_prefill_seed(const corm_desc* desc, const void* q_tail, int32_t m, void
                       void* stream) {
   int rc = validate_desc(desc);
   if (rc) return rc;
-  if (!q_tail || !K || !V || !lens || !pos || !last_hit || !t || !t_first || !score_ring) return CORM_EINVAL;
+  if (!q_tail || !K || !V || !lens || !pos || !last_hit || !t || !t_first) return CORM_EINVAL;
   if (misaligned16(q_tail) || misaligned16(K) || misaligned16(V) || misaligned16(score_ring)) return CORM_EINVAL;
   if (misaligned4(lens) || misaligned4(pos) || misaligned4(last_hit) || misaligned4(t) || misaligned4(t_first) ||
       misaligned4(kept_idx) || misaligned4(status))

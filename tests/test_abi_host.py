@@ -77,6 +77,8 @@ def test_null_and_misaligned_pointers_are_rejected_on_the_host():
     args = dict(q=a, k_new=a, v_new=a, K=a, V=a, lens=a, pos=a, last_hit=a, t=a, t_first=a, score_ring=a, out=a)
     order = ["q", "k_new", "v_new", "K", "V", "lens", "pos", "last_hit", "t", "t_first", "score_ring", "out"]
     for missing in order:
+        if missing == "score_ring":
+            continue   # a null ring is legal (summary-only state): that call would pass validation and launch
         v = dict(args); v[missing] = None
         rc = corm.corm_decode_step(d, *[v[k] for k in order], workspace=a, workspace_bytes=1 << 30, check=False)
         assert rc == corm.CORM_EINVAL, missing

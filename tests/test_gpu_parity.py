@@ -206,6 +206,52 @@ def test_prefill_seed_bad_arguments():
     assert float(st.ring.abs().sum().item()) == 0.0
 
 
+@pytest.mark.parametrize("mode", ["exact", "lazy"])
+@pytest.mark.parametrize("name", ["bf16_mha", "f32_gqa4", "bf16_gqa4"])
+def test_summary_only_state_equals_the_ring_state(name, mode):
+    """score_ring == NULL: prompt seeding and every decode step leave the same bits (out, keep, lens, live
+    masks, K, V, pos, last_hit) as the same calls with a ring, whose parity with the oracle the other tests
+    establish."""
+    wl, _ = TRAJ[name]
+    x = {k: v.to(DEV) for k, v in inputs.make_layer(wl, 0, device="cpu").items() if k != "sinks"}
+    m = min(wl.w, wl.P)
+    a = corm.LayerState(wl.B, wl.Hq, wl.Hkv, wl.d, wl.P + wl.D, wl.P + wl.D, wl.w, wl.r, wl.dtype, device=DEV,
+                        want_masks=True)
+    b = corm.LayerState(wl.B, wl.Hq, wl.Hkv, wl.d, wl.P + wl.D, wl.P + wl.D, wl.w, wl.r, wl.dtype, device=DEV,
+                        want_masks=True, want_ring=False)
+    q_tail = x["Q"][:m].permute(1, 2, 0, 3).contiguous()
+    t = torch.full((wl.B,), wl.P, dtype=torch.int32, device=DEV)
+    tfs = []
+    for st in (a, b):
+        st.preload(x["K0"], x["V0"])
+        tf = torch.zeros_like(t)
+        st.prefill_seed(q_tail, t, tf)
+        tfs.append(tf)
+
+    def same(j):
+        torch.cuda.synchronize()
+        assert torch.equal(a.lens, b.lens) and torch.equal(a.keep, b.keep) and torch.equal(a.live, b.live), j
+        for bb in range(wl.B):
+            for h in range(wl.Hkv):
+                l = int(a.lens[bb, h].item())
+                for nm in ("K", "V", "pos", "last_hit"):
+                    assert torch.equal(getattr(a, nm)[bb, h, :l], getattr(b, nm)[bb, h, :l]), (nm, j, bb, h)
+
+    same("seed")
+    assert int((a.lens < wl.P).sum().item()) > 0, "the bulk eviction removed nothing"
+    for j in range(m, m + wl.D):
+        q, k, v, tt = harness.step_inputs(wl, x, j, m)
+        td = torch.full((wl.B,), tt, dtype=torch.int32, device=DEV)
+        for st, tf in zip((a, b), tfs):
+            if mode == "lazy":
+                st.step_lazy(q, k, v, td, tf, dead_num=1, dead_den=8)
+            else:
+                st.step(q, k, v, td, tf)
+        same(j)
+        assert torch.equal(a.out, b.out), j
+    assert int(a.status.item()) == 0 and int(b.status.item()) == 0
+
+
 def test_split_calls_equal_the_fused_step():
     """append + decode_attend + evict_mask (literal, also == summary) + compact: the same bits
     as the fused step, checked against the same oracle."""
