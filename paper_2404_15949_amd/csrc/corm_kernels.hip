@@ -790,9 +790,6 @@ __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, cons
 
   if (LAZY) stage_live_masks(p, unit, ul, 0, LIVE_WORDS, true, sh_live);
 
-  // metadata of the first record tile, fetched now and used after the stream
-  int pos_next = posb[min(tid, L - 1)];
-  int lh_next = lhb[min(tid, L - 1)];
   if (tid < UNIT_MAX_TILES) sh_tilecnt[tid] = 0;
 
   uint4 qreg[G];
@@ -838,6 +835,21 @@ __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, cons
                  sh_logit, lstride, m_run, z_run, acc);
     }
     off += (uint32_t)(2 * PAIRS_U) * STAGE_BYTES;
+  }
+
+  // The record phase's metadata (this thread's key of every 512-slot tile), requested in one batch as
+  // soon as the stream ends: one memory latency for the whole unit, hidden behind the merge, instead of
+  // one per tile.  The registers of the stream's stages are free by now.
+  int pos_r[UNIT_MAX_TILES], lh_r[UNIT_MAX_TILES];
+#pragma unroll
+  for (int kt = 0; kt < UNIT_MAX_TILES; ++kt) {
+    pos_r[kt] = 0;
+    lh_r[kt] = 0;
+    if (kt * UNIT_WG < L) {   // uniform over the workgroup
+      const int in = min(kt * UNIT_WG + tid, L - 1);
+      pos_r[kt] = posb[in];
+      lh_r[kt] = lhb[in];
+    }
   }
 
   // merge the row groups of each wave, then the waves
@@ -890,9 +902,8 @@ __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, cons
   }
   __syncthreads();
 
-  // record (Def. 3.1) and decide (Def. 4.1 + recent r).  The metadata of the next tile is loaded
-  // while the current one is processed; survivors per tile are summed with LDS atomics, so the
-  // loop has no barrier.
+  // record (Def. 3.1) and decide (Def. 4.1 + recent r).  Survivors per tile are summed with LDS
+  // atomics, so the loop has no barrier.
   const bool step_ok = tcur >= 1 && tcur <= p.Tcap;
   if (!step_ok && tid == 0 && p.status) atomicOr(p.status, CORM_DEV_BAD_STEP);
   const int slot = step_ok ? (tcur - 1) % p.w : 0;
@@ -910,13 +921,8 @@ __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, cons
     const int i = tile + tid;
     // (lazy mode: a slot whose key was evicted earlier takes no part: nothing recorded, stays dead)
     const bool live = i < L && (!LAZY || ((sh_live[i >> 6] >> (i & 63)) & 1ull));
-    const int my_pos = pos_next;
-    int lh = lh_next;
-    if (kt + 1 < UNIT_MAX_TILES) {   // clamped index: always a live slot, no branch around the load
-      const int in = min(i + UNIT_WG, L - 1);
-      pos_next = posb[in];
-      lh_next = lhb[in];
-    }
+    const int my_pos = pos_r[kt];
+    int lh = lh_r[kt];
     bool keep = false;
     if (live) {
       const bool pos_ok = my_pos >= 0 && my_pos < p.Tcap;

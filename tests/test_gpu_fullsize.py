@@ -176,3 +176,65 @@ def test_config5_prompt_seeding_gqa():
 def test_config4_prompt_seeding_long_context():
     wl = W["long32k"]
     _seed_check(wl, 0, [(3, 31)], rows_per_unit=3)
+
+
+# ------------------------------------------------------------------ deferred compaction at full size
+
+def test_config3_structured_lazy_steps():
+    """The eviction-heavy variant of config 3 in the launch configuration `bench.py --structured --lazy-frac 1/4`
+    times: window seeded by corm_prefill_seed, then corm_decode_step_lazy.  Sampled units are followed by
+    oracles rebuilt from the device state after the prompt and fed the recorded scores: at every step the
+    keep decision on the live slots, and at the end the live rows in slot order, last_hit and the live
+    counts, must be the oracle's; dead slots stay dead; out within tolerance."""
+    from oracle import corm_oracle as O
+    wl = W["llama7b_b16"].replace(q_mean_scales=inputs.STRUCTURED_Q_MEAN)
+    n_decode, frac = 12, (1, 4)
+    m = wl.w
+    say("lazy full size", wl.name, "B", wl.B, "heads", wl.Hq, "P", wl.P, "w", wl.w, "frac", frac)
+    x = inputs.make_layer(wl, 2, device=DEV, n_decode=n_decode, n_replay=m)
+    st = harness.make_state(wl, DEV, Lcap=wl.P + n_decode, Tcap=wl.P + n_decode)
+    assert corm.corm_selected_path(st.desc) == 2
+    st.preload(x["K0"], x["V0"])
+    t = torch.full((wl.B,), wl.P, dtype=torch.int32, device=DEV)
+    tf = torch.zeros_like(t)
+    st.prefill_seed(x["Q"][:m].permute(1, 2, 0, 3).contiguous(), t, tf)
+    torch.cuda.synchronize()
+    units = _sample_units(wl, 6, seed=9)
+    t_first = wl.P - m + 1
+    oracles = {u: harness.oracle_from_snapshot(st, u[0], u[1], wl.P, t_first, wl.dtype, 1.0) for u in units}
+    slots = {u: np.arange(oracles[u].l) for u in units}
+    used = {u: oracles[u].l for u in units}
+    G = wl.G
+    evicted = compactions = 0
+    for j in range(n_decode):
+        q, k, v, tt = harness.step_inputs(wl, x, m + j, m)
+        st.step_lazy(q, k, v, torch.full((wl.B,), tt, dtype=torch.int32, device=DEV), tf, dead_num=frac[0],
+                     dead_den=frac[1])
+        torch.cuda.synchronize()
+        assert int(st.status.item()) == 0
+        for (b, h) in units:
+            u = oracles[(b, h)]
+            live_pos = np.concatenate([u.positions, [tt - 1]])
+            pos_t = torch.from_numpy(live_pos).to(DEV)
+            recorded = st.ring[b, h * G:(h + 1) * G, (tt - 1) % wl.w].index_select(1, pos_t).float().cpu().numpy()
+            res = u.step(q[b, h * G:(h + 1) * G].float().cpu().numpy(), k[b, h].float().cpu().numpy(),
+                         v[b, h].float().cpu().numpy(), tt, recorded=recorded)
+            L = used[(b, h)] + 1
+            sl = np.concatenate([slots[(b, h)], [L - 1]])
+            kd = st.keep[b, h, :L].cpu().numpy().astype(bool)
+            assert np.array_equal(kd[sl], res["keep"]) and int(kd.sum()) == int(res["keep"].sum()), ("keep", j, b, h)
+            T = u.l
+            want = T < L and ((L - T) * frac[1] >= L * frac[0] or L + 1 >= st.Lcap)
+            assert int(st.lens[b, h].item()) == (T if want else L), ("lens / policy", j, b, h)
+            compactions += int(want)
+            evicted += len(live_pos) - T
+            slots[(b, h)] = harness.live_slots(st, b, h)
+            used[(b, h)] = int(st.lens[b, h].item())
+            for g in range(G):
+                e = harness.out_rel_err(st.out[b, h * G + g].cpu().numpy().astype(np.float64), res["out"][g])
+                assert e <= harness.OUT_TOL[wl.dtype], ("out", j, b, h, g, e)
+    for (b, h) in units:
+        harness.check_unit_state(st, b, h, oracles[(b, h)], wl.P + n_decode, lazy=True)
+    say("evicted", evicted, "compactions", compactions, "slots in use", [used[u] for u in units],
+        "live", [oracles[u].l for u in units])
+    assert evicted > 0
