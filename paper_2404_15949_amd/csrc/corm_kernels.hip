@@ -729,6 +729,7 @@ __global__ __launch_bounds__(WG) void corm_attend_gqa_kernel(const Params p) {
 
 constexpr int UNIT_WG = 512;
 constexpr int UNIT_WAVES = UNIT_WG / 64;
+constexpr int UNIT_XCDS = 8;         // accelerator dies of the device; the grid is a multiple of it
 constexpr int UNIT_MAX_TILES = 24;   // 48 KiB of logits hold at most 12288 slots = 24 tiles of 512
 static_assert(UNIT_WG == CHUNK, "the unit kernel reports survivors per CHUNK slots, one tile each");
 
@@ -747,7 +748,14 @@ __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, cons
   constexpr int LIVE_WORDS = (UNIT_MAX_TILES * CHUNK + 2048) / 64;
   __shared__ unsigned long long sh_live[LAZY ? LIVE_WORDS : 1];
 
-  const int unit = blockIdx.x;
+  // Workgroups are dealt round-robin to the 8 XCDs, so workgroup id % 8 names the XCD.  Each XCD gets a
+  // contiguous range of units: unit lengths often follow the head index with a small period (heads differ,
+  // sequences less so), and a strided assignment would put all the long units on one or two XCDs, which
+  // then finish the launch alone.
+  const int units = p.B * p.Hkv;
+  const int per_xcd = (units + UNIT_XCDS - 1) / UNIT_XCDS;
+  const int unit = (int)(blockIdx.x % UNIT_XCDS) * per_xcd + (int)(blockIdx.x / UNIT_XCDS);
+  if (unit >= units) return;
   const UnitLen ul = unit_len(p, unit);
   const int L = ul.L;
   const int b = unit / p.Hkv;
@@ -2113,7 +2121,8 @@ int launch_unit_dt(const corm_desc* d, const Params& p, int G, int units, size_t
 int launch_unit(const corm_desc* d, const Params& p, hipStream_t s) {
   int lstride;
   const size_t lds = unit_lds_bytes(d, &lstride);
-  const int G = d->Hq / d->Hkv, units = d->B * d->Hkv;
+  const int G = d->Hq / d->Hkv;
+  const int units = (d->B * d->Hkv + UNIT_XCDS - 1) / UNIT_XCDS * UNIT_XCDS;   // grid: whole rounds over the XCDs
   const hipEvent_t ev0 = g_prof_start, ev1 = g_prof_stop;
   g_prof_start = g_prof_stop = nullptr;
   if (ev0 && hipEventRecord(ev0, s) != hipSuccess) return CORM_EHIP;
