@@ -115,7 +115,7 @@ def main():
     K_steps, W_steps = args.steps, args.warmup
     n_dec = W_steps + K_steps + args.extra_steps
     n_replay = min(wl.w, wl.P)
-    Lcap = Tcap = wl.P + n_dec
+    Lcap = Tcap = (wl.P + n_dec + 63) // 64 * 64   # ring rows start on 128-byte lines (seeding stores whole lines)
     esz = 2 if wl.dtype == "bf16" else 4
     B, Hq, Hkv, d = wl.B, wl.Hq, wl.Hkv, wl.d
 

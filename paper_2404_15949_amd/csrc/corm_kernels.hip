@@ -96,6 +96,27 @@ __device__ __forceinline__ float row_allreduce_sum(float v) {
   return v;
 }
 
+// All-reduce over the four 16-lane rows of a wave (lanes l, l^16, l^32, l^48) on the vector ALU:
+// v_permlane16_swap exchanges the odd rows of its first operand with the even rows of its second,
+// v_permlane32_swap the upper half of the first with the lower half of the second; applied to two copies
+// of a value, the two results hold in every lane the value of the lane itself and of its partner.
+__device__ __forceinline__ float rows_allreduce_max(float v) {
+  const unsigned u = __float_as_uint(v);
+  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const float m = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  const unsigned w = __float_as_uint(m);
+  const auto b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float rows_allreduce_sum(float v) {
+  const unsigned u = __float_as_uint(v);
+  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const float m = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  const unsigned w = __float_as_uint(m);
+  const auto b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
 struct F32 {
   static constexpr int EPL = 4;  // elements per 16-byte lane slice
   static constexpr int ESZ = 4;
@@ -531,8 +552,7 @@ struct AttendGqa {
       tmax = fmaxf(tmax, s[r]);
     }
     // the 16 keys of head n are spread over the four lane groups
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+    tmax = rows_allreduce_max(tmax);
     const float mnew = fmaxf(m_run, tmax);
     const float msafe = mnew == neg_inf() ? 0.f : mnew;
     const float a = fast_exp2(m_run - msafe);
@@ -1492,8 +1512,7 @@ __device__ __forceinline__ void prefill_stats_tile(const f32x4_t (&d)[T], const 
   for (int tl = 0; tl < T; ++tl)
 #pragma unroll
     for (int r = 0; r < 4; ++r) mx = fmaxf(mx, (!MASKED || kp[tl][r] <= vis) ? d[tl][r] : neg_inf());
-  mx = fmaxf(mx, __shfl_xor(mx, 16));
-  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  mx = rows_allreduce_max(mx);
   const float ms = mx == neg_inf() ? 0.f : mx * scale_log2;
   float z = 0.f;
 #pragma unroll
@@ -1503,8 +1522,7 @@ __device__ __forceinline__ void prefill_stats_tile(const f32x4_t (&d)[T], const 
       const float e = fast_exp2(fmaf(d[tl][r], scale_log2, -ms));
       z += (!MASKED || kp[tl][r] <= vis) ? e : 0.f;
     }
-  z += __shfl_xor(z, 16);
-  z += __shfl_xor(z, 32);
+  z = rows_allreduce_sum(z);
   mx_out = mx == neg_inf() ? mx : ms;
   z_out = z;
 }
@@ -1542,6 +1560,10 @@ struct PrefillGeom {
   static constexpr int NCH = ROWB / 64;            // 64-byte chunks of a row
   static constexpr int T = NCH <= 4 ? 4 : 2;       // 16-key tiles per wave
   static constexpr int KB = WAVES * T * 16;        // keys per workgroup
+  static constexpr int QBLK = ROWB <= 256 ? 64 : 32;   // queries staged in LDS at a time
+  static constexpr int QROW = ROWB + 16;           // LDS row pitch (padded against bank conflicts)
+  static constexpr int QLOADS = QBLK * ROWB / (WG * 16);   // 16-byte loads per thread and block
+  static_assert(QBLK * ROWB % (WG * 16) == 0 && QBLK <= WG, "a block is loaded in whole passes of the workgroup");
 };
 
 template <typename DT, int D, int PASS>
@@ -1598,7 +1620,10 @@ __global__ __launch_bounds__(WG) void corm_prefill_kernel(const PrefillArgs a) {
   const int pfirst = posb[key_blk];
   const int jt_first = max(pfirst - tau0 + 1, 0) / 16;
 
+  constexpr int QBLK = Geo::QBLK, QROW = Geo::QROW, QLOADS = Geo::QLOADS;
   __shared__ float2 sh_part[PASS == 1 ? WAVES : 1][PASS == 1 ? PREFILL_SEG : 1];
+  __shared__ __attribute__((aligned(16))) char sh_q[2][QBLK * QROW];     // query blocks, double buffered
+  __shared__ __attribute__((aligned(16))) float4 sh_st[2][PASS == 2 ? QBLK : 1];   // (max, 1/sum, threshold, -) per query
   // Pass 2, bf16 ring: a wave's 16 x 64 tile of stored scores is turned through LDS so that every query's
   // 64 consecutive positions leave as one 128-byte piece of its ring row (16 bytes per lane) instead of
   // sixteen 8-byte pieces.  Rows are padded to 144 bytes.
@@ -1640,23 +1665,46 @@ __global__ __launch_bounds__(WG) void corm_prefill_kernel(const PrefillArgs a) {
         for (int i = tid; i < WAVES * PREFILL_SEG; i += WG) (&sh_part[0][0])[i] = make_float2(neg_inf(), 0.f);
         __syncthreads();
       }
-      const int jt0 = max(jt_first, seg0 / 16);
-      uint4 qb[NCH];
-      float4 st = make_float4(0.f, 0.f, 0.f, 0.f);
-      if (jt0 * 16 < seg1) {
+      // Queries reach the waves through LDS, QBLK at a time: the block after the current one is in flight
+      // (registers) while the current one is worked on, so the loop never waits on a load it has just
+      // issued -- nor, with it, on the acknowledgement of the ring stores of the tile before (loads and
+      // stores share one in-order counter).  Two LDS buffers, one barrier per block.
+      const int blk_first = max(jt_first * 16, seg0) / QBLK * QBLK;
+      uint4 qr[QLOADS];
+      float4 str = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (blk_first < seg1) {
+#pragma unroll
+        for (int i = 0; i < QLOADS; ++i)   // (past the last query the descriptor's range check returns zeros)
+          qr[i] = buffer_load16(rq, (uint32_t)blk_first * ROWB + (uint32_t)((i * WG + tid) * 16));
+        if (PASS == 2 && tid < QBLK && blk_first + tid < a.m) str = stats[blk_first + tid];
+      }
+      __syncthreads();   // the last block of the previous head / segment has been read by every wave
+      for (int blk = blk_first; blk < seg1; blk += QBLK) {
+        const int cur = (blk / QBLK) & 1;
+#pragma unroll
+        for (int i = 0; i < QLOADS; ++i) {
+          const int o = (i * WG + tid) * 16;   // byte offset inside the block: row o / ROWB, column o % ROWB
+          *reinterpret_cast<uint4*>(&sh_q[cur][(o / ROWB) * QROW + (o % ROWB)]) = qr[i];
+        }
+        if (PASS == 2 && tid < QBLK) sh_st[cur][tid] = str;
+        __syncthreads();
+        if (blk + QBLK < seg1) {
+#pragma unroll
+          for (int i = 0; i < QLOADS; ++i)
+            qr[i] = buffer_load16(rq, (uint32_t)(blk + QBLK) * ROWB + (uint32_t)((i * WG + tid) * 16));
+          str = make_float4(0.f, 0.f, 0.f, 0.f);
+          if (PASS == 2 && tid < QBLK && blk + QBLK + tid < a.m) str = stats[blk + QBLK + tid];
+        }
+#pragma unroll
+       for (int ti = 0; ti < QBLK / 16; ++ti) {   // unrolled: the next tile's MFMAs can start under this tile's tail
+        const int jt = blk / 16 + ti;
+        if (jt < jt_first || jt * 16 >= seg1) continue;   // (uniform) no key of this workgroup is visible / past the end
+        uint4 qb[NCH];
 #pragma unroll
         for (int c = 0; c < NCH; ++c)
-          qb[c] = buffer_load16(rq, (uint32_t)(jt0 * 16 + n) * ROWB + (uint32_t)(c * 64 + 16 * lg));
-        if (PASS == 2 && jt0 * 16 + n < a.m) st = stats[jt0 * 16 + n];
-      }
-      for (int jt = jt0; jt * 16 < seg1; ++jt) {
-        // the next tile's operand is fetched while this one is worked on
-        uint4 qn[NCH];
-        float4 stn = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-        for (int c = 0; c < NCH; ++c)   // (past the last query the descriptor's range check returns zeros)
-          qn[c] = buffer_load16(rq, (uint32_t)((jt + 1) * 16 + n) * ROWB + (uint32_t)(c * 64 + 16 * lg));
-        if (PASS == 2 && (jt + 1) * 16 + n < a.m) stn = stats[(jt + 1) * 16 + n];
+          qb[c] = *reinterpret_cast<const uint4*>(&sh_q[cur][(jt * 16 - blk + n) * QROW + c * 64 + 16 * lg]);
+        float4 st = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (PASS == 2) st = sh_st[cur][jt * 16 - blk + n];
 
         f32x4_t d[T];
 #pragma unroll
@@ -1740,9 +1788,7 @@ __global__ __launch_bounds__(WG) void corm_prefill_kernel(const PrefillArgs a) {
             }
           }
         }
-#pragma unroll
-        for (int c = 0; c < NCH; ++c) qb[c] = qn[c];
-        st = stn;
+       }
       }
       if (PASS == 1) {
         __syncthreads();
