@@ -1067,20 +1067,21 @@ __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const i
   }
   __syncthreads();
 
-  // out (Eq. 1): the (head, column) pairs of the unit are dealt round-robin to the waves of its
-  // workgroups; a wave sums one pair over the splits (lane = split) and reduces by shuffles
-  for (int pair = rsplit * WAVES + wv; pair < G * D; pair += nwg * WAVES) {
-    const int g = pair / D, c = pair - g * D;
+  // out (Eq. 1): (head, block of 64 columns) items of the unit are dealt round-robin to the waves of its
+  // workgroups; lane = column, so every split's partial row is read as one contiguous 256-byte piece
+  // and the loads of all splits are independent (no cross-lane reduction, one memory latency per item)
+  const int cblocks = D / 64;
+  for (int item = rsplit * WAVES + wv; item < G * cblocks; item += nwg * WAVES) {
+    const int g = item / cblocks, c = (item - g * cblocks) * 64 + lane;
     const float* part0 = p.partials + (size_t)(b * p.Hq + hq0 + g) * p.nsplit * PSTRIDE;
     const float ms = sh_M[g];
     float at = 0.f;
-    for (int s = lane; s < nlive; s += 64) {
+#pragma unroll 4
+    for (int s = 0; s < nlive; ++s) {
       const float* ps = part0 + (size_t)s * PSTRIDE;
       at = fmaf(ps[2 + c], exp2f(ps[0] - ms), at);
     }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) at += __shfl_xor(at, off);
-    if (lane == 0) p.out[(size_t)(b * p.Hq + hq0 + g) * D + c] = L > 0 ? at / sh_Z[g] : 0.f;
+    p.out[(size_t)(b * p.Hq + hq0 + g) * D + c] = L > 0 ? at / sh_Z[g] : 0.f;
   }
   if (L == 0) return;  // an empty unit: nothing to record
 
