@@ -210,6 +210,11 @@ int corm_prefill_seed(const corm_desc* desc, const void* q_tail, int32_t m, void
                       uint8_t* keep, int32_t* kept_idx, void* workspace, size_t workspace_bytes, int32_t* status,
                       void* stream);
 
+/* HIP graph capture.  The step, seeding and standalone calls enqueue kernels only (no allocation, no memset,
+ * no host synchronization), so a caller may capture them in a HIP graph on `stream` and replay it with the
+ * inputs refreshed in place.  The first call of a process queries the device once (number of compute
+ * units): make one call eagerly before capturing.  corm_profile_attend must not be armed during capture. */
+
 /* Summary-only state.  corm_decode_attend, corm_step_attend, corm_decode_step, corm_decode_step_lazy and
  * corm_prefill_seed accept score_ring == NULL: the scores are still formed, rounded to score_dtype and
  * compared with c/t (Def. 3.1), and last_hit is updated, but no row is recorded.  last_hit alone decides

@@ -574,3 +574,51 @@ def test_two_phase_calls_on_two_streams_equal_the_fused_step():
     for a, b in zip(*results):
         assert torch.equal(a, b)
     assert results[0][1].min() < wl.P
+
+
+def test_decode_step_under_hip_graph_capture():
+    """The library allocates nothing and records no memset, so a caller may capture a step in a HIP graph:
+    every replay (inputs refreshed in place, eager work and synchronizations in between) must leave exactly
+    the state an eager twin reaches."""
+    wl, _ = TRAJ["bf16_mha"]
+    x = {k: v.to(DEV) for k, v in inputs.make_layer(wl, 0, device="cpu").items() if k != "sinks"}
+    n_replay = min(wl.w, wl.P)
+    pre = wl.P - n_replay
+    a, b = harness.make_state(wl, DEV), harness.make_state(wl, DEV)
+    for st in (a, b):
+        st.preload(x["K0"][:, :, :pre], x["V0"][:, :, :pre])
+    tf = torch.full((wl.B,), pre + 1, dtype=torch.int32, device=DEV)
+    q0, k0, v0, t0 = harness.step_inputs(wl, x, 0, n_replay)
+    qs, ks, vs = q0.clone(), k0.clone(), v0.clone()
+    ts = torch.full((wl.B,), t0, dtype=torch.int32, device=DEV)
+    # first step eagerly on both (warm-up before capture), then capture the step of `a`
+    a.step(qs, ks, vs, ts, tf)
+    b.step(q0, k0, v0, ts.clone(), tf)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            a.step(qs, ks, vs, ts, tf)
+    torch.cuda.synchronize()
+    # capture does not execute: `a` is still one step behind what the next replay will compute
+    evicted = 0
+    for j in range(1, n_replay + wl.D):
+        q, k, v, t = harness.step_inputs(wl, x, j, n_replay)
+        qs.copy_(q); ks.copy_(k); vs.copy_(v); ts.fill_(t)
+        graph.replay()
+        b.step(q, k, v, torch.full((wl.B,), t, dtype=torch.int32, device=DEV), tf)
+        torch.cuda.synchronize()
+        assert torch.equal(a.lens, b.lens), j
+        assert torch.equal(a.out, b.out), j
+        assert torch.equal(a.keep, b.keep) and torch.equal(a.kept_idx, b.kept_idx), j
+        evicted += int((a.keep == 0).sum().item())
+        (a.out.sum() + a.lens.sum()).item()   # eager work between replays
+    for nm in ("K", "V", "pos", "last_hit"):
+        for bb in range(wl.B):
+            for h in range(wl.Hkv):
+                l = int(a.lens[bb, h].item())
+                assert torch.equal(getattr(a, nm)[bb, h, :l], getattr(b, nm)[bb, h, :l]), (nm, bb, h)
+    assert torch.equal(a.ring, b.ring)
+    assert int(a.status.item()) == 0 and int(b.status.item()) == 0
