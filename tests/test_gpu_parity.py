@@ -183,6 +183,55 @@ def test_prefill_seed_offsets_and_short_tail():
     assert rep["evicted_total"] > 0   # the window fills during decode
 
 
+def test_prefill_seed_on_a_cache_with_holes():
+    """Positions need not be consecutive: keys are dropped from the part of the prompt before the tail (as an
+    earlier eviction would have), then the tail is seeded.  A key is visible to a query by its position, ring
+    entries go to the position's column, and the oracle replaying the tail over the same thinned cache must
+    agree bit for bit on the decision and the compacted rows."""
+    wl = W["llama7b_1layer"].replace(B=2, Hq=4, Hkv=2, P=900, D=4, w=64, r=16)
+    x_cpu = inputs.make_layer(wl, 0, device="cpu")
+    x = {k: v.to(DEV) for k, v in x_cpu.items() if k != "sinks"}
+    m, G, P = wl.w, wl.G, wl.P
+    pre = P - m
+    st = harness.make_state(wl, DEV, Tcap=P + 8, Lcap=P + 8)
+    st.preload(x["K0"], x["V0"])
+    rng = np.random.default_rng(3)
+    mask = np.ones((wl.B, wl.Hkv, st.Lcap), dtype=np.uint8)
+    mask[:, :, :pre] = rng.random((wl.B, wl.Hkv, pre)) < 0.7
+    corm.corm_compact(st.desc, st.K, st.V, st.pos, st.last_hit, st.lens, torch.from_numpy(mask).to(DEV), None,
+                      st.workspace)
+    torch.cuda.synchronize()
+    t = torch.full((wl.B,), P, dtype=torch.int32, device=DEV)
+    tf = torch.zeros_like(t)
+    st.prefill_seed(x["Q"][:m].permute(1, 2, 0, 3).contiguous(), t, tf)
+    torch.cuda.synchronize()
+    assert int(st.status.item()) == 0
+    evicted = 0
+    for b in range(wl.B):
+        ring = st.ring[b].float().cpu().numpy()
+        for h in range(wl.Hkv):
+            kept = np.nonzero(mask[b, h, :pre])[0]
+            u = O.UnitCache(wl.d, G, wl.w, wl.r, score_dtype=wl.dtype)
+            u.preload(x_cpu["K0"][b, h, kept].float().numpy(), x_cpu["V0"][b, h, kept].float().numpy())
+            u.positions = kept.astype(np.int64)
+            res = None
+            for j in range(m):
+                p = pre + j
+                live_pos = np.concatenate([u.positions, [p]])
+                recorded = ring[h * G:(h + 1) * G, p % wl.w][:, live_pos]
+                res = u.step(x_cpu["Q"][j, b, h * G:(h + 1) * G].float().numpy(), x_cpu["K0"][b, h, p].float().numpy(),
+                             x_cpu["V0"][b, h, p].float().numpy(), p + 1, recorded=recorded)
+                for g in range(G):
+                    a = res["alpha"][g]
+                    err = np.abs(recorded[g].astype(np.float64) - a)
+                    assert (err <= harness.SCORE_RTOL[wl.dtype] * a + harness.SCORE_ATOL_OF_MAX[wl.dtype] * a.max()).all()
+            n_before = len(kept) + m
+            assert np.array_equal(st.keep[b, h, :n_before].cpu().numpy().astype(bool), res["keep"]), (b, h)
+            harness.check_unit_state(st, b, h, u, P)
+            evicted += n_before - u.l
+    assert evicted > 0
+
+
 def test_prefill_seed_bad_arguments():
     wl = W["tiny_f32"]
     st = harness.make_state(wl, DEV)
