@@ -1023,6 +1023,7 @@ __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const i
   const int rend = min(rbeg + RECORD_ROWS, L);
 
   __shared__ float sh_M[G], sh_Z[G];
+  __shared__ float sh_out[WAVES][64];
   __shared__ int sh_cnt[RECORD_CHUNKS][WAVES];
 
   // this thread's keys: issue their loads first, they are consumed after the merge below
@@ -1067,21 +1068,30 @@ __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const i
   }
   __syncthreads();
 
-  // out (Eq. 1): (head, block of 64 columns) items of the unit are dealt round-robin to the waves of its
+  // out (Eq. 1): (head, block of 64 columns) items of the unit are dealt round-robin to its
   // workgroups; lane = column, so every split's partial row is read as one contiguous 256-byte piece
   // and the loads of all splits are independent (no cross-lane reduction, one memory latency per item)
+  // An item belongs to one workgroup; its waves take the splits round-robin and meet in LDS.
   const int cblocks = D / 64;
-  for (int item = rsplit * WAVES + wv; item < G * cblocks; item += nwg * WAVES) {
+  for (int item = rsplit; item < G * cblocks; item += nwg) {   // (uniform over the workgroup)
     const int g = item / cblocks, c = (item - g * cblocks) * 64 + lane;
     const float* part0 = p.partials + (size_t)(b * p.Hq + hq0 + g) * p.nsplit * PSTRIDE;
     const float ms = sh_M[g];
     float at = 0.f;
 #pragma unroll 4
-    for (int s = 0; s < nlive; ++s) {
+    for (int s = wv; s < nlive; s += WAVES) {
       const float* ps = part0 + (size_t)s * PSTRIDE;
       at = fmaf(ps[2 + c], exp2f(ps[0] - ms), at);
     }
-    p.out[(size_t)(b * p.Hq + hq0 + g) * D + c] = L > 0 ? at / sh_Z[g] : 0.f;
+    sh_out[wv][lane] = at;
+    __syncthreads();
+    if (wv == 0) {
+      float tot = 0.f;
+#pragma unroll
+      for (int i = 0; i < WAVES; ++i) tot += sh_out[i][lane];
+      p.out[(size_t)(b * p.Hq + hq0 + g) * D + c] = L > 0 ? tot / sh_Z[g] : 0.f;
+    }
+    __syncthreads();
   }
   if (L == 0) return;  // an empty unit: nothing to record
 
