@@ -20,7 +20,7 @@ def say(*a):
     sys.stdout.flush()
 
 
-def _run(wl, layer, n_decode, check_steps, units, expect_path=None, expect_evictions=False):
+def _run(wl, layer, n_decode, check_steps, units, expect_path=None, expect_evictions=False, seed_kernel=False):
     say("full size", wl.name, "layer", layer, "B", wl.B, "Hq/Hkv", wl.Hq, wl.Hkv, "P", wl.P, "w", wl.w,
         "q_mean", bool(wl.q_mean_scales))
     n_replay = min(wl.w, wl.P)
@@ -29,19 +29,29 @@ def _run(wl, layer, n_decode, check_steps, units, expect_path=None, expect_evict
     if expect_path is not None:
         assert corm.corm_selected_path(st.desc) == expect_path
     pre = wl.P - n_replay
-    st.preload(x["K0"][:, :, :pre], x["V0"][:, :, :pre])
     tf = torch.full((wl.B,), pre + 1, dtype=torch.int32, device=DEV)
-    # the prompt tail: all but its last position unchecked (the last one carries the bulk eviction)
-    for j in range(n_replay - 1):
-        q, k, v, t = harness.step_inputs(wl, x, j, n_replay)
-        st.step(q, k, v, torch.full((wl.B,), t, dtype=torch.int32, device=DEV), tf)
+    if seed_kernel:
+        # as bench.py sets up: the whole prompt preloaded, its last w queries recorded by one dense call
+        st.preload(x["K0"], x["V0"])
+        tf_out = torch.zeros_like(tf)
+        st.prefill_seed(x["Q"][:n_replay].permute(1, 2, 0, 3).contiguous(),
+                        torch.full((wl.B,), wl.P, dtype=torch.int32, device=DEV), tf_out)
+        assert torch.equal(tf_out, tf)
+        first = n_replay
+    else:
+        st.preload(x["K0"][:, :, :pre], x["V0"][:, :, :pre])
+        # the prompt tail: all but its last position unchecked (the last one carries the bulk eviction)
+        for j in range(n_replay - 1):
+            q, k, v, t = harness.step_inputs(wl, x, j, n_replay)
+            st.step(q, k, v, torch.full((wl.B,), t, dtype=torch.int32, device=DEV), tf)
+        first = n_replay - 1
     torch.cuda.synchronize()
     assert int(st.status.item()) == 0
     total_evicted = 0
     worst = 0.0
-    for j in range(n_replay - 1, n_replay + n_decode):
+    for j in range(first, n_replay + n_decode):
         q, k, v, t = harness.step_inputs(wl, x, j, n_replay)
-        if j in check_steps or j == n_replay - 1:
+        if j in check_steps or j == first:
             rep = harness.snapshot_step_check(st, wl, q, k, v, t, pre + 1, units)
             total_evicted += rep["evicted"]
             worst = max(worst, rep["worst_out_rel_err"])
@@ -74,6 +84,15 @@ def test_config3_llama7b_batch16_layer(layer):
     wl = W["llama7b_b16"]
     n_replay = wl.w
     _run(wl, layer, 5, {n_replay, n_replay + 4}, _sample_units(wl, 5, seed=layer), expect_path=2)
+
+
+def test_config3_as_the_bench_runs_it():
+    """Seeded by corm_prefill_seed (the bench's set-up), then exact decode steps on the fused unit kernel."""
+    wl = W["llama7b_b16"]
+    n_replay = wl.w
+    _run(wl, 5, 4, {n_replay, n_replay + 3}, _sample_units(wl, 4, seed=12), expect_path=2, seed_kernel=True)
+    _run(wl.replace(q_mean_scales=inputs.STRUCTURED_Q_MEAN), 3, 4, {n_replay, n_replay + 3},
+         _sample_units(wl, 4, seed=13), expect_path=2, expect_evictions=True, seed_kernel=True)
 
 
 def test_config3_structured_queries_evict_and_compact():
