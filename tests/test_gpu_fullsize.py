@@ -75,7 +75,7 @@ def _sample_units(wl, n, seed=0):
 def test_config2_llama7b_one_layer():
     wl = W["llama7b_1layer"]
     n_replay = wl.w
-    _run(wl, 0, 6, {n_replay, n_replay + 3, n_replay + 5}, _sample_units(wl, 4), expect_path=1)
+    _run(wl, 0, 6, {n_replay, n_replay + 3, n_replay + 5}, _sample_units(wl, 10), expect_path=1)
 
 
 @pytest.mark.parametrize("layer", [0, 2])
@@ -83,7 +83,7 @@ def test_config3_llama7b_batch16_layer(layer):
     """One dense (0) and one sparse (2) layer of the full stack; the launch is exactly the one bench.py times."""
     wl = W["llama7b_b16"]
     n_replay = wl.w
-    _run(wl, layer, 5, {n_replay, n_replay + 4}, _sample_units(wl, 5, seed=layer), expect_path=2)
+    _run(wl, layer, 5, {n_replay, n_replay + 4}, _sample_units(wl, 12, seed=layer), expect_path=2)
 
 
 def test_config3_as_the_bench_runs_it():
@@ -100,7 +100,7 @@ def test_config3_structured_queries_evict_and_compact():
     the bulk eviction at the end of the prompt takes the serial compaction path, decode steps the parallel one."""
     wl = W["llama7b_b16"].replace(q_mean_scales=inputs.STRUCTURED_Q_MEAN)
     n_replay = wl.w
-    lens = _run(wl, 2, 6, {n_replay, n_replay + 1, n_replay + 5}, _sample_units(wl, 6, seed=5), expect_path=2,
+    lens = _run(wl, 2, 6, {n_replay, n_replay + 1, n_replay + 5}, _sample_units(wl, 12, seed=5), expect_path=2,
                 expect_evictions=True)
     assert lens.max() - lens.min() > 1000
 
@@ -114,13 +114,13 @@ def test_config4_long_context():
 def test_config5_gqa():
     wl = W["gqa_llama3"]
     n_replay = wl.w
-    _run(wl, 0, 4, {n_replay, n_replay + 3}, _sample_units(wl, 3), expect_path=1)
+    _run(wl, 0, 4, {n_replay, n_replay + 3}, _sample_units(wl, 6), expect_path=1)
 
 
 def test_config5_gqa_structured_evicts():
     wl = W["gqa_llama3"].replace(q_mean_scales=(3.0, 5.0), key_scale=1.5)
     n_replay = wl.w
-    _run(wl, 0, 4, {n_replay, n_replay + 3}, _sample_units(wl, 3, seed=2), expect_path=1, expect_evictions=True)
+    _run(wl, 0, 4, {n_replay, n_replay + 3}, _sample_units(wl, 6, seed=2), expect_path=1, expect_evictions=True)
 
 
 # ------------------------------------------------------------------ prompt seeding at full size
@@ -182,14 +182,14 @@ def _seed_check(wl, layer, units, rows_per_unit=5, expect_evictions=False):
 
 def test_config3_prompt_seeding():
     wl = W["llama7b_b16"]
-    _seed_check(wl, 2, _sample_units(wl, 3, seed=3))
-    _seed_check(wl.replace(q_mean_scales=inputs.STRUCTURED_Q_MEAN), 2, _sample_units(wl, 4, seed=4),
+    _seed_check(wl, 2, _sample_units(wl, 6, seed=3))
+    _seed_check(wl.replace(q_mean_scales=inputs.STRUCTURED_Q_MEAN), 2, _sample_units(wl, 8, seed=4),
                 expect_evictions=True)
 
 
 def test_config5_prompt_seeding_gqa():
     wl = W["gqa_llama3"].replace(q_mean_scales=(3.0, 5.0), key_scale=1.5)
-    _seed_check(wl, 0, _sample_units(wl, 2, seed=6), expect_evictions=True)
+    _seed_check(wl, 0, _sample_units(wl, 4, seed=6), expect_evictions=True)
 
 
 def test_config4_prompt_seeding_long_context():
@@ -218,7 +218,7 @@ def test_config3_structured_lazy_steps():
     tf = torch.zeros_like(t)
     st.prefill_seed(x["Q"][:m].permute(1, 2, 0, 3).contiguous(), t, tf)
     torch.cuda.synchronize()
-    units = _sample_units(wl, 6, seed=9)
+    units = _sample_units(wl, 10, seed=9)
     t_first = wl.P - m + 1
     oracles = {u: harness.oracle_from_snapshot(st, u[0], u[1], wl.P, t_first, wl.dtype, 1.0) for u in units}
     slots = {u: np.arange(oracles[u].l) for u in units}
