@@ -50,6 +50,12 @@
  * Arithmetic: logits and all accumulation in fp32; scores are rounded (nearest-even) to
  * score_dtype when stored, and the importance test compares the STORED value, widened to fp32,
  * against fp32(c) / fp32(t) (IEEE division) with >=.
+ *
+ * score_dtype CORM_BIT: the ring holds the boolean message of Algorithm 1 instead of scores:
+ *   score_ring     [B, Hq, w, ceil(Tcap/32)]  uint32     bit (pos % 32) of word (pos / 32) of row (tau-1) mod w
+ *                                                        = the key at position pos was important at step tau
+ * (1/16 of a bf16 ring).  The test then compares the fp32 score itself; the row of a step is cleared
+ * before its bits are set.
  */
 #ifndef CORM_H
 #define CORM_H
@@ -61,7 +67,7 @@
 extern "C" {
 #endif
 
-enum corm_dtype { CORM_F32 = 0, CORM_BF16 = 1 };
+enum corm_dtype { CORM_F32 = 0, CORM_BF16 = 1, CORM_BIT = 2 /* score_dtype only */ };
 
 enum corm_status {
   CORM_OK = 0,

@@ -22,7 +22,8 @@ def unit_from_device_arrays(K, V, pos, lens, ring, b: int, h: int, G: int, w: in
     """State of unit (b, h) after step t_prev.
 
     K, V [B,Hkv,Lcap,d]; pos [B,Hkv,Lcap]; lens [B,Hkv]; ring [B,Hq,w,Tcap] with the row of step
-    tau in slot (tau-1) mod w and columns indexed by absolute position.  The boolean message of
+    tau in slot (tau-1) mod w and columns indexed by absolute position (or, int32, the boolean message
+    [B,Hq,w,ceil(Tcap/32)]: bit pos % 32 of word pos // 32).  The boolean message of
     Algorithm 1 is rebuilt by thresholding each recorded row with its own c/tau (Def. 3.1);
     keys that did not exist at step tau count as minor in that row.
     """
@@ -34,11 +35,17 @@ def unit_from_device_arrays(K, V, pos, lens, ring, b: int, h: int, G: int, w: in
     u.positions = pos[b, h, :l].cpu().numpy().astype(np.int64)
     rows = list(range(max(t_first, t_prev - w + 1), t_prev + 1))
     pos_t = torch.from_numpy(u.positions).to(ring.device)
-    sc_all = _f32(ring[b, h * G:(h + 1) * G].index_select(2, pos_t))        # [G, w, l]
+    bits = ring.dtype == torch.int32     # the ring holds the boolean message itself, 32 positions per word
+    if bits:
+        words = ring[b, h * G:(h + 1) * G].index_select(2, pos_t >> 5)     # [G, w, l]
+        sc_all = ((words >> (pos_t & 31)) & 1).cpu().numpy().astype(bool)
+    else:
+        sc_all = _f32(ring[b, h * G:(h + 1) * G].index_select(2, pos_t))   # [G, w, l]
     msg = np.zeros((len(rows), G, l), dtype=bool)
     for a, tau in enumerate(rows):
         born = u.positions <= tau - 1
-        msg[a] = O.important(sc_all[:, (tau - 1) % w], tau, thr_scale) & born[None, :]
+        row = sc_all[:, (tau - 1) % w]
+        msg[a] = (row if bits else O.important(row, tau, thr_scale)) & born[None, :]
     u.message = msg
     u.row_steps = rows
     return u

@@ -16,7 +16,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcorm.so")
 
-CORM_F32, CORM_BF16 = 0, 1
+CORM_F32, CORM_BF16, CORM_BIT = 0, 1, 2
 CORM_OK, CORM_EINVAL, CORM_EUNSUPPORTED, CORM_ECAPACITY, CORM_EHIP = 0, -1, -2, -3, -4
 CORM_DEV_UNIT_FULL, CORM_DEV_BAD_STEP, CORM_DEV_BAD_LENS = 1, 2, 4
 
@@ -112,9 +112,10 @@ def _check(code: int, what: str) -> int:
 
 def make_desc(B, Hq, Hkv, d, Lcap, Tcap, w, r, kv_dtype, score_dtype=None, thr_scale=1.0, sm_scale=0.0) -> corm_desc:
     def code(x):
-        if x in (CORM_F32, CORM_BF16):
+        if x in (CORM_F32, CORM_BF16, CORM_BIT):
             return x
-        return {"f32": CORM_F32, "bf16": CORM_BF16, torch.float32: CORM_F32, torch.bfloat16: CORM_BF16}[x]
+        return {"f32": CORM_F32, "bf16": CORM_BF16, "bit": CORM_BIT, torch.float32: CORM_F32,
+                torch.bfloat16: CORM_BF16}[x]
     kv = code(kv_dtype)
     sc = kv if score_dtype is None else code(score_dtype)
     return corm_desc(B, Hq, Hkv, d, Lcap, Tcap, w, r, kv, sc, thr_scale, sm_scale)
@@ -262,9 +263,10 @@ class LayerState:
     """The device arrays of one layer, allocated with torch, in the layouts corm.h documents."""
 
     def __init__(self, B, Hq, Hkv, d, Lcap, Tcap, w, r, dtype, thr_scale=1.0, device="cuda",
-                 workspace: Optional[torch.Tensor] = None, want_masks=False, want_ring=True):
+                 workspace: Optional[torch.Tensor] = None, want_masks=False, want_ring=True, score_dtype=None):
         tdt = {"f32": torch.float32, "bf16": torch.bfloat16}[dtype]
-        self.desc = make_desc(B, Hq, Hkv, d, Lcap, Tcap, w, r, dtype, thr_scale=thr_scale)
+        self.desc = make_desc(B, Hq, Hkv, d, Lcap, Tcap, w, r, dtype, score_dtype=score_dtype, thr_scale=thr_scale)
+        self.ring_bits = self.desc.score_dtype == CORM_BIT
         self.B, self.Hq, self.Hkv, self.d, self.Lcap, self.Tcap, self.w, self.r = B, Hq, Hkv, d, Lcap, Tcap, w, r
         self.dtype = tdt
         self.K = torch.zeros(B, Hkv, Lcap, d, dtype=tdt, device=device)
@@ -273,7 +275,13 @@ class LayerState:
         self.pos = torch.zeros(B, Hkv, Lcap, dtype=torch.int32, device=device)
         self.last_hit = torch.zeros(B, Hkv, Lcap, dtype=torch.int32, device=device)
         # want_ring=False: summary-only state (score_ring == NULL in every call)
-        self.ring = torch.zeros(B, Hq, w, Tcap, dtype=tdt, device=device) if want_ring else None
+        if not want_ring:
+            self.ring = None
+        elif self.ring_bits:   # the boolean message: bit pos % 32 of word pos // 32
+            self.ring = torch.zeros(B, Hq, w, (Tcap + 31) // 32, dtype=torch.int32, device=device)
+        else:
+            sdt = tdt if score_dtype is None else {"f32": torch.float32, "bf16": torch.bfloat16}[score_dtype]
+            self.ring = torch.zeros(B, Hq, w, Tcap, dtype=sdt, device=device)
         self.out = torch.zeros(B, Hq, d, dtype=torch.float32, device=device)
         self.status = torch.zeros(1, dtype=torch.int32, device=device)
         self.keep = torch.zeros(B, Hkv, Lcap, dtype=torch.uint8, device=device) if want_masks else None

@@ -56,6 +56,8 @@ struct Params {
   int32_t B, Hq, Hkv, Lcap, Tcap, w, r, nsplit;
   float thr_scale, scale_log2;
   int32_t do_append, do_evict, ring_bf16;
+  int32_t ring_bits;    // the ring holds the boolean message: one bit per (row, position), 32 positions per word
+  int32_t ring_words;   // words per ring row in that case: ceil(Tcap / 32)
   int32_t kb_stride;    // 64-bit words per unit in keepbits
   int32_t lazy;         // lazy mode: keepbits are the caller's persistent live masks; dead slots are skipped
 };
@@ -193,6 +195,50 @@ __device__ __forceinline__ UnitLen unit_len(const Params& p, int unit) {
     }
   }
   return u;
+}
+
+// ---------------------------------------------------------------- boolean message (bit ring)
+//
+// score_dtype CORM_BIT: the ring holds what Algorithm 1 itself keeps, one bit per (recorded query, key
+// position): [B, Hq, w, ceil(Tcap/32)] words, bit pos % 32 of word pos / 32.  The row of a step is
+// cleared before the step's keys are recorded into it (the positions a step can touch are < t).
+
+__device__ __forceinline__ void clear_bit_rows(const Params& p, int b, int hq0, int G, int nthreads) {
+  const int tcur = p.t[b];
+  if (!p.ring_bits || !p.ring || tcur < 1 || tcur > p.Tcap) return;
+  const int slot = (tcur - 1) % p.w;
+  const int nw = min((tcur + 31) >> 5, p.ring_words);
+  for (int g = 0; g < G; ++g) {
+    uint32_t* row = reinterpret_cast<uint32_t*>(p.ring) + ((size_t)(b * p.Hq + hq0 + g) * p.w + slot) * p.ring_words;
+    for (int i = threadIdx.x; i < nw; i += nthreads) row[i] = 0u;
+  }
+}
+
+// Sets the bits of the keys this wave found important for one head.  pos: this lane's key position
+// (any value where !valid); hit implies valid.  When the valid lanes hold consecutive positions
+// (lane l: base + l) the wave's ballot is shifted into at most three words and three lanes issue one
+// atomic each; otherwise every hit lane sets its own bit.
+__device__ __forceinline__ void record_bits(uint32_t* row, int ring_words, int pos, bool valid, bool hit) {
+  const int lane = threadIdx.x & 63;
+  const unsigned long long vmask = __ballot(valid);
+  if (vmask == 0ull) return;
+  const int first = __ffsll((long long)vmask) - 1;
+  const int base = __shfl(pos, first) - first;
+  const bool run = __all(!valid || pos == base + lane) && base >= 0;
+  const unsigned long long hmask = __ballot(hit);
+  if (hmask == 0ull) return;
+  if (run) {
+    const int sh = base & 31;
+    const unsigned long long lo = hmask << sh;                        // bits 0..63 of the shifted mask
+    const uint32_t hi = sh ? (uint32_t)(hmask >> (64 - sh)) : 0u;     // bits 64..95
+    if (lane < 3) {
+      const uint32_t part = lane == 0 ? (uint32_t)lo : (lane == 1 ? (uint32_t)(lo >> 32) : hi);
+      const int w = (base >> 5) + lane;
+      if (part && w < ring_words) atomicOr(&row[w], part);
+    }
+  } else if (hit) {
+    atomicOr(&row[pos >> 5], 1u << (pos & 31));
+  }
 }
 
 // ---------------------------------------------------------------- attend
@@ -336,6 +382,8 @@ __global__ __launch_bounds__(WG) void corm_attend_kernel(const Params p) {
   const int unit = blockIdx.y;
   const UnitLen ul = unit_len(p, unit);
   const int L = ul.L;
+  // (boolean message) the row of this step is cleared here, one launch before the record kernel sets bits
+  if (split == 0) clear_bit_rows(p, unit / p.Hkv, (unit % p.Hkv) * G, G, WG);
   if (split * CHUNK >= L) return;   // no live key in this split
 
   const int b = unit / p.Hkv;
@@ -597,6 +645,7 @@ __global__ __launch_bounds__(WG) void corm_attend_gqa_kernel(const Params p) {
   const int unit = blockIdx.y;
   const UnitLen ul = unit_len(p, unit);
   const int L = ul.L;
+  if (split == 0) clear_bit_rows(p, unit / p.Hkv, (unit % p.Hkv) * G, G, WG);
   if (split * CHUNK >= L) return;
 
   const int b = unit / p.Hkv;
@@ -792,6 +841,7 @@ __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, cons
   int32_t* lhb = p.last_hit + (size_t)unit * p.Lcap;
   const int tcur = p.t[b];
 
+  clear_bit_rows(p, b, hq0, G, UNIT_WG);   // (ordered before the record phase by the barriers of the merge)
   if (L == 0) {   // empty unit: out = 0, nothing to record
     for (int idx = tid; idx < G * D; idx += UNIT_WG) p.out[(size_t)(b * p.Hq + hq0) * D + idx] = 0.f;
     return;
@@ -940,12 +990,52 @@ __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, cons
   const bool full = p.do_evict && step_ok && (tcur - tfirst + 1 >= p.w);
   uint8_t* keepb = p.keep ? p.keep + (size_t)unit * p.Lcap : nullptr;
   unsigned long long* bitsb = p.keepbits + (size_t)unit * p.kb_stride;
+  // Boolean message (score_dtype CORM_BIT): a plain loop of its own, so that the unrolled loop below
+  // keeps its register budget.  The fp32 score itself is compared; bits are set wave by wave.
+  if (p.ring_bits) {
+#pragma unroll 1
+    for (int tile = 0; tile < L; tile += UNIT_WG) {
+      const int i = tile + tid;
+      const bool live = i < L && (!LAZY || ((sh_live[i >> 6] >> (i & 63)) & 1ull));
+      const int my_pos = posb[min(i, L - 1)];
+      int lh = lhb[min(i, L - 1)];
+      const bool pos_ok = live && my_pos >= 0 && my_pos < p.Tcap;
+      if (live && !pos_ok && p.status) atomicOr(p.status, CORM_DEV_BAD_STEP);
+      bool hit = false;
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float sc = live ? fast_exp2(sh_logit[g * lstride + i] - sh_M[g]) / sh_Z[g] : 0.f;
+        const bool hg = live && sc >= thr;
+        hit |= hg;
+        if (p.ring && step_ok)
+          record_bits(reinterpret_cast<uint32_t*>(p.ring) + ((size_t)(b * p.Hq + hq0 + g) * p.w + slot) * p.ring_words,
+                      p.ring_words, my_pos, pos_ok, hg && pos_ok);
+      }
+      bool keep = false;
+      if (live) {
+        if (hit && step_ok) {
+          lh = tcur;
+          lhb[i] = tcur;
+        }
+        const bool recent = LAZY ? (my_pos >= tcur - p.r) : (i >= L - p.r);
+        keep = !full || (lh > tcur - p.w) || recent;
+      }
+      if (p.do_evict && keepb && i < L) keepb[i] = keep ? 1 : 0;
+      if (p.do_evict) {
+        const unsigned long long bal = __ballot(keep);
+        if (lane == 0 && tile + wv * 64 < L) {
+          bitsb[(tile >> 6) + wv] = bal;
+          atomicAdd(&sh_tilecnt[tile / CHUNK], __popcll(bal));
+        }
+      }
+    }
+  }
   // (fully unrolled up to the largest tile count the LDS budget allows: straight-line code keeps the
   // wait counts exact, so a tile's stores are never waited for before the next tile starts)
 #pragma unroll
   for (int kt = 0; kt < UNIT_MAX_TILES; ++kt) {
     const int tile = kt * UNIT_WG;
-    if (tile >= L) break;
+    if (tile >= L || p.ring_bits) break;
     const int i = tile + tid;
     // (lazy mode: a slot whose key was evicted earlier takes no part: nothing recorded, stays dead)
     const bool live = i < L && (!LAZY || ((sh_live[i >> 6] >> (i & 63)) & 1ull));
@@ -1111,7 +1201,29 @@ __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const i
     const int i = rbeg + k * WG + tid;
     const bool live = i < rend && my_live[k];
     bool keep = false;
-    if (live) {
+    if (p.ring_bits) {   // (uniform) boolean message: compare the fp32 score, set bits wave by wave
+      const bool pos_ok = live && my_pos[k] >= 0 && my_pos[k] < p.Tcap;
+      if (live && !pos_ok && p.status) atomicOr(p.status, CORM_DEV_BAD_STEP);
+      bool hit = false;
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float sc = live ? exp2f(lg[k][g] - sh_M[g]) / sh_Z[g] : 0.f;
+        const bool hg = live && sc >= thr;
+        hit |= hg;
+        if (p.ring && step_ok)
+          record_bits(reinterpret_cast<uint32_t*>(p.ring) + ((size_t)(b * p.Hq + hq0 + g) * p.w + slot) * p.ring_words,
+                      p.ring_words, my_pos[k], pos_ok, hg && pos_ok);
+      }
+      if (live) {
+        int lh = my_lh[k];
+        if (hit && step_ok) {
+          lh = tcur;
+          lhb[i] = tcur;
+        }
+        const bool recent = p.lazy ? (my_pos[k] >= tcur - p.r) : (i >= L - p.r);
+        keep = !full || (lh > tcur - p.w) || recent;
+      }
+    } else if (live) {
       const bool pos_ok = my_pos[k] >= 0 && my_pos[k] < p.Tcap;
       if (!pos_ok && p.status) atomicOr(p.status, CORM_DEV_BAD_STEP);
       bool hit = false;
@@ -1933,7 +2045,7 @@ __global__ __launch_bounds__(64) void corm_append_kernel(char* K, char* V, int32
 }
 
 // literal windowed OR over the ring (Def. 4.1 + recent r + group rule)
-__global__ __launch_bounds__(WG) void corm_evict_mask_kernel(const void* ring, int ring_bf16, const int32_t* lens,
+__global__ __launch_bounds__(WG) void corm_evict_mask_kernel(const void* ring, int ring_mode, const int32_t* lens,
                                                              const int32_t* pos, const int32_t* t,
                                                              const int32_t* t_first, uint8_t* keep, int Hq, int Hkv,
                                                              int Lcap, int Tcap, int w, int r, float c) {
@@ -1957,10 +2069,17 @@ __global__ __launch_bounds__(WG) void corm_evict_mask_kernel(const void* ring, i
       const float thr = importance_threshold(c, tau);
       const int slot = (tau - 1) % w;
       for (int g = 0; g < G; ++g) {
-        size_t ri = ((size_t)(b * Hq + hkv * G + g) * w + slot) * Tcap + (size_t)pi;
-        float v = ring_bf16 ? __uint_as_float((uint32_t) reinterpret_cast<const uint16_t*>(ring)[ri] << 16)
-                            : reinterpret_cast<const float*>(ring)[ri];
-        k |= (v >= thr);
+        const size_t row = (size_t)(b * Hq + hkv * G + g) * w + slot;
+        if (ring_mode == CORM_BIT) {   // the recorded boolean itself
+          const uint32_t word = reinterpret_cast<const uint32_t*>(ring)[row * ((Tcap + 31) >> 5) + (size_t)(pi >> 5)];
+          k |= ((word >> (pi & 31)) & 1u) != 0;
+        } else {
+          const size_t ri = row * Tcap + (size_t)pi;
+          const float v = ring_mode == CORM_BF16
+                              ? __uint_as_float((uint32_t) reinterpret_cast<const uint16_t*>(ring)[ri] << 16)
+                              : reinterpret_cast<const float*>(ring)[ri];
+          k |= (v >= thr);
+        }
       }
     }
   }
@@ -2037,7 +2156,7 @@ int validate_desc(const corm_desc* d) {
   if (d->B * d->Hkv > 65535) return CORM_EUNSUPPORTED;  // grid.y limit
   if ((long long)d->Lcap * 512 >= (1LL << 31)) return CORM_EUNSUPPORTED;  // byte offsets inside a unit are 32-bit
   if (d->kv_dtype != CORM_F32 && d->kv_dtype != CORM_BF16) return CORM_EUNSUPPORTED;
-  if (d->score_dtype != CORM_F32 && d->score_dtype != CORM_BF16) return CORM_EUNSUPPORTED;
+  if (d->score_dtype != CORM_F32 && d->score_dtype != CORM_BF16 && d->score_dtype != CORM_BIT) return CORM_EUNSUPPORTED;
   if (d->d != 64 && d->d != 128) return CORM_EUNSUPPORTED;
   const int G = d->Hq / d->Hkv;
   if (G != 1 && G != 2 && G != 4 && G != 8) return CORM_EUNSUPPORTED;
@@ -2073,6 +2192,8 @@ void bind_params(const corm_desc* d, const WorkspaceLayout& wl, void* workspace,
   const float sm = d->sm_scale > 0.f ? d->sm_scale : 1.0f / sqrtf((float)d->d);
   p.scale_log2 = sm * LOG2E;
   p.ring_bf16 = d->score_dtype == CORM_BF16;
+  p.ring_bits = d->score_dtype == CORM_BIT;
+  p.ring_words = (d->Tcap + 31) / 32;
 }
 
 // 0 = choose by shape, 1 = split kernels (attend + record), 2 = fused unit kernel,
@@ -2380,7 +2501,7 @@ int corm_evict_mask(const corm_desc* desc, const void* score_ring, const int32_t
     return CORM_EINVAL;
   dim3 grid((desc->Lcap + WG - 1) / WG, desc->B * desc->Hkv);
   hipLaunchKernelGGL(corm_evict_mask_kernel, grid, dim3(WG), 0, (hipStream_t)stream, score_ring,
-                     (int)(desc->score_dtype == CORM_BF16), lens, pos, t, t_first, keep, desc->Hq, desc->Hkv,
+                     (int)desc->score_dtype, lens, pos, t, t_first, keep, desc->Hq, desc->Hkv,
                      desc->Lcap, desc->Tcap, desc->w, desc->r, desc->thr_scale);
   return launch_status();
 }
@@ -2504,6 +2625,7 @@ int corm_prefill_seed(const corm_desc* desc, const void* q_tail, int32_t m, void
       misaligned4(kept_idx) || misaligned4(status))
     return CORM_EINVAL;
   if (m < 1 || m > desc->w) return CORM_EINVAL;
+  if (desc->score_dtype == CORM_BIT && score_ring) return CORM_EUNSUPPORTED;
   WorkspaceLayout wl;
   rc = check_workspace(desc, workspace, workspace_bytes, &wl);
   if (rc) return rc;

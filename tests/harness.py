@@ -30,12 +30,39 @@ def out_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
 
 
 def make_state(wl: inputs.Workload, device, Lcap=None, Tcap=None, thr_scale=1.0, want_masks=True,
-               workspace=None) -> corm.LayerState:
+               workspace=None, score_dtype=None) -> corm.LayerState:
     n_replay = min(wl.w, wl.P)
     Lcap = wl.P + wl.D if Lcap is None else Lcap
     Tcap = wl.P + wl.D if Tcap is None else Tcap
     return corm.LayerState(wl.B, wl.Hq, wl.Hkv, wl.d, Lcap, Tcap, wl.w, wl.r, wl.dtype, thr_scale=thr_scale,
-                           device=device, workspace=workspace, want_masks=want_masks)
+                           device=device, workspace=workspace, want_masks=want_masks, score_dtype=score_dtype)
+
+
+def ring_row(st: corm.LayerState, b: int, slot: int) -> np.ndarray:
+    """Row `slot` of sequence b's ring as float32 [Hq, Tcap].  A bit ring (the boolean message) reads as
+    1.0 / 0.0, which the oracle's threshold test maps back to the recorded boolean for any threshold in (0, 1]."""
+    if st.ring_bits:
+        words = st.ring[b, :, slot].cpu().numpy().view(np.uint32)
+        bits = np.unpackbits(np.ascontiguousarray(words).view(np.uint8), axis=1, bitorder="little")
+        return bits[:, :st.Tcap].astype(np.float32)
+    return _f32(st.ring[b, :, slot])
+
+
+def check_recorded(wl, st, recorded_g, alpha_g, t, thr_scale, where) -> float:
+    """The row the device recorded for one head against the oracle's fp64 scores: within tolerance for a score
+    ring; for a bit ring, equal to the oracle's own threshold test except within rounding of the threshold.
+    Returns error / bound (score ring) or 0."""
+    a = alpha_g
+    if st.ring_bits:
+        thr = float(O.importance_threshold(t, thr_scale))
+        own = a >= thr
+        differ = own != (recorded_g > 0.5)
+        assert (np.abs(a[differ] - thr) <= 1e-4 * thr).all(), ("recorded bit", where)
+        return 0.0
+    err = np.abs(recorded_g.astype(np.float64) - a)
+    bound = SCORE_RTOL[wl.dtype] * a + SCORE_ATOL_OF_MAX[wl.dtype] * a.max()
+    assert (err <= bound).all(), ("recorded score", where, float((err / bound).max()))
+    return float((err / bound).max())
 
 
 def step_inputs(wl: inputs.Workload, x: Dict[str, torch.Tensor], j: int, n_replay: int):
@@ -99,7 +126,8 @@ def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_sca
                           units: Optional[Sequence[Tuple[int, int]]] = None, steps: Optional[int] = None,
                           use_split_calls=False, seq_offsets: Optional[Sequence[int]] = None,
                           Lcap: Optional[int] = None, Tcap: Optional[int] = None,
-                          lazy: Optional[Tuple[int, int]] = None, seed_kernel: bool = False) -> Dict:
+                          lazy: Optional[Tuple[int, int]] = None, seed_kernel: bool = False,
+                          score_dtype: Optional[str] = None) -> Dict:
     """Run replay + decode on the device, slaving one oracle per checked unit.  Returns a report.
 
     seq_offsets[b]: sequence b behaves as if o_b tokens preceded its prompt (their keys already evicted):
@@ -119,7 +147,7 @@ def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_sca
     offs = np.zeros(wl.B, dtype=np.int64) if seq_offsets is None else np.asarray(seq_offsets, dtype=np.int64)
     offs_dev = torch.from_numpy(offs).to(device=device, dtype=torch.int32)
     st = make_state(wl, device, thr_scale=thr_scale, Lcap=Lcap,
-                    Tcap=(wl.P + wl.D + int(offs.max())) if Tcap is None else Tcap)
+                    Tcap=(wl.P + wl.D + int(offs.max())) if Tcap is None else Tcap, score_dtype=score_dtype)
     G = wl.G
     pre = wl.P - n_replay
     n_pre = wl.P if seed_kernel else pre
@@ -179,7 +207,7 @@ def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_sca
             u = oracles[(b, h)]
             tb = t + int(offs[b])
             if b not in ring_rows:
-                ring_rows[b] = _f32(ring_all[b, :, (tb - 1) % wl.w])          # [Hq, Tcap]
+                ring_rows[b] = ring_row(st, b, (tb - 1) % wl.w)              # [Hq, Tcap]
             live_pos = np.concatenate([u.positions, [tb - 1]])
             recorded = ring_rows[b][h * G:(h + 1) * G][:, live_pos]
             res = u.step(qc[b, h * G:(h + 1) * G], kc[b, h], vc[b, h], tb, recorded=recorded)
@@ -207,12 +235,9 @@ def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_sca
                 e = out_rel_err(out[b, h * G + g].astype(np.float64), res["out"][g])
                 worst_out = max(worst_out, e)
                 assert e <= tol, ("out", j, b, h, g, e)
-                a = res["alpha"][g]
-                err = np.abs(recorded[g].astype(np.float64) - a)
-                bound = SCORE_RTOL[wl.dtype] * a + SCORE_ATOL_OF_MAX[wl.dtype] * a.max()
-                worst_score = max(worst_score, float((err / bound).max()))
-                assert (err <= bound).all(), ("recorded score", j, b, h, g, float((err / bound).max()))
-            own = O.important(O.round_to_storage(res["alpha"], wl.dtype), tb, thr_scale)
+                worst_score = max(worst_score, check_recorded(wl, st, recorded[g], res["alpha"][g], tb, thr_scale,
+                                                              (j, b, h, g)))
+            own = O.important(O.round_to_storage(res["alpha"], "f32" if st.ring_bits else wl.dtype), tb, thr_scale)
             flips += int((own != O.important(recorded, tb, thr_scale)).sum())
             if check_state_every and ((j + 1) % check_state_every == 0 or j == n_steps - 1):
                 check_unit_state(st, b, h, u, tb, lazy=lazy is not None)

@@ -301,6 +301,31 @@ def test_summary_only_state_equals_the_ring_state(name, mode):
     assert int(a.status.item()) == 0 and int(b.status.item()) == 0
 
 
+# the boolean message (score_dtype "bit"): the ring holds what Algorithm 1 itself keeps
+BITS = ["tiny_f32", "bf16_mha", "bf16_gqa4", "bf16_gqa8", "r_lt_w", "structured"]
+
+
+@pytest.mark.parametrize("name", BITS)
+def test_bit_ring_trajectory(name):
+    """A bit per (recorded query, key position) instead of a score: the slaved oracle takes the recorded
+    booleans as its message; every recorded bit must equal the oracle's own threshold test except within
+    rounding of the threshold; decisions, indices and caches bit for bit as always."""
+    wl, every = TRAJ[name]
+    say("bit ring", name, wl)
+    rep = harness.run_slaved_trajectory(wl, DEV, check_state_every=every, score_dtype="bit")
+    say("report", name, {k: v for k, v in rep.items() if k != "final_lens"})
+    assert rep["evicted_total"] > 0
+
+
+def test_bit_ring_split_calls_and_lazy():
+    """The literal mask (corm_evict_mask) reads the bits; deferred compaction and ragged steps work on a bit ring."""
+    wl = W["tiny_f32"].replace(B=3, P=300, D=40, w=32, r=8)
+    harness.run_slaved_trajectory(wl, DEV, check_state_every=2, use_split_calls=True, score_dtype="bit")
+    harness.run_slaved_trajectory(wl, DEV, check_state_every=2, seq_offsets=[0, 7, 1000], score_dtype="bit")
+    rep = harness.run_slaved_trajectory(TRAJ["bf16_mha"][0], DEV, check_state_every=6, lazy=(1, 8), score_dtype="bit")
+    assert rep["compactions"] > 0
+
+
 def test_split_calls_equal_the_fused_step():
     """append + decode_attend + evict_mask (literal, also == summary) + compact: the same bits
     as the fused step, checked against the same oracle."""
