@@ -47,6 +47,9 @@ def parse():
     ap.add_argument("--seed", default="kernel", choices=["kernel", "replay"],
                     help="how the prompt fills the recent-query window before decoding (untimed set-up): one "
                          "corm_prefill_seed call per layer, or its last w tokens replayed through corm_decode_step")
+    ap.add_argument("--ring", default="scores", choices=["scores", "bits"],
+                    help="what the ring records: the queries' probabilities in the KV dtype (default), or the boolean "
+                         "message of Algorithm 1, one bit per recorded query and key position")
     ap.add_argument("--no-ring", action="store_true",
                     help="summary-only state: no score ring is allocated or written (score_ring = NULL); decisions "
                          "come from last_hit alone and are bit-identical")
@@ -121,7 +124,8 @@ def main():
 
     # ---------------- set-up (untimed): allocate, generate, feed the prompt
     t0 = time.time()
-    desc = corm.make_desc(B, Hq, Hkv, d, Lcap, Tcap, wl.w, wl.r, wl.dtype)
+    score_dtype = "bit" if args.ring == "bits" else None
+    desc = corm.make_desc(B, Hq, Hkv, d, Lcap, Tcap, wl.w, wl.r, wl.dtype, score_dtype=score_dtype)
     ws = torch.empty(corm.corm_workspace_bytes(desc), dtype=torch.uint8, device=dev)
     corm.corm_workspace_init(desc, ws)
     lens_all = torch.zeros(layers, B, Hkv, dtype=torch.int32, device=dev)
@@ -133,7 +137,7 @@ def main():
     t_first = torch.full((B,), pre + 1, dtype=torch.int32, device=dev)
     for l in range(layers):
         st = corm.LayerState(B, Hq, Hkv, d, Lcap, Tcap, wl.w, wl.r, wl.dtype, device=dev, workspace=ws,
-                             want_ring=not args.no_ring)
+                             want_ring=not args.no_ring, score_dtype=score_dtype)
         st.lens = lens_all[l]
         st.nlive = nlive_all[l]
         x = inputs.make_layer(wl, l, device=dev, n_decode=n_dec, n_replay=n_replay)
@@ -217,7 +221,8 @@ def main():
         seeding = {"how": "corm_prefill_seed, one call per layer (layout copy of the queries included)",
                    "median_ms_per_layer": ms[len(ms) // 2],
                    "algorithmic_tflops": 2.0 * d * pairs * B * Hq / (ms[len(ms) // 2] * 1e-3) / 1e12,
-                   "ring_gb_written_per_layer": 0.0 if args.no_ring else pairs * B * Hq * esz / 1e9}
+                   "ring_gb_written_per_layer": 0.0 if args.no_ring else
+                   pairs * B * Hq * (0.125 if args.ring == "bits" else esz) / 1e9}
     else:
         for j in range(n_replay):          # prompt tail: seeds the recent-query window; bulk eviction at its end
             run_step(j)
@@ -268,7 +273,7 @@ def main():
 
     ms_per_step = ms_total / K_steps
     n_launch = K_steps * layers
-    ssz = 0 if args.no_ring else esz
+    ssz = 0 if args.no_ring else (0.125 if args.ring == "bits" else esz)   # ring bytes per key and head
     # the whole step (every launch of every layer) against its algorithmic bytes
     total_bytes = sum(algorithmic_bytes(lens_hist[k], wl, esz, ssz) for k in range(K_steps))
     step_gbs = total_bytes / (ms_total * 1e-3) / 1e9
@@ -310,7 +315,8 @@ def main():
         "config": {"workload": wl.name + ("+structured_queries" if args.structured else ""),
                    "layers": layers, "batch": B, "q_heads": Hq, "kv_heads": Hkv, "head_dim": d,
                    "prompt": wl.P, "w": wl.w, "r": wl.r, "tokens_per_step": B, "streams": args.streams, "path": corm.corm_selected_path(desc),
-                   "score_ring": "none (summary-only state)" if args.no_ring else f"{wl.dtype} probabilities",
+                   "score_ring": "none (summary-only state)" if args.no_ring else
+                   ("boolean message, 1 bit per entry" if args.ring == "bits" else f"{wl.dtype} probabilities"),
                    "compaction": f"deferred until {lazy[0]}/{lazy[1]} of a unit's slots are dead" if lazy
                    else "at every step",
                    "live_fraction_end": live_end, "keys_evicted_in_timed_region": evicted},

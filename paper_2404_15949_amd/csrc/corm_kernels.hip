@@ -119,6 +119,13 @@ __device__ __forceinline__ float rows_allreduce_sum(float v) {
   return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
+__device__ __forceinline__ uint32_t rows_allreduce_or(uint32_t u) {
+  const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+  const uint32_t w = a[0] | a[1];
+  const auto b = __builtin_amdgcn_permlane32_swap(w, w, false, false);
+  return b[0] | b[1];
+}
+
 struct F32 {
   static constexpr int EPL = 4;  // elements per 16-byte lane slice
   static constexpr int ESZ = 4;
@@ -1596,6 +1603,7 @@ struct PrefillArgs {
   float4* stats;   // [B*Hq, w]       (max, 1/sum, threshold of the query's step, unused)
   int32_t* status;
   int32_t Hq, Hkv, Lcap, Tcap, w, m, nkb, ring_bf16;
+  int32_t ring_bits, ring_words;   // boolean message: one bit per (row, position), words per row
   float thr_scale, scale_log2;
 };
 
@@ -1689,7 +1697,7 @@ struct PrefillGeom {
   static_assert(QBLK * ROWB % (WG * 16) == 0 && QBLK <= WG, "a block is loaded in whole passes of the workgroup");
 };
 
-template <typename DT, int D, int PASS>
+template <typename DT, int D, int PASS, bool BITS>
 __global__ __launch_bounds__(WG) void corm_prefill_kernel(const PrefillArgs a) {
   constexpr int ROWB = D * DT::ESZ;
   using Geo = PrefillGeom<ROWB>;
@@ -1754,7 +1762,7 @@ __global__ __launch_bounds__(WG) void corm_prefill_kernel(const PrefillArgs a) {
   __shared__ __attribute__((aligned(16))) uint16_t sh_t[PASS == 2 ? WAVES : 1][PASS == 2 ? 16 : 1][TROW];
   // ... possible when the wave's 64 slots hold consecutive positions starting at a multiple of 8 (and rows
   // of the ring start at multiples of 8 elements), for query tiles that see all of them
-  bool wave_rows = false;
+  bool wave_rows = false, wave_bitrows = false;
   // every slot of the wave holds a key (then pos_wlast is the largest position among them)
   const bool wave_whole = wkey0 + T * 16 <= L;
   const int pos_w0 = __shfl(kp[0][0], 0);
@@ -1764,6 +1772,8 @@ __global__ __launch_bounds__(WG) void corm_prefill_kernel(const PrefillArgs a) {
 #pragma unroll
     for (int tl = 0; tl < T; ++tl) ok = ok && quad[tl] && kp[tl][0] == pos_w0 + tl * 16 + 4 * lg;
     wave_rows = __all(ok) && a.ring_bf16 && (pos_w0 & 7) == 0 && (a.Tcap & 7) == 0;
+    // boolean message: the wave's 64 consecutive positions are exactly two words of a row
+    wave_bitrows = BITS && __all(ok) && (pos_w0 & 31) == 0;
   }
   int hm[T][4];   // pass 2: latest step at which one of the group's queries found the key important
 #pragma unroll
@@ -1853,7 +1863,37 @@ __global__ __launch_bounds__(WG) void corm_prefill_kernel(const PrefillArgs a) {
           if (slot >= a.w) slot -= a.w;
           const size_t rowbase = ((size_t)head * a.w + (size_t)(j < a.m ? slot : 0)) * a.Tcap;
           const bool rows_now = wave_rows && all_seen;
-          if (a.ring_bf16) {
+          if (BITS) {
+            // boolean message: the fp32 score itself is compared; bit tl*16 + 4*lg + r of the wave's 64 positions
+            uint32_t hbits = 0u;
+#pragma unroll
+            for (int tl = 0; tl < T; ++tl)
+#pragma unroll
+              for (int r = 0; r < 4; ++r) {
+                const float e = fast_exp2(fmaf(d[tl][r], a.scale_log2, -st.x)) * st.y;
+                const bool hit = kp[tl][r] <= vis && e >= thr;
+                hmg[tl][r] = hit ? tau : hmg[tl][r];
+                hbits |= (uint32_t)hit << (tl * 4 + r);
+              }
+            if (a.ring) {
+              uint32_t* roww = reinterpret_cast<uint32_t*>(a.ring) +
+                               ((size_t)head * a.w + (size_t)(j < a.m ? slot : 0)) * a.ring_words;
+              if (wave_bitrows) {   // (uniform) the wave owns two whole words of every query's row: plain stores
+                uint32_t w0 = (((hbits >> 0) & 0xfu) << (4 * lg)) | (((hbits >> 4) & 0xfu) << (16 + 4 * lg));
+                uint32_t w1 = 0u;
+                if (T == 4) w1 = (((hbits >> 8) & 0xfu) << (4 * lg)) | (((hbits >> 12) & 0xfu) << (16 + 4 * lg));
+                w0 = rows_allreduce_or(w0);
+                w1 = rows_allreduce_or(w1);
+                if (j < a.m && lg < 2) roww[(pos_w0 >> 5) + lg] = lg == 0 ? w0 : w1;
+              } else {              // rows were cleared by the launch before: set single bits
+#pragma unroll
+                for (int tl = 0; tl < T; ++tl)
+#pragma unroll
+                  for (int r = 0; r < 4; ++r)
+                    if ((hbits >> (tl * 4 + r)) & 1u) atomicOr(&roww[kp[tl][r] >> 5], 1u << (kp[tl][r] & 31));
+              }
+            }
+          } else if (a.ring_bf16) {
             uint32_t pk[T][2];   // stored scores, two bf16 per word
             if (all_seen) prefill_scores_bf16<false, T>(d, kp, vis, a.scale_log2, st, thr, tau, pk, hmg);
             else prefill_scores_bf16<true, T>(d, kp, vis, a.scale_log2, st, thr, tau, pk, hmg);
@@ -1949,6 +1989,25 @@ __global__ __launch_bounds__(WG) void corm_prefill_kernel(const PrefillArgs a) {
         const int key = wkey0 + tl * 16 + 4 * lg + r;
         if (n == 0 && key < L && v > lhb[key]) lhb[key] = v;
       }
+  }
+}
+
+// boolean message: zero the words of the rows of steps tau_0 .. tau_{m-1} that pass 2 may set bits in
+// (positions < tau); workgroup = 16 rows of one head
+__global__ __launch_bounds__(256) void corm_prefill_clear_bits_kernel(const PrefillArgs a) {
+  const int head = blockIdx.y;
+  const int tcur = a.t[head / a.Hq];
+  const int tau0 = tcur - a.m + 1;
+  if (tau0 < 1 || tcur > a.Tcap) return;
+  const int s0 = (tau0 - 1) % a.w;
+  for (int jr = 0; jr < 16; ++jr) {
+    const int j = blockIdx.x * 16 + jr;
+    if (j >= a.m) break;
+    int slot = s0 + j;
+    if (slot >= a.w) slot -= a.w;
+    uint32_t* row = reinterpret_cast<uint32_t*>(a.ring) + ((size_t)head * a.w + slot) * a.ring_words;
+    const int nw = min((tau0 + j + 31) >> 5, a.ring_words);
+    for (int i = threadIdx.x; i < nw; i += 256) row[i] = 0u;
   }
 }
 
@@ -2397,9 +2456,10 @@ int launch_compact(const corm_desc* d, const WorkspaceLayout& wl, void* workspac
 
 template <typename DT, int D>
 int launch_prefill_dt(const PrefillArgs& a, dim3 grid, dim3 mgrid, int KB, hipStream_t s) {
-  hipLaunchKernelGGL((corm_prefill_kernel<DT, D, 1>), grid, dim3(WG), 0, s, a);
+  hipLaunchKernelGGL((corm_prefill_kernel<DT, D, 1, false>), grid, dim3(WG), 0, s, a);
   hipLaunchKernelGGL(corm_prefill_merge_kernel, mgrid, dim3(256), 0, s, a, KB);
-  hipLaunchKernelGGL((corm_prefill_kernel<DT, D, 2>), grid, dim3(WG), 0, s, a);
+  if (a.ring_bits) hipLaunchKernelGGL((corm_prefill_kernel<DT, D, 2, true>), grid, dim3(WG), 0, s, a);
+  else hipLaunchKernelGGL((corm_prefill_kernel<DT, D, 2, false>), grid, dim3(WG), 0, s, a);
   return launch_status();
 }
 
@@ -2625,7 +2685,6 @@ int corm_prefill_seed(const corm_desc* desc, const void* q_tail, int32_t m, void
       misaligned4(kept_idx) || misaligned4(status))
     return CORM_EINVAL;
   if (m < 1 || m > desc->w) return CORM_EINVAL;
-  if (desc->score_dtype == CORM_BIT && score_ring) return CORM_EUNSUPPORTED;
   WorkspaceLayout wl;
   rc = check_workspace(desc, workspace, workspace_bytes, &wl);
   if (rc) return rc;
@@ -2638,10 +2697,15 @@ int corm_prefill_seed(const corm_desc* desc, const void* q_tail, int32_t m, void
   a.status = status;
   a.Hq = desc->Hq; a.Hkv = desc->Hkv; a.Lcap = desc->Lcap; a.Tcap = desc->Tcap; a.w = desc->w; a.m = m;
   a.nkb = wl.seed_nkb; a.ring_bf16 = desc->score_dtype == CORM_BF16;
+  a.ring_bits = desc->score_dtype == CORM_BIT; a.ring_words = (desc->Tcap + 31) / 32;
   a.thr_scale = desc->thr_scale;
   a.scale_log2 = (desc->sm_scale > 0.f ? desc->sm_scale : 1.0f / sqrtf((float)desc->d)) * LOG2E;
   const int units = desc->B * desc->Hkv;
   const dim3 grid(wl.seed_nkb, units), mgrid((m + 255) / 256, desc->B * desc->Hq);
+  if (a.ring_bits && score_ring) {
+    hipLaunchKernelGGL(corm_prefill_clear_bits_kernel, dim3((m + 15) / 16, desc->B * desc->Hq), dim3(256), 0, s, a);
+    if (launch_status()) return CORM_EHIP;
+  }
   if (desc->kv_dtype == CORM_F32)
     rc = desc->d == 64 ? launch_prefill_dt<F32, 64>(a, grid, mgrid, wl.seed_kb, s)
                        : launch_prefill_dt<F32, 128>(a, grid, mgrid, wl.seed_kb, s);

@@ -264,7 +264,7 @@ def _seed_with_kernel(wl, st, x, x_cpu, oracles, units, offs, offs_dev, n_replay
     for (b, h) in units:
         u = oracles[(b, h)]
         if b not in ring_b:
-            ring_b[b] = _f32(st.ring[b])                                          # [Hq, w, Tcap]
+            ring_b[b] = np.stack([ring_row(st, b, sl) for sl in range(wl.w)], axis=1)   # [Hq, w, Tcap]
         res = None
         for j in range(n_replay):
             p = wl.P - n_replay + j
@@ -274,11 +274,8 @@ def _seed_with_kernel(wl, st, x, x_cpu, oracles, units, offs, offs_dev, n_replay
             res = u.step(_f32(x_cpu["Q"][j, b, h * G:(h + 1) * G]), _f32(x_cpu["K0"][b, h, p]),
                          _f32(x_cpu["V0"][b, h, p]), tb, recorded=recorded)
             for g in range(G):
-                a = res["alpha"][g]
-                err = np.abs(recorded[g].astype(np.float64) - a)
-                bound = SCORE_RTOL[wl.dtype] * a + SCORE_ATOL_OF_MAX[wl.dtype] * a.max()
-                worst = max(worst, float((err / bound).max()))
-                assert (err <= bound).all(), ("seeded score", j, b, h, g, float((err / bound).max()))
+                worst = max(worst, check_recorded(wl, st, recorded[g], res["alpha"][g], tb, thr_scale,
+                                                  ("seeded", j, b, h, g)))
         assert np.array_equal(keep_d[b, h, :wl.P].astype(bool), res["keep"]), ("keep after seeding", b, h)
         assert int(st.lens[b, h].item()) == u.l, ("lens after seeding", b, h)
         assert np.array_equal(idx_d[b, h, :u.l].astype(np.int64), res["indices"]), ("kept_idx after seeding", b, h)

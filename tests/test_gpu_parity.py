@@ -317,6 +317,19 @@ def test_bit_ring_trajectory(name):
     assert rep["evicted_total"] > 0
 
 
+@pytest.mark.parametrize("name", ["tiny_f32", "bf16_mha", "bf16_gqa4", "bf16_d64", "f32_d128"])
+def test_bit_ring_prefill_seed(name):
+    """corm_prefill_seed writing the boolean message: whole words by plain stores where a wave's 64 positions
+    are two words of a row, single bits into cleared rows elsewhere (offset positions below)."""
+    wl, every = TRAJ[name]
+    rep = harness.run_slaved_trajectory(wl, DEV, check_state_every=every, seed_kernel=True, score_dtype="bit")
+    assert rep["evicted_total"] > 0
+    if name == "tiny_f32":
+        wl2 = W["tiny_f32"].replace(B=3, P=300, D=12, w=32, r=32)
+        harness.run_slaved_trajectory(wl2, DEV, check_state_every=4, seq_offsets=[0, 7, 1000], seed_kernel=True,
+                                      score_dtype="bit")
+
+
 def test_bit_ring_split_calls_and_lazy():
     """The literal mask (corm_evict_mask) reads the bits; deferred compaction and ragged steps work on a bit ring."""
     wl = W["tiny_f32"].replace(B=3, P=300, D=40, w=32, r=8)
