@@ -31,6 +31,7 @@ constexpr int WG = 256;          // threads per workgroup
 constexpr int WAVES = WG / 64;   // waves per workgroup
 constexpr int CHUNK = 512;       // keys per split
 constexpr int UNROLL = 4;        // 16-byte K loads (and V loads) per lane and pipeline stage
+constexpr int MAX_PARTS_PER_CHUNK = 4;   // split path: a chunk may be shared by up to 4 attend workgroups
 constexpr float LOG2E = 1.4426950408889634f;
 
 struct Params {
@@ -58,6 +59,8 @@ struct Params {
   int32_t do_append, do_evict, ring_bf16;
   int32_t ring_bits;    // the ring holds the boolean message: one bit per (row, position), 32 positions per word
   int32_t ring_words;   // words per ring row in that case: ceil(Tcap / 32)
+  int32_t part_keys;    // split path: keys per attend workgroup (CHUNK, or a fraction of it when the launch has few units)
+  int32_t npart;        // partials per head in the workspace: nsplit * (CHUNK / smallest part)
   int32_t kb_stride;    // 64-bit words per unit in keepbits
   int32_t lazy;         // lazy mode: keepbits are the caller's persistent live masks; dead slots are skipped
 };
@@ -391,7 +394,7 @@ __global__ __launch_bounds__(WG) void corm_attend_kernel(const Params p) {
   const int L = ul.L;
   // (boolean message) the row of this step is cleared here, one launch before the record kernel sets bits
   if (split == 0) clear_bit_rows(p, unit / p.Hkv, (unit % p.Hkv) * G, G, WG);
-  if (split * CHUNK >= L) return;   // no live key in this split
+  if (split * p.part_keys >= L) return;   // no live key in this part
 
   const int b = unit / p.Hkv;
   const int hkv = unit - b * p.Hkv;
@@ -408,12 +411,14 @@ __global__ __launch_bounds__(WG) void corm_attend_kernel(const Params p) {
   char* Kb = reinterpret_cast<char*>(p.K) + (size_t)unit * p.Lcap * ROWB;
   char* Vb = reinterpret_cast<char*>(p.V) + (size_t)unit * p.Lcap * ROWB;
   const int hq0 = hkv * G;
-  const int cbeg = split * CHUNK;
-  const int cend = min(cbeg + CHUNK, L);
+  // this workgroup's keys: a whole 512-key chunk, or (launches with few units) a fraction of one; the
+  // unrolled pipeline below simply ends early
+  const int cbeg = split * p.part_keys;
+  const int cend = min(cbeg + p.part_keys, L);
 
   // The append: the owner of the chunk that holds the new slot writes the row and its metadata into the
   // cache first; after the barrier every wave of this workgroup reads it back like any other row.
-  if (ul.appended && ul.L0 >= cbeg) {   // L0 = L-1 < cend: this workgroup owns the new slot
+  if (ul.appended && ul.L0 >= cbeg && ul.L0 < cend) {   // this workgroup owns the new slot
     if (wv == 0) {
       if (lane < LPR) {
         const char* knew = reinterpret_cast<const char*>(p.k_new) + (size_t)unit * ROWB;
@@ -431,7 +436,7 @@ __global__ __launch_bounds__(WG) void corm_attend_kernel(const Params p) {
     __syncthreads();
   }
 
-  if (LAZY) stage_live_masks(p, unit, ul, cbeg, CHUNK / 64, ul.appended && ul.L0 >= cbeg, sh_live);
+  if (LAZY) stage_live_masks(p, unit, ul, cbeg, CHUNK / 64, ul.appended && ul.L0 >= cbeg && ul.L0 < cend, sh_live);
 
   // this lane's slice of the G queries
   uint4 qreg[G];
@@ -534,7 +539,7 @@ __global__ __launch_bounds__(WG) void corm_attend_kernel(const Params p) {
       zt = fmaf(sh_z[g][i], a, zt);
       at = fmaf(sh_acc[g][i][c], a, at);
     }
-    float* part = p.partials + ((size_t)(b * p.Hq + hq0 + g) * p.nsplit + split) * PSTRIDE;
+    float* part = p.partials + ((size_t)(b * p.Hq + hq0 + g) * p.npart + split) * PSTRIDE;
     part[2 + c] = at;
     if (c == 0) {
       part[0] = mx;
@@ -653,7 +658,7 @@ __global__ __launch_bounds__(WG) void corm_attend_gqa_kernel(const Params p) {
   const UnitLen ul = unit_len(p, unit);
   const int L = ul.L;
   if (split == 0) clear_bit_rows(p, unit / p.Hkv, (unit % p.Hkv) * G, G, WG);
-  if (split * CHUNK >= L) return;
+  if (split * p.part_keys >= L) return;
 
   const int b = unit / p.Hkv;
   const int hkv = unit - b * p.Hkv;
@@ -672,10 +677,12 @@ __global__ __launch_bounds__(WG) void corm_attend_gqa_kernel(const Params p) {
   char* Kb = reinterpret_cast<char*>(p.K) + (size_t)unit * p.Lcap * ROWB;
   char* Vb = reinterpret_cast<char*>(p.V) + (size_t)unit * p.Lcap * ROWB;
   const int hq0 = hkv * G;
-  const int cbeg = split * CHUNK;
-  const int cend = min(cbeg + CHUNK, L);
+  // this workgroup's keys: a whole 512-key chunk, or (launches with few units) a fraction of one; the
+  // unrolled pipeline below simply ends early
+  const int cbeg = split * p.part_keys;
+  const int cend = min(cbeg + p.part_keys, L);
 
-  if (ul.appended && ul.L0 >= cbeg) {   // this workgroup owns the new slot: write it, then read it back
+  if (ul.appended && ul.L0 >= cbeg && ul.L0 < cend) {   // this workgroup owns the new slot: write it, then read it back
     if (wv == 0) {
       if (lane < LPR) {
         const char* knew = reinterpret_cast<const char*>(p.k_new) + (size_t)unit * ROWB;
@@ -693,7 +700,7 @@ __global__ __launch_bounds__(WG) void corm_attend_gqa_kernel(const Params p) {
     __syncthreads();
   }
 
-  if (LAZY) stage_live_masks(p, unit, ul, cbeg, CHUNK / 64, ul.appended && ul.L0 >= cbeg, sh_live);
+  if (LAZY) stage_live_masks(p, unit, ul, cbeg, CHUNK / 64, ul.appended && ul.L0 >= cbeg && ul.L0 < cend, sh_live);
 
   // B operand: column n < G holds query head n, elements 32*kb + 8*lg .. +8 in block kb
   uint4 qb[4];
@@ -786,7 +793,7 @@ __global__ __launch_bounds__(WG) void corm_attend_gqa_kernel(const Params p) {
       zt = fmaf(sh_z[g][i], a, zt);
       at = fmaf(sh_acc[g][i][c], a, at);
     }
-    float* part = p.partials + ((size_t)(b * p.Hq + hq0 + g) * p.nsplit + split) * PSTRIDE;
+    float* part = p.partials + ((size_t)(b * p.Hq + hq0 + g) * p.npart + split) * PSTRIDE;
     part[2 + c] = at;
     if (c == 0) {
       part[0] = mx;
@@ -1107,7 +1114,8 @@ __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const i
   const int L = ul.L;
   const int tid = threadIdx.x;
   if (rsplit == 0 && tid == 0 && ul.flags && p.status) atomicOr(p.status, ul.flags);
-  const int nlive = (L + CHUNK - 1) / CHUNK;                        // attend splits that hold keys
+  const int nlive = (L + CHUNK - 1) / CHUNK;                        // chunks that hold keys
+  const int nparts = (L + p.part_keys - 1) / p.part_keys;           // attend partials that hold keys
   const int nwg = max((L + RECORD_ROWS - 1) / RECORD_ROWS, 1);      // record workgroups that have work
   if (rsplit >= nwg) return;
 
@@ -1145,14 +1153,14 @@ __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const i
 
   // global max and sum of Eq. 2 from the split partials (wave g handles head g, g + WAVES, ...)
   for (int g = wv; g < G; g += WAVES) {
-    const float* part0 = p.partials + (size_t)(b * p.Hq + hq0 + g) * p.nsplit * PSTRIDE;
+    const float* part0 = p.partials + (size_t)(b * p.Hq + hq0 + g) * p.npart * PSTRIDE;
     float mx = neg_inf();
-    for (int s = lane; s < nlive; s += 64) mx = fmaxf(mx, part0[(size_t)s * PSTRIDE]);
+    for (int s = lane; s < nparts; s += 64) mx = fmaxf(mx, part0[(size_t)s * PSTRIDE]);
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
     const float ms = mx == neg_inf() ? 0.f : mx;
     float zt = 0.f;
-    for (int s = lane; s < nlive; s += 64) {
+    for (int s = lane; s < nparts; s += 64) {
       const float* ps = part0 + (size_t)s * PSTRIDE;
       zt = fmaf(ps[1], exp2f(ps[0] - ms), zt);
     }
@@ -1172,11 +1180,11 @@ __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const i
   const int cblocks = D / 64;
   for (int item = rsplit; item < G * cblocks; item += nwg) {   // (uniform over the workgroup)
     const int g = item / cblocks, c = (item - g * cblocks) * 64 + lane;
-    const float* part0 = p.partials + (size_t)(b * p.Hq + hq0 + g) * p.nsplit * PSTRIDE;
+    const float* part0 = p.partials + (size_t)(b * p.Hq + hq0 + g) * p.npart * PSTRIDE;
     const float ms = sh_M[g];
     float at = 0.f;
 #pragma unroll 4
-    for (int s = wv; s < nlive; s += WAVES) {
+    for (int s = wv; s < nparts; s += WAVES) {
       const float* ps = part0 + (size_t)s * PSTRIDE;
       at = fmaf(ps[2 + c], exp2f(ps[0] - ms), at);
     }
@@ -2193,7 +2201,7 @@ WorkspaceLayout workspace_layout(const corm_desc& d) {
   w.unit_len_off = align_up(units * w.nsplit * sizeof(int32_t), 256);
   w.keepbits_off = align_up(w.unit_len_off + units * sizeof(int32_t), 256);
   w.partials_off = align_up(w.keepbits_off + units * w.kb_stride * sizeof(unsigned long long), 256);
-  w.logits_off = align_up(w.partials_off + heads * w.nsplit * (d.d + 2) * sizeof(float), 256);
+  w.logits_off = align_up(w.partials_off + heads * w.nsplit * MAX_PARTS_PER_CHUNK * (d.d + 2) * sizeof(float), 256);
   w.stage_meta_off = align_up(w.logits_off + heads * d.Lcap * sizeof(float), 256);
   w.stage_k_off = align_up(w.stage_meta_off + stage_rows * 2 * sizeof(int32_t), 256);
   w.stage_v_off = align_up(w.stage_k_off + stage_rows * row_bytes(&d), 256);
@@ -2247,6 +2255,8 @@ void bind_params(const corm_desc* d, const WorkspaceLayout& wl, void* workspace,
   p.logits = reinterpret_cast<float*>(ws + wl.logits_off);
   p.B = d->B; p.Hq = d->Hq; p.Hkv = d->Hkv; p.Lcap = d->Lcap; p.Tcap = d->Tcap; p.w = d->w; p.r = d->r;
   p.nsplit = wl.nsplit;
+  p.npart = wl.nsplit * MAX_PARTS_PER_CHUNK;
+  p.part_keys = CHUNK;
   p.thr_scale = d->thr_scale;
   const float sm = d->sm_scale > 0.f ? d->sm_scale : 1.0f / sqrtf((float)d->d);
   p.scale_log2 = sm * LOG2E;
@@ -2294,7 +2304,7 @@ int launch_attend_dt(const corm_desc* d, const Params& p, int G, dim3 grid, hipS
 
 int launch_attend(const corm_desc* d, const Params& p, hipStream_t s) {
   const int G = d->Hq / d->Hkv;
-  const dim3 grid(p.nsplit, d->B * d->Hkv);
+  const dim3 grid((d->Lcap + p.part_keys - 1) / p.part_keys, d->B * d->Hkv);
   const hipEvent_t ev0 = g_prof_start, ev1 = g_prof_stop;
   g_prof_start = g_prof_stop = nullptr;
   if (ev0 && hipEventRecord(ev0, s) != hipSuccess) return CORM_EHIP;
@@ -2396,8 +2406,24 @@ int launch_record(const corm_desc* d, const Params& p, hipStream_t s) {
   return launch_record_rc<1>(d, p, s);
 }
 
-int launch_attend_record(const corm_desc* d, const Params& p, hipStream_t s) {
-  if (use_unit_path(d)) return launch_unit(d, p, s);
+// Keys per attend workgroup on the split path: a whole chunk, or a half / a quarter of one while the
+// launch would otherwise have fewer than about two workgroups per compute unit.  A part must hold whole
+// pairs of pipeline stages of the kernel that runs.
+int attend_part_keys(const corm_desc* d) {
+  const int G = d->Hq / d->Hkv;
+  const bool mfma = d->kv_dtype == CORM_BF16 && d->d == 128 && G > 1 && g_force_path != 3;
+  const int stage_rows = mfma ? WAVES * 16 : WAVES * (64 / (row_bytes(d) / 16)) * UNROLL;
+  const long want = 2L * (g_num_cus > 0 ? g_num_cus : 256);
+  const long wgs = (long)d->B * d->Hkv * ((d->Lcap + CHUNK - 1) / CHUNK);
+  int part = CHUNK;
+  while (part / 2 >= 2 * stage_rows && CHUNK / (part / 2) <= MAX_PARTS_PER_CHUNK && wgs * (CHUNK / part) < want) part /= 2;
+  return part;
+}
+
+int launch_attend_record(const corm_desc* d, const Params& p0, hipStream_t s) {
+  if (use_unit_path(d)) return launch_unit(d, p0, s);
+  Params p = p0;
+  p.part_keys = attend_part_keys(d);
   const int rc = launch_attend(d, p, s);
   if (rc) return rc;
   return launch_record(d, p, s);

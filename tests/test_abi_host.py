@@ -45,7 +45,7 @@ def test_workspace_size_formula():
     nsplit = (1024 + 511) // 512
     units, heads = 2 * 2, 2 * 8
     stage_rows = units * nsplit * 512
-    need = (units * nsplit * 4 + units * 4 + units * (1024 // 64) * 8 + heads * nsplit * 130 * 4 + heads * 1024 * 4
+    need = (units * nsplit * 4 + units * 4 + units * (1024 // 64) * 8 + heads * nsplit * 4 * 130 * 4 + heads * 1024 * 4
             + stage_rows * (8 + 2 * 256)
             + heads * (1024 // 256) * 16 * 8 + heads * 16 * 16)     # prompt seeding: partial and merged row statistics
     assert need <= n <= need + 10 * 256
