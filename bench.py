@@ -37,7 +37,7 @@ def parse():
     ap.add_argument("--layers", type=int, default=None, help="override the number of layers (development only)")
     ap.add_argument("--structured", action="store_true",
                     help="supplementary variant: per-head query means so that eviction happens at w >= 256")
-    ap.add_argument("--streams", type=int, default=2, choices=[1, 2, 3, 4],
+    ap.add_argument("--streams", type=int, default=3, choices=[1, 2, 3, 4],
                     help="layers are issued round-robin on this many streams (they are independent)")
     ap.add_argument("--path", type=int, default=0, choices=[0, 1, 2, 3],
                     help="corm_force_path: 0 by shape, 1 split kernels, 2 one workgroup per unit, 3 split without MFMA")
@@ -160,8 +160,8 @@ def main():
     log(f"allocated + generated {layers} layers in {time.time() - t0:.1f}s; "
         f"{torch.cuda.memory_allocated() / 2**30:.1f} GiB resident")
 
-    # Launch order of one step.  --streams 1: every layer's fused step call on one stream.  --streams 2:
-    # layers alternate between two streams, each with its own workspace.  Layers are independent and a
+    # Launch order of one step.  --streams 1: every layer's fused step call on one stream.  --streams N:
+    # layers are dealt round-robin to N streams, each with its own workspace.  Layers are independent and a
     # layer always runs on the same stream, so no event is needed; the device overlaps the tail of one
     # layer's launch (its record / compaction work, which moves few bytes) with the head of the next.
     main = torch.cuda.current_stream()
