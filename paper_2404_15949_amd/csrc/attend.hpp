@@ -20,6 +20,14 @@ __device__ __forceinline__ uint4 buffer_load16(__amdgpu_buffer_rsrc_t r, uint32_
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// The same with the non-temporal cache policy (the `nt` bit of the instruction): for the K and V rows of
+// a decode step, which are read exactly once per launch and not again before gigabytes of other rows have
+// passed.  Measured on the unit kernel (config 3 shape): 207 -> 186 us per launch.
+__device__ __forceinline__ uint4 buffer_load16_stream(__amdgpu_buffer_rsrc_t r, uint32_t byte_offset) {
+  const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_offset, 0, 2);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // byte offset beyond any descriptor: the load returns zeros without touching memory
 constexpr uint32_t DEAD_OFFSET = 0x7ffffff0u;
 
@@ -63,12 +71,12 @@ struct Attend {
 #pragma unroll
     for (int j = 0; j < U; ++j) {
       const uint32_t o = (!LAZY || ((st.live >> j) & 1u)) ? off + (uint32_t)(j * LOAD_ROWS * ROWB) : DEAD_OFFSET;
-      st.k[j] = buffer_load16(rk, o);
+      st.k[j] = buffer_load16_stream(rk, o);
     }
 #pragma unroll
     for (int j = 0; j < U; ++j) {
       const uint32_t o = (!LAZY || ((st.live >> j) & 1u)) ? off + (uint32_t)(j * LOAD_ROWS * ROWB) : DEAD_OFFSET;
-      st.v[j] = buffer_load16(rv, o);
+      st.v[j] = buffer_load16_stream(rv, o);
     }
   }
 
@@ -338,11 +346,11 @@ struct AttendGqa {
     if (LAZY) st.live = (uint32_t)(sh_live[trow >> 6] >> (trow & 63)) & 0xffffu;
     const bool klive = !LAZY || ((st.live >> n) & 1u);
 #pragma unroll
-    for (int kb = 0; kb < 4; ++kb) st.k[kb] = buffer_load16(rk, klive ? koff + (uint32_t)(64 * kb) : DEAD_OFFSET);
+    for (int kb = 0; kb < 4; ++kb) st.k[kb] = buffer_load16_stream(rk, klive ? koff + (uint32_t)(64 * kb) : DEAD_OFFSET);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const bool vlive = !LAZY || ((st.live >> (4 * j + lg)) & 1u);
-      st.v[j] = buffer_load16(rv, vlive ? voff + (uint32_t)(j * 4 * ROWB) : DEAD_OFFSET);
+      st.v[j] = buffer_load16_stream(rv, vlive ? voff + (uint32_t)(j * 4 * ROWB) : DEAD_OFFSET);
     }
   }
 
