@@ -344,7 +344,7 @@ __global__ __launch_bounds__(WG) void corm_prefill_kernel(const PrefillArgs a) {
                 if (sl >= a.w) sl -= a.w;
                 uint16_t* dst =
                     reinterpret_cast<uint16_t*>(a.ring) + ((size_t)head * a.w + sl) * a.Tcap + pos_w0 + ch * 8;
-                *reinterpret_cast<uint4*>(dst) = v;
+                __builtin_nontemporal_store(u32x4_t{v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4_t*>(dst));
               }
               __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
             } else {
