@@ -309,10 +309,10 @@ int launch_compact(const corm_desc* d, const WorkspaceLayout& wl, void* workspac
 
 template <typename DT, int D>
 int launch_prefill_dt(const PrefillArgs& a, dim3 grid, dim3 mgrid, int KB, hipStream_t s) {
-  hipLaunchKernelGGL((corm_prefill_kernel<DT, D, 1, false>), grid, dim3(WG), 0, s, a);
+  hipLaunchKernelGGL((corm_prefill_stats_kernel<DT, D>), grid, dim3(WG), 0, s, a);
   hipLaunchKernelGGL(corm_prefill_merge_kernel, mgrid, dim3(256), 0, s, a, KB);
-  if (a.ring_bits) hipLaunchKernelGGL((corm_prefill_kernel<DT, D, 2, true>), grid, dim3(WG), 0, s, a);
-  else hipLaunchKernelGGL((corm_prefill_kernel<DT, D, 2, false>), grid, dim3(WG), 0, s, a);
+  if (a.ring_bits) hipLaunchKernelGGL((corm_prefill_scores_kernel<DT, D, true>), grid, dim3(WG), 0, s, a);
+  else hipLaunchKernelGGL((corm_prefill_scores_kernel<DT, D, false>), grid, dim3(WG), 0, s, a);
   return launch_status();
 }
 

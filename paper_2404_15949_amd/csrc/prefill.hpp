@@ -115,7 +115,7 @@ __device__ __forceinline__ void prefill_scores_bf16(const f32x4_t (&d)[T], const
   }
 }
 
-constexpr int PREFILL_SEG = 1024;   // queries whose pass-1 partials a workgroup holds in LDS at a time
+constexpr int PREFILL_SEG = 512;   // queries whose pass-1 partials a workgroup holds in LDS at a time
 
 template <int ROWB>
 struct PrefillGeom {
@@ -129,7 +129,7 @@ struct PrefillGeom {
 };
 
 template <typename DT, int D, int PASS, bool BITS>
-__global__ __launch_bounds__(WG) void corm_prefill_kernel(const PrefillArgs a) {
+__device__ __forceinline__ void prefill_pass(const PrefillArgs& a) {
   constexpr int ROWB = D * DT::ESZ;
   using Geo = PrefillGeom<ROWB>;
   constexpr int NCH = Geo::NCH, T = Geo::T, KB = Geo::KB;
@@ -421,6 +421,19 @@ __global__ __launch_bounds__(WG) void corm_prefill_kernel(const PrefillArgs a) {
         if (n == 0 && key < L && v > lhb[key]) lhb[key] = v;
       }
   }
+}
+
+// Pass 1 has a light tail (max, exp, sum) and is latency-bound at two waves per SIMD: held to the registers
+// and LDS of three (0.91 -> 0.64 ms per layer on config 3).  Pass 2 needs its registers.
+template <typename DT, int D>
+__global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(3, 3))) void corm_prefill_stats_kernel(
+    const PrefillArgs a) {
+  prefill_pass<DT, D, 1, false>(a);
+}
+
+template <typename DT, int D, bool BITS>
+__global__ __launch_bounds__(WG) void corm_prefill_scores_kernel(const PrefillArgs a) {
+  prefill_pass<DT, D, 2, BITS>(a);
 }
 
 // boolean message: zero the words of the rows of steps tau_0 .. tau_{m-1} that pass 2 may set bits in
