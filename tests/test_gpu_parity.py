@@ -330,6 +330,15 @@ def test_bit_ring_prefill_seed(name):
                                       score_dtype="bit")
 
 
+def test_f32_ring_on_a_bf16_cache():
+    """score_dtype is independent of kv_dtype: fp32 probabilities recorded for a bf16 cache (decode steps and
+    prompt seeding)."""
+    wl, every = TRAJ["bf16_gqa4"]
+    harness.run_slaved_trajectory(wl, DEV, check_state_every=every, score_dtype="f32")
+    rep = harness.run_slaved_trajectory(wl, DEV, check_state_every=every, score_dtype="f32", seed_kernel=True)
+    assert rep["evicted_total"] > 0
+
+
 def test_bit_ring_split_calls_and_lazy():
     """The literal mask (corm_evict_mask) reads the bits; deferred compaction and ragged steps work on a bit ring."""
     wl = W["tiny_f32"].replace(B=3, P=300, D=40, w=32, r=8)
