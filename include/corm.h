@@ -127,6 +127,13 @@ int corm_decode_attend(const corm_desc* desc, const void* q, const void* K, cons
 int corm_evict_mask(const corm_desc* desc, const void* score_ring, const int32_t* lens, const int32_t* pos,
                     const int32_t* t, const int32_t* t_first, uint8_t* keep, void* stream);
 
+/* Diagnostic (Section 3, the sparsity measurement): density[b,hq] = share of the unit's live keys whose
+ * recorded score of the current step t reaches c/t (Def. 3.1), read from the ring row of step t after
+ * corm_decode_attend / a step call recorded it (before a compaction moves pos).  density: device float32
+ * [B, Hq]; 1 - density is the share of minor keys of that head at that step.  Works on score and bit rings. */
+int corm_row_density(const corm_desc* desc, const void* score_ring, const int32_t* lens, const int32_t* pos,
+                     const int32_t* t, float* density, void* stream);
+
 /* The same decision from the per-key summary: keep[i] = last_hit[i] > t - w  OR  i >= lens - r
  * (equal to corm_evict_mask when last_hit was maintained by corm_decode_attend over the window). */
 int corm_evict_mask_summary(const corm_desc* desc, const int32_t* last_hit, const int32_t* lens,

@@ -107,6 +107,13 @@ def important(stored_scores: np.ndarray, t: int, c: float = 1.0) -> np.ndarray:
     return np.asarray(stored_scores, dtype=np.float32) >= importance_threshold(t, c)
 
 
+def important_fraction(stored_scores: np.ndarray, t: int, c: float = 1.0) -> float:
+    """Share of the live keys a query finds important (Def. 3.1): the per-head quantity behind the
+    sparsity figures of Section 3 (1 - this value is the share of minor keys).  Empty cache: 0."""
+    imp = important(stored_scores, t, c)
+    return float(imp.mean()) if imp.size else 0.0
+
+
 # --------------------------------------------------------------------------
 # Algorithm 1
 

@@ -21,7 +21,7 @@ CORM_OK, CORM_EINVAL, CORM_EUNSUPPORTED, CORM_ECAPACITY, CORM_EHIP = 0, -1, -2, 
 CORM_DEV_UNIT_FULL, CORM_DEV_BAD_STEP, CORM_DEV_BAD_LENS = 1, 2, 4
 
 EXPORTS = ("corm_version", "corm_strerror", "corm_workspace_bytes", "corm_workspace_init", "corm_append",
-           "corm_decode_attend", "corm_evict_mask", "corm_evict_mask_summary", "corm_compact",
+           "corm_decode_attend", "corm_evict_mask", "corm_evict_mask_summary", "corm_row_density", "corm_compact",
            "corm_decode_step", "corm_step_attend", "corm_step_evict", "corm_decode_step_lazy", "corm_prefill_seed", "corm_force_path",
            "corm_selected_path", "corm_profile_attend", "corm_threshold")
 
@@ -62,6 +62,7 @@ def lib() -> ctypes.CDLL:
         L.corm_decode_attend.argtypes = [dp, vp, vp, vp, i32p, i32p, i32p, vp, i32p, vp, vp, sz, i32p, vp]
         L.corm_evict_mask.argtypes = [dp, vp, i32p, i32p, i32p, i32p, vp, vp]
         L.corm_evict_mask_summary.argtypes = [dp, i32p, i32p, i32p, i32p, vp, vp]
+        L.corm_row_density.argtypes = [dp, vp, i32p, i32p, i32p, vp, vp]
         L.corm_compact.argtypes = [dp, vp, vp, i32p, i32p, i32p, vp, i32p, vp, sz, vp]
         L.corm_step_attend.argtypes = [dp, vp, vp, vp, vp, vp, i32p, i32p, i32p, i32p, i32p, vp, vp, vp, vp, sz,
                                        i32p, vp]
@@ -196,6 +197,12 @@ def corm_step_evict(desc, K, V, lens, pos, last_hit, kept_idx=None, workspace=No
     rc = lib().corm_step_evict(ctypes.byref(desc), _ptr(K), _ptr(V), _ptr(lens), _ptr(pos), _ptr(last_hit),
                                _ptr(kept_idx), _ptr(workspace), _nbytes(workspace, workspace_bytes), _stream(stream))
     return _check(rc, "corm_step_evict") if check else rc
+
+
+def corm_row_density(desc, score_ring, lens, pos, t, density, stream=None, check=True) -> int:
+    rc = lib().corm_row_density(ctypes.byref(desc), _ptr(score_ring), _ptr(lens), _ptr(pos), _ptr(t), _ptr(density),
+                                _stream(stream))
+    return _check(rc, "corm_row_density") if check else rc
 
 
 def corm_selected_path(desc) -> int:

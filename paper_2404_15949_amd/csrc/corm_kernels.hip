@@ -121,6 +121,19 @@ int corm_evict_mask(const corm_desc* desc, const void* score_ring, const int32_t
   return launch_status();
 }
 
+int corm_row_density(const corm_desc* desc, const void* score_ring, const int32_t* lens, const int32_t* pos,
+                     const int32_t* t, float* density, void* stream) {
+  int rc = validate_desc(desc);
+  if (rc) return rc;
+  if (!score_ring || !lens || !pos || !t || !density) return CORM_EINVAL;
+  if (misaligned4(score_ring) || misaligned4(lens) || misaligned4(pos) || misaligned4(t) || misaligned4(density))
+    return CORM_EINVAL;
+  hipLaunchKernelGGL(corm_row_density_kernel, dim3(desc->B * desc->Hq), dim3(WG), 0, (hipStream_t)stream, score_ring,
+                     (int)desc->score_dtype, lens, pos, t, density, desc->Hq, desc->Hkv, desc->Lcap, desc->Tcap,
+                     desc->w, desc->thr_scale);
+  return launch_status();
+}
+
 int corm_evict_mask_summary(const corm_desc* desc, const int32_t* last_hit, const int32_t* lens, const int32_t* t,
                             const int32_t* t_first, uint8_t* keep, void* stream) {
   int rc = validate_desc(desc);

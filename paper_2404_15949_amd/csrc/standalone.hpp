@@ -89,6 +89,51 @@ __global__ __launch_bounds__(WG) void corm_evict_mask_summary_kernel(const int32
   keep[(size_t)unit * Lcap + i] = k ? 1 : 0;
 }
 
+// Diagnostic (Section 3, attention sparsity): per query head, the share of the unit's live keys whose
+// recorded score of step t reaches c/t.  One workgroup per head.
+__global__ __launch_bounds__(WG) void corm_row_density_kernel(const void* ring, int ring_mode, const int32_t* lens,
+                                                              const int32_t* pos, const int32_t* t, float* density,
+                                                              int Hq, int Hkv, int Lcap, int Tcap, int w, float c) {
+  __shared__ int sh_cnt[WAVES];
+  const int head = blockIdx.x;
+  const int b = head / Hq, hq = head - b * Hq;
+  const int unit = b * Hkv + hq / (Hq / Hkv);
+  int L = lens[unit];
+  L = L < 0 ? 0 : (L > Lcap ? Lcap : L);
+  const int tcur = t[b];
+  const bool step_ok = tcur >= 1 && tcur <= Tcap;
+  const float thr = importance_threshold(c, step_ok ? tcur : 1);
+  const size_t row = (size_t)head * w + (size_t)(step_ok ? (tcur - 1) % w : 0);
+  int cnt = 0;
+  for (int i0 = 0; i0 < L; i0 += WG) {
+    const int i = i0 + (int)threadIdx.x;
+    bool hit = false;
+    if (i < L && step_ok) {
+      const int pi = pos[(size_t)unit * Lcap + i];
+      if (pi >= 0 && pi < Tcap && pi <= tcur - 1) {
+        if (ring_mode == CORM_BIT) {
+          hit = ((reinterpret_cast<const uint32_t*>(ring)[row * ((Tcap + 31) >> 5) + (size_t)(pi >> 5)] >> (pi & 31)) & 1u) != 0;
+        } else {
+          const size_t ri = row * Tcap + (size_t)pi;
+          const float v = ring_mode == CORM_BF16
+                              ? __uint_as_float((uint32_t) reinterpret_cast<const uint16_t*>(ring)[ri] << 16)
+                              : reinterpret_cast<const float*>(ring)[ri];
+          hit = v >= thr;
+        }
+      }
+    }
+    cnt += __popcll(__ballot(hit));
+  }
+  if ((threadIdx.x & 63) == 0) sh_cnt[threadIdx.x >> 6] = cnt;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int tot = 0;
+#pragma unroll
+    for (int i = 0; i < WAVES; ++i) tot += sh_cnt[i];
+    density[head] = L > 0 ? (float)tot / (float)L : 0.f;
+  }
+}
+
 __global__ void corm_threshold_kernel(float c, const int32_t* t, int n, float* thr) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) thr[i] = importance_threshold(c, t[i]);

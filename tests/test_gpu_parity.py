@@ -330,6 +330,39 @@ def test_bit_ring_prefill_seed(name):
                                       score_dtype="bit")
 
 
+@pytest.mark.parametrize("ring", [None, "bit"])
+def test_row_density_matches_the_oracle(ring):
+    """corm_row_density (the sparsity measurement of Section 3) on the row a step just recorded: per query head
+    exactly the oracle's share of important keys among the recorded scores."""
+    wl = W["gqa_llama3"].replace(B=2, Hq=8, Hkv=2, P=700, D=4, w=16, r=16)
+    x = {k: v.to(DEV) for k, v in inputs.make_layer(wl, 0, device="cpu").items() if k != "sinks"}
+    st = harness.make_state(wl, DEV, score_dtype=ring)
+    n_replay = min(wl.w, wl.P)
+    pre = wl.P - n_replay
+    st.preload(x["K0"][:, :, :pre], x["V0"][:, :, :pre])
+    dens = torch.zeros(wl.B, wl.Hq, dtype=torch.float32, device=DEV)
+    G = wl.G
+    for j in range(6):
+        q, k, v, t = harness.step_inputs(wl, x, j, n_replay)
+        td = torch.full((wl.B,), t, dtype=torch.int32, device=DEV)
+        corm.corm_append(st.desc, st.K, st.V, st.lens, st.pos, st.last_hit, k, v, td, st.status)
+        corm.corm_decode_attend(st.desc, q, st.K, st.V, st.lens, st.pos, td, st.ring, st.last_hit, st.out,
+                                st.workspace, status=st.status)
+        corm.corm_row_density(st.desc, st.ring, st.lens, st.pos, td, dens)
+        torch.cuda.synchronize()
+        got = dens.cpu().numpy()
+        for b in range(wl.B):
+            row = harness.ring_row(st, b, (t - 1) % wl.w)
+            for hq in range(wl.Hq):
+                h = hq // G
+                l = int(st.lens[b, h].item())
+                positions = st.pos[b, h, :l].cpu().numpy()
+                want = np.float32(O.important(row[hq][positions], t).sum()) / np.float32(l)
+                assert got[b, hq] == want, (j, b, hq, got[b, hq], want)
+                assert abs(O.important_fraction(row[hq][positions], t) - float(want)) < 1e-6
+    assert 0.0 < got.min() and got.max() < 1.0
+
+
 def test_f32_ring_on_a_bf16_cache():
     """score_dtype is independent of kv_dtype: fp32 probabilities recorded for a bf16 cache (decode steps and
     prompt seeding)."""

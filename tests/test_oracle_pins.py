@@ -104,6 +104,19 @@ def test_threshold_is_correctly_rounded_fp32_quotient():
             assert abs(got - exact) <= abs(lo - exact) and abs(got - exact) <= abs(hi - exact), (c, t)
 
 
+def test_important_fraction_closed_forms():
+    """Section 3's sparsity measurement: all keys important under uniform attention (every score is exactly
+    1/t, and the compare is inclusive); a query that puts nearly everything on one key finds 1 of l
+    important; geometric scores p_i = 2^-(i+1) have exactly floor(log2 t) keys at or above 1/t."""
+    t = 64
+    assert O.important_fraction(np.full(t, 1.0 / t, dtype=np.float32), t) == 1.0
+    one = np.full(t, 1e-6, dtype=np.float32); one[17] = 1.0 - 63e-6
+    assert O.important_fraction(one, t) == 1.0 / t
+    geo = np.float32(2.0) ** -np.arange(1, t + 1, dtype=np.float32)
+    assert O.important_fraction(geo, t) == 6.0 / t          # 2^-1 .. 2^-6 >= 1/64
+    assert O.important_fraction(np.zeros(0, dtype=np.float32), 5) == 0.0
+
+
 def test_important_is_inclusive_and_nan_is_minor():
     t = 7
     thr = O.importance_threshold(t)
