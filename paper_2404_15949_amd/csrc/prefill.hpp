@@ -20,7 +20,8 @@ namespace {
 //            position, and per key the latest step whose stored score reaches the threshold
 // The workgroup keeps its keys in registers as the A operand (lane l: key l%16 of a 16-key tile, the
 // 16 bytes 64*c + 16*(l/16) .. of each 64-byte chunk c of the row); a tile of 16 queries is the B
-// operand, loaded the same way.  D: lane l holds query l%16, keys 4*(l/16) .. +3 of the tile.
+// operand in the same layout, read from LDS, where the workgroup stages the queries in double-buffered
+// blocks.  D: lane l holds query l%16, keys 4*(l/16) .. +3 of the tile.
 
 struct PrefillArgs {
   const void* q_tail;   // [B, Hq, m, d]
