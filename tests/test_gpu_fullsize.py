@@ -123,6 +123,39 @@ def test_config5_gqa_structured_evicts():
     _run(wl, 0, 4, {n_replay, n_replay + 3}, _sample_units(wl, 6, seed=2), expect_path=1, expect_evictions=True)
 
 
+def _all_units(wl):
+    return [(b, h) for b in range(wl.B) for h in range(wl.Hkv)]
+
+
+def test_config3_every_unit_of_a_layer():
+    """All 512 units of one layer of the eviction-heavy variant at three decode steps after the prompt
+    (oracles rebuilt from the device state before each, one per unit): ragged
+    lengths, evictions and compaction in every corner of the launch, not only in a sample."""
+    wl = W["llama7b_b16"].replace(q_mean_scales=inputs.STRUCTURED_Q_MEAN)
+    n_replay = wl.w
+    _run(wl, 2, 3, {n_replay, n_replay + 1, n_replay + 2}, _all_units(wl), expect_path=2, expect_evictions=True,
+         seed_kernel=True)
+
+
+def test_config3_literal_generator_many_units():
+    """The headline workload itself (literal generator, nothing evicted): 128 of the 512 units at two steps."""
+    wl = W["llama7b_b16"]
+    n_replay = wl.w
+    _run(wl, 7, 2, {n_replay + 1}, _all_units(wl)[1::4], expect_path=2, seed_kernel=True)
+
+
+def test_config5_gqa_every_unit():
+    """All 128 units of the grouped-query workload (MFMA attend kernel), eviction-heavy variant, one step."""
+    wl = W["gqa_llama3"].replace(q_mean_scales=(3.0, 5.0), key_scale=1.5)
+    _run(wl, 0, 1, set(), _all_units(wl), expect_path=1, expect_evictions=True, seed_kernel=True)
+
+
+def test_config4_long_context_more_units():
+    """16 of the 128 units of the 32k-token workload, one step after the seeded prompt."""
+    wl = W["long32k"]
+    _run(wl, 0, 1, set(), _all_units(wl)[3::8], expect_path=1, seed_kernel=True)
+
+
 # ------------------------------------------------------------------ prompt seeding at full size
 
 def _seed_check(wl, layer, units, rows_per_unit=5, expect_evictions=False):
@@ -187,9 +220,15 @@ def test_config3_prompt_seeding():
                 expect_evictions=True)
 
 
+def test_config3_prompt_seeding_every_unit():
+    """The bulk eviction at the end of the prompt, all 512 units of a layer of the eviction-heavy variant."""
+    wl = W["llama7b_b16"].replace(q_mean_scales=inputs.STRUCTURED_Q_MEAN)
+    _seed_check(wl, 4, _all_units(wl), rows_per_unit=1, expect_evictions=True)
+
+
 def test_config5_prompt_seeding_gqa():
     wl = W["gqa_llama3"].replace(q_mean_scales=(3.0, 5.0), key_scale=1.5)
-    _seed_check(wl, 0, _sample_units(wl, 4, seed=6), expect_evictions=True)
+    _seed_check(wl, 0, _all_units(wl)[::4], rows_per_unit=2, expect_evictions=True)
 
 
 def test_config4_prompt_seeding_long_context():
@@ -201,7 +240,7 @@ def test_config4_prompt_seeding_long_context():
 
 def test_config3_structured_lazy_steps():
     """The eviction-heavy variant of config 3 in the launch configuration `bench.py --structured --lazy-frac 1/4`
-    times: window seeded by corm_prefill_seed, then corm_decode_step_lazy.  Sampled units are followed by
+    times: window seeded by corm_prefill_seed, then corm_decode_step_lazy.  All 512 units are followed by
     oracles rebuilt from the device state after the prompt and fed the recorded scores: at every step the
     keep decision on the live slots, and at the end the live rows in slot order, last_hit and the live
     counts, must be the oracle's; dead slots stay dead; out within tolerance."""
@@ -218,7 +257,7 @@ def test_config3_structured_lazy_steps():
     tf = torch.zeros_like(t)
     st.prefill_seed(x["Q"][:m].permute(1, 2, 0, 3).contiguous(), t, tf)
     torch.cuda.synchronize()
-    units = _sample_units(wl, 10, seed=9)
+    units = _all_units(wl)
     t_first = wl.P - m + 1
     oracles = {u: harness.oracle_from_snapshot(st, u[0], u[1], wl.P, t_first, wl.dtype, 1.0) for u in units}
     slots = {u: np.arange(oracles[u].l) for u in units}
@@ -254,6 +293,6 @@ def test_config3_structured_lazy_steps():
                 assert e <= harness.OUT_TOL[wl.dtype], ("out", j, b, h, g, e)
     for (b, h) in units:
         harness.check_unit_state(st, b, h, oracles[(b, h)], wl.P + n_decode, lazy=True)
-    say("evicted", evicted, "compactions", compactions, "slots in use", [used[u] for u in units],
-        "live", [oracles[u].l for u in units])
+    say("evicted", evicted, "compactions", compactions, "slots in use", sum(used[u] for u in units),
+        "live", sum(oracles[u].l for u in units))
     assert evicted > 0
