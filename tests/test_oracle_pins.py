@@ -50,6 +50,29 @@ def test_bf16_rounding_matches_library():
     assert O.round_to_bf16(np.float32(1.0 + 3 * 2 ** -8)) == np.float32(1.0 + 2 ** -6)
 
 
+def test_stored_scores_are_the_library_conversions():
+    """What the record holds: the fp64 score rounded to fp32, then (bf16 record) to bfloat16 -- the two
+    conversions a library performs, in that order; and a bf16 unit really stores bf16 values."""
+    rng = np.random.default_rng(4)
+    a = rng.dirichlet(np.ones(500) * 0.1, size=8)
+    as32 = torch.from_numpy(a).to(torch.float32)
+    assert np.array_equal(O.round_to_storage(a, "f32"), as32.numpy())
+    got = O.round_to_storage(a, "bf16")
+    assert got.dtype == np.float32
+    assert np.array_equal(got, as32.to(torch.bfloat16).float().numpy())
+    assert not np.array_equal(got, as32.numpy())
+    with pytest.raises(ValueError):
+        O.round_to_storage(a, "f16")
+    for dt in ("bf16", "f32"):
+        u = O.UnitCache(16, 2, 4, 2, score_dtype=dt)
+        low_bits = 0
+        for t in range(1, 30):
+            res = u.step(rng.standard_normal((2, 16)) * 2, rng.standard_normal(16), rng.standard_normal(16), t)
+            assert np.array_equal(res["stored"], O.round_to_storage(res["alpha"], dt))
+            low_bits |= int(np.bitwise_or.reduce(res["stored"].view(np.uint32).ravel()) & 0xFFFF)
+        assert (low_bits == 0) == (dt == "bf16")
+
+
 # ------------------------------------------------------------------ Eq. (1), Eq. (2)
 
 def test_scores_are_a_softmax_and_sum_to_one():
