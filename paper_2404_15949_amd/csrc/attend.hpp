@@ -313,13 +313,17 @@ __global__ __launch_bounds__(WG) void corm_attend_kernel(const Params p) {
 // ---------------------------------------------------------------- attend, grouped queries: q.K^T on MFMA
 //
 // bf16, d = 128, G query heads per KV head.  Per stage a wave owns a tile of 16 consecutive keys.
-// K is loaded straight into the A-operand layout of v_mfma_f32_16x16x32_bf16 (lane l: key l%16, the 8
-// elements 32*kb + 8*(l/16) .. +8 of block kb: 64 contiguous bytes of a row per load), the G queries
-// sit in columns 0..G-1 of the B operand (the other columns are zero), and four MFMAs give the 16 x G
-// logits of the tile without any cross-lane reduction: lane (n = l%16 < G, lg = l/16) holds the logits
-// of head n for keys 4*lg .. 4*lg+3.  The softmax bookkeeping runs in those lanes (all heads at once),
-// the probabilities go through a per-wave LDS tile to the lanes that hold V in the row layout
-// (lane l: row l/16 of a load, 16-byte column slice l%16), and p.V stays on the vector ALU.
+// K and V are both loaded in the row layout (lane l: row l/16 of a load, 16-byte column slice l%16, so
+// 16 lanes read one whole 256-byte row and a load covers four full rows).  The A operand of
+// v_mfma_f32_16x16x32_bf16 wants lane l to hold key l%16, elements 32*kb + 8*(l/16) .. +8 of block kb;
+// loading K that way straight from memory would fetch 64-byte pieces of 16 rows per instruction (half
+// cache lines: measurably slower), so the tile takes a turn through a wave-private 4 KiB LDS tile
+// instead, its 16-byte pieces XOR-swizzled by the row so that neither the writes nor the reads
+// conflict.  The G queries sit in columns 0..G-1 of the B operand (the other columns are zero), and
+// four MFMAs give the 16 x G logits of the tile without any cross-lane reduction: lane (n = l%16 < G,
+// lg = l/16) holds the logits of head n for keys 4*lg .. 4*lg+3.  The softmax bookkeeping runs in those
+// lanes (all heads at once), the probabilities go through a per-wave LDS tile to the lanes that hold V,
+// and p.V stays on the vector ALU.
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
@@ -331,8 +335,8 @@ struct AttendGqa {
   static constexpr int STAGE_ROWS = WAVES * TILE;    // keys per workgroup and stage
 
   struct Stage {
-    uint4 k[4];  // A operand, k-blocks 0..3
-    uint4 v[4];  // rows 4*j + lane/16 of the tile, this lane's 16-byte column slice
+    uint4 k[4];  // rows 4*j + lane/16 of the tile, this lane's 16-byte column slice
+    uint4 v[4];  // the same rows and slice of V
     uint32_t live;   // lazy mode: bit i = key i of the tile is live
   };
 
@@ -340,30 +344,41 @@ struct AttendGqa {
   // slot sh_live covers (a multiple of 16); the loads of dead keys get an out-of-range offset.
   template <bool LAZY>
   __device__ static __forceinline__ void load(Stage& st, __amdgpu_buffer_rsrc_t rk, __amdgpu_buffer_rsrc_t rv,
-                                              uint32_t koff, uint32_t voff, const unsigned long long* sh_live,
-                                              int trow, int n, int lg) {
+                                              uint32_t off, const unsigned long long* sh_live, int trow,
+                                              int lg) {
     st.live = 0xffffu;
     if (LAZY) st.live = (uint32_t)(sh_live[trow >> 6] >> (trow & 63)) & 0xffffu;
-    const bool klive = !LAZY || ((st.live >> n) & 1u);
-#pragma unroll
-    for (int kb = 0; kb < 4; ++kb) st.k[kb] = buffer_load16_stream(rk, klive ? koff + (uint32_t)(64 * kb) : DEAD_OFFSET);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const bool vlive = !LAZY || ((st.live >> (4 * j + lg)) & 1u);
-      st.v[j] = buffer_load16_stream(rv, vlive ? voff + (uint32_t)(j * 4 * ROWB) : DEAD_OFFSET);
+      const bool rlive = !LAZY || ((st.live >> (4 * j + lg)) & 1u);
+      st.k[j] = buffer_load16_stream(rk, rlive ? off + (uint32_t)(j * 4 * ROWB) : DEAD_OFFSET);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const bool rlive = !LAZY || ((st.live >> (4 * j + lg)) & 1u);
+      st.v[j] = buffer_load16_stream(rv, rlive ? off + (uint32_t)(j * 4 * ROWB) : DEAD_OFFSET);
     }
   }
 
-  // row0: first key of this wave's tile; lrel0: its index in the logit staging array
+  // row0: first key of this wave's tile; lrel0: its index in the logit staging array;
+  // sh_kt: this wave's 16 x 16 tile of 16-byte pieces (piece c of key r at [r][c ^ (r & 7)])
   __device__ static __forceinline__ void compute(const Stage& st, int row0, int lrel0, int cend, int n, int lg,
                                                  const uint4 (&qb)[4], float scale_log2, float* sh_logit,
-                                                 int lstride, float* sh_p, float* sh_alpha, float& m_run,
-                                                 float& z_run, float (&acc)[G][EPL]) {
+                                                 int lstride, uint4* sh_kt, float* sh_p, float* sh_alpha,
+                                                 float& m_run, float& z_run, float (&acc)[G][EPL]) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int r = 4 * j + lg;
+      sh_kt[r * 16 + (n ^ (r & 7))] = st.k[j];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // LDS is in order within a wave: compiler fence only
     f32x4_t d = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int kb = 0; kb < 4; ++kb)
-      d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, st.k[kb]),
+    for (int kb = 0; kb < 4; ++kb) {
+      const uint4 a = sh_kt[n * 16 + ((4 * kb + lg) ^ (n & 7))];   // key n, elements 32*kb + 8*lg .. +8
+      d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a),
                                                   __builtin_bit_cast(bf16x8_t, qb[kb]), d, 0, 0, 0);
+    }
     float s[4];
     float tmax = neg_inf();
 #pragma unroll
@@ -411,7 +426,8 @@ struct AttendGqa {
 };
 
 template <int G, bool LAZY>
-__global__ __launch_bounds__(WG) void corm_attend_gqa_kernel(const Params p) {
+__global__ __launch_bounds__(WG) __attribute__((amdgpu_waves_per_eu(G <= 4 ? 3 : 2)))
+void corm_attend_gqa_kernel(const Params p) {
   using A = AttendGqa<G>;
   constexpr int D = A::D, ROWB = A::ROWB, EPL = A::EPL, LPR = 16;
 
@@ -432,6 +448,7 @@ __global__ __launch_bounds__(WG) void corm_attend_gqa_kernel(const Params p) {
   __shared__ float sh_z[G][WAVES];
   __shared__ float sh_acc[G][WAVES][D];
   __shared__ float sh_logit[G][CHUNK];
+  __shared__ uint4 sh_kt[WAVES][A::TILE * 16];
   __shared__ __attribute__((aligned(16))) float sh_p[WAVES][A::TILE * G];
   __shared__ __attribute__((aligned(16))) float sh_alpha[WAVES][G];
   __shared__ unsigned long long sh_live[LAZY ? CHUNK / 64 : 1];
@@ -485,29 +502,26 @@ __global__ __launch_bounds__(WG) void corm_attend_gqa_kernel(const Params p) {
   const __amdgpu_buffer_rsrc_t rk = make_rsrc(Kb, (uint32_t)cend * ROWB);
   const __amdgpu_buffer_rsrc_t rv = make_rsrc(Vb, (uint32_t)cend * ROWB);
   const int tile0 = cbeg + wv * A::TILE;   // first key of this wave's tile in stage 0
-  const uint32_t koff = (uint32_t)(tile0 + n) * ROWB + (uint32_t)(16 * lg);
-  const uint32_t voff = (uint32_t)(tile0 + lg) * ROWB + (uint32_t)(16 * n);
+  const uint32_t off = (uint32_t)(tile0 + lg) * ROWB + (uint32_t)(16 * n);
   constexpr uint32_t STAGE_BYTES = (uint32_t)A::STAGE_ROWS * ROWB;
   constexpr int PAIRS = CHUNK / (2 * A::STAGE_ROWS);
   static_assert(PAIRS >= 1 && CHUNK % (2 * A::STAGE_ROWS) == 0, "CHUNK must hold whole stage pairs");
 
   typename A::Stage s0, s1;
-  A::template load<LAZY>(s0, rk, rv, koff, voff, sh_live, wv * A::TILE, n, lg);
+  A::template load<LAZY>(s0, rk, rv, off, sh_live, wv * A::TILE, lg);
 #pragma unroll
   for (int i = 0; i < PAIRS; ++i) {
     const int it = cbeg + i * 2 * A::STAGE_ROWS;
     if (it >= cend) break;
-    A::template load<LAZY>(s1, rk, rv, koff + (uint32_t)(2 * i + 1) * STAGE_BYTES,
-                           voff + (uint32_t)(2 * i + 1) * STAGE_BYTES, sh_live,
-                           (2 * i + 1) * A::STAGE_ROWS + wv * A::TILE, n, lg);
+    A::template load<LAZY>(s1, rk, rv, off + (uint32_t)(2 * i + 1) * STAGE_BYTES, sh_live,
+                           (2 * i + 1) * A::STAGE_ROWS + wv * A::TILE, lg);
     A::compute(s0, it + wv * A::TILE, it - cbeg + wv * A::TILE, cend, n, lg, qb, p.scale_log2, &sh_logit[0][0],
-               CHUNK, sh_p[wv], sh_alpha[wv], m_run, z_run, acc);
+               CHUNK, sh_kt[wv], sh_p[wv], sh_alpha[wv], m_run, z_run, acc);
     if (i + 1 < PAIRS)
-      A::template load<LAZY>(s0, rk, rv, koff + (uint32_t)(2 * i + 2) * STAGE_BYTES,
-                             voff + (uint32_t)(2 * i + 2) * STAGE_BYTES, sh_live,
-                             (2 * i + 2) * A::STAGE_ROWS + wv * A::TILE, n, lg);
+      A::template load<LAZY>(s0, rk, rv, off + (uint32_t)(2 * i + 2) * STAGE_BYTES, sh_live,
+                             (2 * i + 2) * A::STAGE_ROWS + wv * A::TILE, lg);
     A::compute(s1, it + A::STAGE_ROWS + wv * A::TILE, it - cbeg + A::STAGE_ROWS + wv * A::TILE, cend, n, lg, qb,
-               p.scale_log2, &sh_logit[0][0], CHUNK, sh_p[wv], sh_alpha[wv], m_run, z_run, acc);
+               p.scale_log2, &sh_logit[0][0], CHUNK, sh_kt[wv], sh_p[wv], sh_alpha[wv], m_run, z_run, acc);
   }
 
   // the wave's sum of head n is spread over the lane groups; its accumulators over the rows of a load.
