@@ -156,6 +156,28 @@ def test_config4_long_context_more_units():
     _run(wl, 0, 1, set(), _all_units(wl)[3::8], expect_path=1, seed_kernel=True)
 
 
+# ------------------------------------------------------------------ the largest shapes the interface accepts
+
+def test_longest_unit_the_interface_accepts():
+    """One unit of fp32 d = 128 rows at the slot limit (byte offsets inside a unit are 32-bit: Lcap * 512 B
+    < 2^31, i.e. 4194303 slots, 2 GiB of K and of V): the last prompt position with its bulk eviction
+    (more than half of four million keys leave in one compaction) and a decode step, against an oracle
+    rebuilt from the device state."""
+    wl = W["tiny_f32"].replace(name="longest_unit", B=1, Hq=1, Hkv=1, d=128, P=4194301, D=2, w=4, r=4)
+    n_replay = wl.w
+    lens = _run(wl, 0, 2, {n_replay + 1}, [(0, 0)], expect_path=1, expect_evictions=True)
+    assert 4 <= int(lens[0, 0]) < wl.P // 2
+
+
+def test_most_units_the_interface_accepts():
+    """65520 units (the launch grid allows 65535), short caches: the fused unit kernel with one workgroup
+    per unit, first and last units included in the sample."""
+    wl = W["tiny_f32"].replace(name="most_units", B=4095, Hq=16, Hkv=16, d=64, P=40, D=6, w=8, r=4)
+    n_replay = wl.w
+    units = sorted(set(_sample_units(wl, 40, seed=21)) | {(0, 0), (wl.B - 1, wl.Hkv - 1)})
+    _run(wl, 0, 6, {n_replay, n_replay + 5}, units, expect_path=2, expect_evictions=True)
+
+
 # ------------------------------------------------------------------ prompt seeding at full size
 
 def _seed_check(wl, layer, units, rows_per_unit=5, expect_evictions=False):
