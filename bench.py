@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--layers", type=int, default=None, help="override the number of layers (development only)")
     ap.add_argument("--structured", action="store_true",
                     help="supplementary variant: per-head query means so that eviction happens at w >= 256")
+    ap.add_argument("--w", type=int, default=None, help="override the window of recorded queries (the paper's w/r "
+                    "sweep, Section 5; the ring holds w rows, so memory follows it)")
+    ap.add_argument("--r", type=int, default=None, help="override the number of protected recent keys (default: = w)")
     ap.add_argument("--streams", type=int, default=3, choices=[1, 2, 3, 4],
                     help="layers are issued round-robin on this many streams (they are independent)")
     ap.add_argument("--path", type=int, default=0, choices=[0, 1, 2, 3],
@@ -114,6 +117,10 @@ def main():
     wl = inputs.WORKLOADS[args.workload]
     if args.structured:
         wl = wl.replace(q_mean_scales=inputs.STRUCTURED_Q_MEAN)
+    if args.w is not None or args.r is not None:
+        w_new = wl.w if args.w is None else args.w
+        wl = wl.replace(w=w_new, r=w_new if args.r is None else args.r)
+        assert 1 <= wl.w and 1 <= wl.r, "w and r must be at least 1"
     layers = wl.layers if args.layers is None else args.layers
     K_steps, W_steps = args.steps, args.warmup
     n_dec = W_steps + K_steps + args.extra_steps
@@ -121,6 +128,16 @@ def main():
     Lcap = Tcap = (wl.P + n_dec + 63) // 64 * 64   # ring rows start on 128-byte lines (seeding stores whole lines)
     esz = 2 if wl.dtype == "bf16" else 4
     B, Hq, Hkv, d = wl.B, wl.Hq, wl.Hkv, wl.d
+
+    # the resident state must fit the device: say so before allocating anything
+    ring_b = 0 if args.no_ring else layers * B * Hq * wl.w * (Tcap // 8 if args.ring == "bits" else Tcap * esz)
+    kv_b = 2 * layers * B * Hkv * Lcap * (d * esz + 4)
+    total_mem = torch.cuda.mem_get_info()[1]
+    if ring_b + kv_b > 0.93 * total_mem:
+        print(f"bench.py: the state of this run ({kv_b / 2**30:.0f} GiB of K, V and metadata + {ring_b / 2**30:.0f} GiB "
+              f"of score ring) does not fit the device ({total_mem / 2**30:.0f} GiB); use --ring bits, --no-ring or a "
+              f"smaller --w / --layers", file=sys.stderr)
+        sys.exit(2)
 
     # ---------------- set-up (untimed): allocate, generate, feed the prompt
     t0 = time.time()
