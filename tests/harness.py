@@ -171,10 +171,13 @@ def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_sca
     used_before = {u: pre for u in units}
     j_first = 0
     if seed_kernel:
-        assert lazy is None and not use_split_calls and n_steps >= n_replay
+        assert not use_split_calls and n_steps >= n_replay
         j_first = n_replay
         worst_score = _seed_with_kernel(wl, st, x, x_cpu, oracles, units, offs, offs_dev, n_replay, t_first, thr_scale)
         evicted_total += sum(wl.P - oracles[u].l for u in units)
+        for u in units:     # the seeding call leaves every unit compacted: slots 0 .. l-1 hold the live keys
+            slots_before[u] = np.arange(oracles[u].l)
+            used_before[u] = oracles[u].l
     for j in range(j_first, n_steps):
         q, k, v, t = step_inputs(wl, x, j, n_replay)
         t_dev = torch.full((wl.B,), t, dtype=torch.int32, device=device) + offs_dev

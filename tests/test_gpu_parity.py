@@ -421,6 +421,45 @@ def test_capacity_smaller_than_the_sequence():
     assert (np.array(rep["final_lens"]) == wl.r).all()
 
 
+def _random_shapes(n, seed=2024):
+    """Seeded draw of small workloads across the shapes the interface accepts: odd head counts, every group
+    size, both row widths and dtypes, prompts shorter than the window, r on either side of w, thresholds off
+    the default, every kind of ring, exact and deferred compaction, replayed and dense prompt seeding."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        G = int(rng.choice([1, 1, 2, 4, 8]))
+        Hkv = int(rng.choice([1, 2, 3, 5]))
+        dtype = str(rng.choice(["f32", "bf16"]))
+        w = int(rng.choice([1, 2, 5, 16, 33, 64]))
+        wl = W["tiny_f32"].replace(
+            name=f"random{i}", B=int(rng.integers(1, 4)), Hq=G * Hkv, Hkv=Hkv, d=int(rng.choice([64, 128])),
+            dtype=dtype, P=int(rng.choice([1, 3, 17, 64, 255, 513, 700, 1030])), D=int(rng.integers(6, 28)),
+            w=w, r=int(rng.choice([1, 2, w, w, 2 * w + 1])), key_scale=float(rng.choice([0.5, 1.0, 2.0])),
+            n_sinks=int(rng.choice([0, 4])), seed=int(rng.integers(1 << 20)))
+        kw = dict(thr_scale=float(rng.choice([0.25, 1.0, 1.0, 3.0])),
+                  lazy=(1, int(rng.choice([2, 4, 8]))) if rng.random() < 0.4 else None,
+                  seed_kernel=bool(rng.random() < 0.5),
+                  score_dtype=(None, None, "bit", "f32")[int(rng.integers(4))],
+                  slack=int(rng.choice([0, 1, 7, 64])))
+        out.append((wl, kw))
+    return out
+
+
+RANDOM_SHAPES = _random_shapes(48)
+
+
+@pytest.mark.parametrize("case", range(len(RANDOM_SHAPES)))
+def test_random_shapes(case):
+    wl, kw = RANDOM_SHAPES[case]
+    kw = dict(kw)
+    slack = kw.pop("slack")
+    say("random shape", case, wl, kw, "slack", slack)
+    rep = harness.run_slaved_trajectory(wl, DEV, check_state_every=3, Lcap=wl.P + wl.D + slack,
+                                        Tcap=wl.P + wl.D + slack, **kw)
+    say("report", case, {k: v for k, v in rep.items() if k != "final_lens"})
+
+
 def test_w1_r1():
     wl = W["tiny_f32"].replace(P=40, D=30, w=1, r=1)
     say("w=1 r=1")
