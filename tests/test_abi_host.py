@@ -107,3 +107,37 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(corm, "LIB_PATH", "/nonexistent/libcorm.so")
     with pytest.raises(RuntimeError, match="no fallback"):
         corm.lib()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU: `--gpus 2` (or a multi-rank launch) ends with a message, before
+    anything touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    for argv, env in ((["--gpus", "2"], {}), ([], {"WORLD_SIZE": "2"})):
+        r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), *argv], capture_output=True, text=True,
+                           env={**os.environ, **env}, timeout=120)
+        assert r.returncode == 2, (argv, env, r.returncode, r.stderr[-300:])
+        assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_product_code_never_touches_the_oracle():
+    """The oracle is test infrastructure: nothing in the package imports it, and bench.py only inside its
+    cpu_baseline leg."""
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    pkg = os.path.join(root, "paper_2404_15949_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith(".py"):
+                for ln in open(os.path.join(dirpath, f)):
+                    assert not re.match(r"\s*(from|import)\s+.*\boracle\b", ln), (os.path.join(dirpath, f), ln)
+            elif f.endswith((".hip", ".hpp", ".h")):
+                assert "oracle" not in open(os.path.join(dirpath, f)).read().lower(), os.path.join(dirpath, f)
+    bench = open(os.path.join(root, "bench.py")).read()
+    uses = [ln for ln in bench.splitlines() if "import" in ln and "oracle" in ln]
+    assert uses, "bench.py times the oracle as its CPU baseline"
+    body = bench[bench.index("def cpu_baseline_leg"):]
+    nxt = re.search(r"^(def |class |if __name__)", body[1:], flags=re.M)     # the next top-level statement
+    body = body[:nxt.start() + 1] if nxt else body
+    assert all(ln.strip() in body for ln in uses), "the oracle is imported outside the cpu_baseline leg"
