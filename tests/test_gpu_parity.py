@@ -421,6 +421,20 @@ def test_capacity_smaller_than_the_sequence():
     assert (np.array(rep["final_lens"]) == wl.r).all()
 
 
+@pytest.mark.parametrize("G,P", [(4, 3040), (2, 6100), (1, 12250)])
+def test_unit_kernel_at_its_lds_limit(G, P, launch_path):
+    """The longest caches the fused unit kernel takes (48 KiB of logits in LDS beside its static arrays):
+    forced onto that path, it must really be the one that runs, and stay exact."""
+    wl = W["gqa_llama3"].replace(name=f"lds_limit_g{G}", B=1, Hq=G, Hkv=1, P=P, D=12, w=8, r=8, key_scale=1.5)
+    st = harness.make_state(wl, DEV, Lcap=wl.P + wl.D, Tcap=wl.P + wl.D)
+    if launch_path == "unit":
+        assert corm.corm_selected_path(st.desc) == 2
+    del st
+    rep = harness.run_slaved_trajectory(wl, DEV, check_state_every=4)
+    say("report", G, P, {k: v for k, v in rep.items() if k != "final_lens"})
+    assert rep["evicted_total"] > 0
+
+
 def _random_shapes(n, seed=2024):
     """Seeded draw of small workloads across the shapes the interface accepts: odd head counts, every group
     size, both row widths and dtypes, prompts shorter than the window, r on either side of w, thresholds off
