@@ -41,7 +41,11 @@
  *                                                        the window is full iff t - t_first + 1 >= w
  *   score_ring     [B, Hq, w, Tcap]      score_dtype     row (tau-1) mod w holds the scores of step tau,
  *                                                        column = ABSOLUTE position of the key, so rows
- *                                                        never need compaction
+ *                                                        never need compaction.  A step writes the columns
+ *                                                        of the keys live at that step; the columns of keys
+ *                                                        evicted earlier keep what an older query left
+ *                                                        there (nothing reads them); columns of positions
+ *                                                        the sequence has not reached must start at zero
  *   out            [B, Hq, d]            float32
  *   keep           [B, Hkv, Lcap]        uint8           1 = survives; entries >= lens are unspecified
  *   kept_idx       [B, Hkv, Lcap]        int32           old slot of the j-th survivor, ascending

@@ -804,3 +804,18 @@ def test_decode_step_under_hip_graph_capture():
                 assert torch.equal(getattr(a, nm)[bb, h, :l], getattr(b, nm)[bb, h, :l]), (nm, bb, h)
     assert torch.equal(a.ring, b.ring)
     assert int(a.status.item()) == 0 and int(b.status.item()) == 0
+
+
+def test_c_abi_client_without_python(launch_path):
+    """The boundary from a plain C++ process (dlopen + HIP runtime, no torch): a few dozen decode steps
+    checked there against closed forms (c = 0: full attention; c huge: a sliding window of r keys)."""
+    import os
+    import subprocess
+    if launch_path != "split":
+        pytest.skip("the client runs in its own process with the library's own path choice: once is enough")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = os.path.join(root, "tests", "abi_client", "abi_client")
+    assert os.path.exists(exe), "tests/abi_client/abi_client is built by __graft_entry__.build()"
+    res = subprocess.run([exe, corm.LIB_PATH], capture_output=True, text=True, timeout=120)
+    say("abi_client", res.returncode, res.stdout[-400:], res.stderr[-200:])
+    assert res.returncode == 0 and "all checks passed" in res.stdout
