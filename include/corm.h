@@ -44,8 +44,9 @@
  *                                                        never need compaction.  A step writes the columns
  *                                                        of the keys live at that step; the columns of keys
  *                                                        evicted earlier keep what an older query left
- *                                                        there (nothing reads them); columns of positions
- *                                                        the sequence has not reached must start at zero
+ *                                                        there, and columns of positions a row's query
+ *                                                        had not reached hold whatever the buffer held:
+ *                                                        no call reads either
  *   out            [B, Hq, d]            float32
  *   keep           [B, Hkv, Lcap]        uint8           1 = survives; entries >= lens are unspecified
  *   kept_idx       [B, Hkv, Lcap]        int32           old slot of the j-th survivor, ascending
