@@ -819,3 +819,22 @@ def test_c_abi_client_without_python(launch_path):
     res = subprocess.run([exe, corm.LIB_PATH], capture_output=True, text=True, timeout=120)
     say("abi_client", res.returncode, res.stdout[-400:], res.stderr[-200:])
     assert res.returncode == 0 and "all checks passed" in res.stdout
+
+
+@pytest.mark.parametrize("score_dtype", [None, "bit"])
+def test_ring_needs_no_initialisation(score_dtype, monkeypatch):
+    """No call reads a ring column it did not write for a query of the current window: a ring that starts
+    out full of ones (every entry 'important') gives the same trajectory, the literal mask included."""
+    wl = W["tiny_f32"].replace(B=2, Hq=4, Hkv=2, P=150, D=30, w=12, r=5)
+    make = harness.make_state
+
+    def dirty(*a, **kw):
+        st = make(*a, **kw)
+        st.ring.fill_(-1 if st.ring_bits else 1.0)
+        return st
+
+    monkeypatch.setattr(harness, "make_state", dirty)
+    say("dirty ring", score_dtype)
+    rep = harness.run_slaved_trajectory(wl, DEV, check_state_every=2, score_dtype=score_dtype, use_split_calls=True)
+    rep2 = harness.run_slaved_trajectory(wl, DEV, check_state_every=2, score_dtype=score_dtype)
+    assert rep["evicted_total"] > 0 and rep["final_lens"] == rep2["final_lens"]
