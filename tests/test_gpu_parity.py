@@ -837,4 +837,5 @@ def test_ring_needs_no_initialisation(score_dtype, monkeypatch):
     say("dirty ring", score_dtype)
     rep = harness.run_slaved_trajectory(wl, DEV, check_state_every=2, score_dtype=score_dtype, use_split_calls=True)
     rep2 = harness.run_slaved_trajectory(wl, DEV, check_state_every=2, score_dtype=score_dtype)
-    assert rep["evicted_total"] > 0 and rep["final_lens"] == rep2["final_lens"]
+    rep3 = harness.run_slaved_trajectory(wl, DEV, check_state_every=2, score_dtype=score_dtype, seed_kernel=True)
+    assert rep["evicted_total"] > 0 and rep["final_lens"] == rep2["final_lens"] == rep3["final_lens"]
