@@ -839,3 +839,26 @@ def test_ring_needs_no_initialisation(score_dtype, monkeypatch):
     rep2 = harness.run_slaved_trajectory(wl, DEV, check_state_every=2, score_dtype=score_dtype)
     rep3 = harness.run_slaved_trajectory(wl, DEV, check_state_every=2, score_dtype=score_dtype, seed_kernel=True)
     assert rep["evicted_total"] > 0 and rep["final_lens"] == rep2["final_lens"] == rep3["final_lens"]
+
+
+@pytest.mark.parametrize("mode", ["exact", "lazy", "seeded"])
+def test_slots_beyond_lens_are_never_read(mode, monkeypatch):
+    """Slots at or above lens hold unspecified data: caches that start out full of NaN rows (and junk
+    positions and hit records) give the same trajectory -- a NaN that reached a dot product, even with
+    weight zero, would poison out."""
+    wl = W["llama7b_1layer"].replace(B=2, Hq=4, Hkv=2, P=530, D=30, w=16, r=6, key_scale=1.5)
+    make = harness.make_state
+
+    def dirty(*a, **kw):
+        st = make(*a, **kw)
+        st.K.fill_(float("nan"))
+        st.V.fill_(float("nan"))
+        st.pos.fill_(-7)
+        st.last_hit.fill_(12345)
+        return st
+
+    monkeypatch.setattr(harness, "make_state", dirty)
+    say("dirty slots", mode)
+    rep = harness.run_slaved_trajectory(wl, DEV, check_state_every=2, lazy=(1, 4) if mode == "lazy" else None,
+                                        seed_kernel=mode == "seeded")
+    assert rep["evicted_total"] > 0
