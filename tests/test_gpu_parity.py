@@ -844,8 +844,8 @@ def test_ring_needs_no_initialisation(score_dtype, monkeypatch):
 @pytest.mark.parametrize("mode", ["exact", "lazy", "seeded"])
 def test_slots_beyond_lens_are_never_read(mode, monkeypatch):
     """Slots at or above lens hold unspecified data: caches that start out full of NaN rows (and junk
-    positions and hit records) give the same trajectory -- a NaN that reached a dot product, even with
-    weight zero, would poison out."""
+    positions and hit records, and a workspace of junk bytes) give the same trajectory -- a NaN that reached a
+    dot product, even with weight zero, would poison out."""
     wl = W["llama7b_1layer"].replace(B=2, Hq=4, Hkv=2, P=530, D=30, w=16, r=6, key_scale=1.5)
     make = harness.make_state
 
@@ -855,6 +855,8 @@ def test_slots_beyond_lens_are_never_read(mode, monkeypatch):
         st.V.fill_(float("nan"))
         st.pos.fill_(-7)
         st.last_hit.fill_(12345)
+        st.workspace.fill_(0xAB)      # the workspace too: only what corm_workspace_init sets is relied on
+        corm.corm_workspace_init(st.desc, st.workspace)
         return st
 
     monkeypatch.setattr(harness, "make_state", dirty)
