@@ -864,3 +864,60 @@ def test_slots_beyond_lens_are_never_read(mode, monkeypatch):
     rep = harness.run_slaved_trajectory(wl, DEV, check_state_every=2, lazy=(1, 4) if mode == "lazy" else None,
                                         seed_kernel=mode == "seeded")
     assert rep["evicted_total"] > 0
+
+
+@pytest.mark.parametrize("lazy", [False, True])
+def test_layers_round_robin_on_three_streams(lazy):
+    """The benchmark's launch configuration: independent layers dealt round-robin over three streams, one
+    workspace per stream, joined after every step.  Every layer must end bit for bit where it ends when the
+    layers run one after the other on one stream with one workspace."""
+    wl = W["llama7b_b16"].replace(layers=5, B=2, Hq=4, Hkv=4, P=900, D=24, w=48, r=48,
+                                  q_mean_scales=inputs.STRUCTURED_Q_MEAN)
+    n_replay = wl.w
+    xs = [{k: v.to(DEV) for k, v in inputs.make_layer(wl, l, device="cpu").items() if k != "sinks"}
+          for l in range(wl.layers)]
+    tf = torch.full((wl.B,), wl.P - n_replay + 1, dtype=torch.int32, device=DEV)
+    results = []
+    for n_streams in (1, 3):
+        states = [harness.make_state(wl, DEV) for _ in range(wl.layers)]
+        for st, x in zip(states, xs):
+            st.preload(x["K0"][:, :, :wl.P - n_replay], x["V0"][:, :, :wl.P - n_replay])
+        main = torch.cuda.current_stream()
+        streams = [main] + [torch.cuda.Stream() for _ in range(n_streams - 1)]
+        wss = [states[k].workspace for k in range(n_streams)]      # one workspace per stream
+        outs = []
+        torch.cuda.synchronize()
+        for j in range(n_replay + wl.D):
+            t = harness.step_inputs(wl, xs[0], j, n_replay)[3]
+            t_dev = torch.full((wl.B,), t, dtype=torch.int32, device=DEV)   # (on the main stream, before the fork)
+            for s in streams[1:]:
+                s.wait_stream(main)
+            for l, (st, x) in enumerate(zip(states, xs)):
+                k_ = l % n_streams
+                with torch.cuda.stream(streams[k_]):
+                    q, k, v, _ = harness.step_inputs(wl, x, j, n_replay)      # (its copies run on this stream too)
+                    if lazy:
+                        st.step_lazy(q, k, v, t_dev, tf, dead_num=1, dead_den=4, stream=streams[k_], workspace=wss[k_])
+                    else:
+                        corm.corm_decode_step(st.desc, q, k, v, st.K, st.V, st.lens, st.pos, st.last_hit, t_dev, tf,
+                                              st.ring, st.out, st.keep, st.kept_idx, wss[k_], status=st.status,
+                                              stream=streams[k_])
+                t_dev.record_stream(streams[k_])
+            for s in streams[1:]:
+                main.wait_stream(s)
+            outs.append(torch.stack([st.out for st in states]).clone())
+        torch.cuda.synchronize()
+        assert all(int(st.status.item()) == 0 for st in states)
+        snap = []
+        for st in states:
+            lens = st.lens.cpu()
+            used = torch.arange(st.Lcap).view(1, 1, -1) < lens.unsqueeze(-1)
+            snap.append((lens, st.K.cpu() * used.unsqueeze(-1), st.V.cpu() * used.unsqueeze(-1), st.pos.cpu() * used,
+                         st.last_hit.cpu() * used, st.ring.cpu(), st.live.cpu() if lazy else lens))
+        results.append((torch.stack(outs).cpu(), snap))
+        del states
+    assert torch.equal(results[0][0], results[1][0]), "out differs between one and three streams"
+    for l, (a, b) in enumerate(zip(results[0][1], results[1][1])):
+        for i, (u, v) in enumerate(zip(a, b)):
+            assert torch.equal(u, v), ("layer", l, "field", i)
+    assert min(int(s[0].min()) for s in results[0][1]) < wl.P
