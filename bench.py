@@ -329,7 +329,7 @@ def main():
         "n_gpus": 1, "steps": K_steps, "warmup": W_steps, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype, "data": "synthetic",
-        "device": f"{torch.cuda.get_device_name(0)} ({torch.cuda.get_device_properties(0).gcnArchName}, "
+        "device": f"{torch.cuda.get_device_name(0) or 'AMD GPU'} ({torch.cuda.get_device_properties(0).gcnArchName}, "
                   f"{torch.cuda.get_device_properties(0).multi_processor_count} CUs, {total_mem / 2**30:.0f} GiB)",
         "config": {"workload": wl.name + ("+structured_queries" if args.structured else ""),
                    "layers": layers, "batch": B, "q_heads": Hq, "kv_heads": Hkv, "head_dim": d,
