@@ -38,10 +38,41 @@ __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, cons
   // contiguous range of units: unit lengths often follow the head index with a small period (heads differ,
   // sequences less so), and a strided assignment would put all the long units on one or two XCDs, which
   // then finish the launch alone.
+  // Inside an XCD the first 32 workgroups land on its 32 compute units one each and the next 32 join them in
+  // the same order (two workgroups per compute unit), so workgroups i and i + 32 of a block of 64 share a
+  // compute unit and its memory pipeline.  A unit's length is a property of its head, and the same head of
+  // the next sequence sits exactly 32 (or 64, ...) units further on: the plain order pairs like with like, and
+  // the compute units holding two long units finish the launch alone.  Instead every block of 64 units is
+  // ranked by length and the longest is paired with the shortest, the second longest with the second
+  // shortest, and so on.  (A guess at the placement only costs balance, never correctness: the map is a
+  // permutation of the block whatever the hardware does.)
   const int units = p.B * p.Hkv;
   const int per_xcd = (units + UNIT_XCDS - 1) / UNIT_XCDS;
-  const int unit = (int)(blockIdx.x % UNIT_XCDS) * per_xcd + (int)(blockIdx.x / UNIT_XCDS);
-  if (unit >= units) return;
+  constexpr int XCD_CUS = 32, BLK = 2 * XCD_CUS;
+  static_assert(BLK == 64, "one lane of a wave per unit of a block");
+  const int li = (int)(blockIdx.x / UNIT_XCDS);   // index inside the XCD's range
+  const int blk0 = (int)(blockIdx.x % UNIT_XCDS) * per_xcd + (li / BLK) * BLK;   // first unit of the block
+  const int nblk = min(BLK, min(per_xcd - (li / BLK) * BLK, units - blk0));      // units in it
+  const int jblk = li % BLK;
+  if (jblk >= nblk) return;
+  __shared__ int sh_unit;
+  if (threadIdx.x < 64) {
+    const int k = threadIdx.x;
+    int Lk = -1;
+    if (k < nblk) {
+      Lk = p.lens[blk0 + k];
+      Lk = Lk < 0 ? 0 : (Lk > p.Lcap ? p.Lcap : Lk);
+    }
+    int rank = 0;   // units of the block that come before this one: longer, or as long and earlier
+    for (int m = 0; m < BLK; ++m) {
+      const int Lm = __shfl(Lk, m);
+      rank += (Lm > Lk || (Lm == Lk && m < k)) ? 1 : 0;
+    }
+    const int want = jblk < XCD_CUS ? jblk : nblk - 1 - (jblk - XCD_CUS);
+    if (k < nblk && rank == want) sh_unit = blk0 + k;
+  }
+  __syncthreads();
+  const int unit = sh_unit;
   const UnitLen ul = unit_len(p, unit);
   const int L = ul.L;
   const int b = unit / p.Hkv;
