@@ -163,10 +163,11 @@ struct UnitLen {
   int flags;      // CORM_DEV_* conditions seen
 };
 
-__device__ __forceinline__ UnitLen unit_len(const Params& p, int unit) {
+// lens_value: what lens holds for the unit
+__device__ __forceinline__ UnitLen unit_len_of(const Params& p, int lens_value) {
   UnitLen u;
   u.flags = 0;
-  int L0 = p.lens[unit];
+  int L0 = lens_value;
   if (L0 < 0 || L0 > p.Lcap) {
     u.flags |= CORM_DEV_BAD_LENS;
     L0 = L0 < 0 ? 0 : p.Lcap;
@@ -184,6 +185,8 @@ __device__ __forceinline__ UnitLen unit_len(const Params& p, int unit) {
   }
   return u;
 }
+
+__device__ __forceinline__ UnitLen unit_len(const Params& p, int unit) { return unit_len_of(p, p.lens[unit]); }
 
 // ---------------------------------------------------------------- boolean message (bit ring)
 //

@@ -44,8 +44,9 @@ __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, cons
   // the next sequence sits exactly 32 (or 64, ...) units further on: the plain order pairs like with like, and
   // the compute units holding two long units finish the launch alone.  Instead every block of 64 units is
   // ranked by length and the longest is paired with the shortest, the second longest with the second
-  // shortest, and so on.  (A guess at the placement only costs balance, never correctness: the map is a
-  // permutation of the block whatever the hardware does.)
+  // shortest, and so on -- unless the block's lengths differ by less than an eighth, where there is nothing
+  // to balance.  (A guess at the placement only costs balance, never correctness: the map is a permutation
+  // of the block whatever the hardware does.)
   const int units = p.B * p.Hkv;
   const int per_xcd = (units + UNIT_XCDS - 1) / UNIT_XCDS;
   constexpr int XCD_CUS = 32, BLK = 2 * XCD_CUS;
@@ -55,25 +56,39 @@ __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, cons
   const int nblk = min(BLK, min(per_xcd - (li / BLK) * BLK, units - blk0));      // units in it
   const int jblk = li % BLK;
   if (jblk >= nblk) return;
-  __shared__ int sh_unit;
-  if (threadIdx.x < 64) {
+  __shared__ int sh_unit, sh_lens;
+  if (threadIdx.x < 64) {   // one wave, one unit of the block per lane
     const int k = threadIdx.x;
-    int Lk = -1;
+    int Lk = -1, raw = 0;
     if (k < nblk) {
-      Lk = p.lens[blk0 + k];
-      Lk = Lk < 0 ? 0 : (Lk > p.Lcap ? p.Lcap : Lk);
+      raw = p.lens[blk0 + k];
+      Lk = raw < 0 ? 0 : (raw > p.Lcap ? p.Lcap : raw);
     }
-    int rank = 0;   // units of the block that come before this one: longer, or as long and earlier
-    for (int m = 0; m < BLK; ++m) {
-      const int Lm = __shfl(Lk, m);
-      rank += (Lm > Lk || (Lm == Lk && m < k)) ? 1 : 0;
+    int lmax = Lk, lmin = k < nblk ? Lk : 0x7fffffff;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      lmax = max(lmax, __shfl_xor(lmax, o));
+      lmin = min(lmin, __shfl_xor(lmin, o));
     }
-    const int want = jblk < XCD_CUS ? jblk : nblk - 1 - (jblk - XCD_CUS);
-    if (k < nblk && rank == want) sh_unit = blk0 + k;
+    // A block of (nearly) equal lengths keeps the plain order: there is nothing to balance there.
+    int rank = k, want = jblk;
+    if ((lmax - lmin) * 8 > lmax) {   // (uniform)
+      rank = 0;   // units of the block that come before this one: longer, or as long and earlier
+      for (int m = 0; m < BLK; ++m) {
+        const int Lm = __shfl(Lk, m);
+        rank += (Lm > Lk || (Lm == Lk && m < k)) ? 1 : 0;
+      }
+      want = jblk < XCD_CUS ? jblk : nblk - 1 - (jblk - XCD_CUS);
+    }
+    if (k < nblk && rank == want) {   // exactly one lane
+      sh_unit = blk0 + k;
+      sh_lens = raw;
+    }
   }
   __syncthreads();
-  const int unit = sh_unit;
-  const UnitLen ul = unit_len(p, unit);
+  // (the same for every thread; said so explicitly, or the K and V descriptors would count as divergent)
+  const int unit = __builtin_amdgcn_readfirstlane(sh_unit);
+  const UnitLen ul = unit_len_of(p, __builtin_amdgcn_readfirstlane(sh_lens));
   const int L = ul.L;
   const int b = unit / p.Hkv;
   const int hkv = unit - b * p.Hkv;
