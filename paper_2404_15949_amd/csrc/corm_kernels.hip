@@ -269,7 +269,11 @@ int corm_prefill_seed(const corm_desc* desc, const void* q_tail, int32_t m, void
   a.thr_scale = desc->thr_scale;
   a.scale_log2 = (desc->sm_scale > 0.f ? desc->sm_scale : 1.0f / sqrtf((float)desc->d)) * LOG2E;
   const int units = desc->B * desc->Hkv;
-  const dim3 grid(wl.seed_nkb, units), mgrid((m + 255) / 256, desc->B * desc->Hq);
+  a.units = units;
+  if ((long long)PREFILL_XCDS * ((units + PREFILL_XCDS - 1) / PREFILL_XCDS) * wl.seed_nkb > 2147483647LL)
+    return CORM_EUNSUPPORTED;
+  const dim3 grid((unsigned)(PREFILL_XCDS * ((units + PREFILL_XCDS - 1) / PREFILL_XCDS) * wl.seed_nkb));
+  const dim3 mgrid((m + 255) / 256, desc->B * desc->Hq);
   if (a.ring_bits && score_ring) {
     hipLaunchKernelGGL(corm_prefill_clear_bits_kernel, dim3((m + 15) / 16, desc->B * desc->Hq), dim3(256), 0, s, a);
     if (launch_status()) return CORM_EHIP;

@@ -23,6 +23,8 @@ namespace {
 // operand in the same layout, read from LDS, where the workgroup stages the queries in double-buffered
 // blocks.  D: lane l holds query l%16, keys 4*(l/16) .. +3 of the tile.
 
+constexpr int PREFILL_XCDS = 8;   // accelerator dies of the device
+
 struct PrefillArgs {
   const void* q_tail;   // [B, Hq, m, d]
   const void* K;
@@ -35,6 +37,7 @@ struct PrefillArgs {
   float4* stats;   // [B*Hq, w]       (max, 1/sum, threshold of the query's step, unused)
   int32_t* status;
   int32_t Hq, Hkv, Lcap, Tcap, w, m, nkb, ring_bf16;
+  int32_t units;                   // B * Hkv
   int32_t ring_bits, ring_words;   // boolean message: one bit per (row, position), words per row
   float thr_scale, scale_log2;
 };
@@ -136,7 +139,14 @@ __device__ __forceinline__ void prefill_pass(const PrefillArgs& a) {
   constexpr int NCH = Geo::NCH, T = Geo::T, KB = Geo::KB;
   constexpr int NEVER = 0x7fffffff;   // position of a slot that holds no key: visible to no query
 
-  const int kb = blockIdx.x, unit = blockIdx.y;
+  // One-dimensional grid of 8 * ceil(units / 8) * nkb workgroups.  Workgroups are dealt round-robin to the 8
+  // XCDs, so id % 8 names the XCD; each XCD takes a contiguous range of units and runs the key blocks of a unit
+  // one after the other: they all read the same tail queries, which then stay in that XCD's L2.
+  const int per_xcd = (a.units + PREFILL_XCDS - 1) / PREFILL_XCDS;
+  const int li = (int)(blockIdx.x / PREFILL_XCDS);
+  const int unit = (int)(blockIdx.x % PREFILL_XCDS) * per_xcd + li / a.nkb;
+  const int kb = li % a.nkb;
+  if (li / a.nkb >= per_xcd || unit >= a.units) return;
   const int b = unit / a.Hkv, hkv = unit - b * a.Hkv;
   const int G = a.Hq / a.Hkv;
   int L = a.lens[unit];
