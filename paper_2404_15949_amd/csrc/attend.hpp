@@ -35,13 +35,13 @@ constexpr uint32_t DEAD_OFFSET = 0x7ffffff0u;
 // probabilities vanish against a sum that is >= 1)
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-template <typename DT, int D, int G, int NW>
+template <typename DT, int D, int G, int NW, int UU = UNROLL>
 struct Attend {
   static constexpr int EPL = DT::EPL;
   static constexpr int ROWB = D * DT::ESZ;
   static constexpr int LPR = ROWB / 16;   // lanes per row
   static constexpr int RPL = 64 / LPR;    // rows per wave-wide load
-  static constexpr int U = UNROLL;
+  static constexpr int U = UU;          // 16-byte K loads (and V loads) per lane and pipeline stage
   static constexpr int LOAD_ROWS = NW * RPL;          // consecutive rows one unrolled load of the workgroup covers
   static constexpr int STAGE_ROWS = LOAD_ROWS * U;    // rows one pipeline stage of the workgroup covers
   static_assert(U <= LPR, "logit store uses one lane per unrolled load");

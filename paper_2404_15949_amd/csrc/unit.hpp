@@ -19,9 +19,14 @@ constexpr int UNIT_XCDS = 8;         // accelerator dies of the device; the grid
 constexpr int UNIT_MAX_TILES = 24;   // 48 KiB of logits hold at most 12288 slots = 24 tiles of 512
 static_assert(UNIT_WG == CHUNK, "the unit kernel reports survivors per CHUNK slots, one tile each");
 
-template <typename DT, int D, int G, bool LAZY>
+// UU: 16-byte K (and V) loads per lane and pipeline stage.  UNROLL for one query head per KV head.  Grouped
+// queries have two instances: UNROLL (146-224 registers: one workgroup per compute unit, deep stages) for
+// launches that have about one unit per compute unit anyway, and a small stage (UNROLL / G) that keeps the G
+// accumulator sets and two stages within 128 registers, so that two workgroups share a compute unit, for
+// launches with at least two units per compute unit.
+template <typename DT, int D, int G, bool LAZY, int UU>
 __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, const int lstride) {
-  using A = Attend<DT, D, G, UNIT_WAVES>;
+  using A = Attend<DT, D, G, UNIT_WAVES, UU>;
   constexpr int EPL = A::EPL, ROWB = A::ROWB, LPR = A::LPR, RPL = A::RPL;
 
   extern __shared__ float sh_logit[];   // [G][lstride] raw logits of the unit (log2 domain)

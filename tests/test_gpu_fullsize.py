@@ -318,3 +318,21 @@ def test_config3_structured_lazy_steps():
     say("evicted", evicted, "compactions", compactions, "slots in use", sum(used[u] for u in units),
         "live", sum(oracles[u].l for u in units))
     assert evicted > 0
+
+
+# ------------------------------------------------------------------ grouped queries on the fused unit kernel
+
+@pytest.mark.parametrize("G", [2, 4])
+@pytest.mark.parametrize("lazy", [None, (1, 4)])
+def test_grouped_queries_with_many_units(G, lazy):
+    """At two or more units per compute unit the grouped-query unit kernel runs its small-stage instance
+    (two workgroups per compute unit): 512 units, whole trajectories of a sample of them, exact and deferred."""
+    wl = W["gqa_llama3"].replace(name=f"gqa_many_units_g{G}", B=64, Hq=8 * G, Hkv=8, P=640, D=16, w=24, r=24,
+                                 key_scale=1.5, q_mean_scales=(0.0, 2.0, 3.0))
+    st = harness.make_state(wl, DEV)
+    assert corm.corm_selected_path(st.desc) == 2
+    del st
+    units = sorted(set(_sample_units(wl, 24, seed=30 + G)) | {(0, 0), (wl.B - 1, wl.Hkv - 1)})
+    rep = harness.run_slaved_trajectory(wl, DEV, check_state_every=5, units=units, lazy=lazy)
+    say("report", G, lazy, {k: v for k, v in rep.items() if k != "final_lens"})
+    assert rep["evicted_total"] > 0
