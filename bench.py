@@ -34,7 +34,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=256)
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="llama7b_b16")
-    ap.add_argument("--layers", type=int, default=None, help="override the number of layers (development only)")
+    ap.add_argument("--layers", type=int, default=None, help="override the number of layers: a stack of layers of the workload's shape (the one-layer workloads as "
+                    "a model with that many layers would run them), or fewer layers for short counter runs")
     ap.add_argument("--structured", action="store_true",
                     help="supplementary variant: per-head query means so that eviction happens at w >= 256")
     ap.add_argument("--w", type=int, default=None, help="override the window of recorded queries (the paper's w/r "
