@@ -336,3 +336,39 @@ def test_grouped_queries_with_many_units(G, lazy):
     rep = harness.run_slaved_trajectory(wl, DEV, check_state_every=5, units=units, lazy=lazy)
     say("report", G, lazy, {k: v for k, v in rep.items() if k != "final_lens"})
     assert rep["evicted_total"] > 0
+
+
+@pytest.mark.parametrize("B,Hkv", [(75, 4), (65, 8), (33, 8)])
+def test_unit_kernel_pairs_units_of_partial_blocks(B, Hkv):
+    """The unit kernel ranks blocks of 64 units by length and pairs long with short ones; unit counts that leave
+    partial blocks (38, 65 and 33 units per XCD here) and diverging lengths: every unit must still be served
+    exactly once -- a unit served twice or not at all shows in its cache, checked on a sample and, for lens, on
+    all units."""
+    wl = W["llama7b_1layer"].replace(name=f"partial_blocks_{B}x{Hkv}", B=B, Hq=Hkv, Hkv=Hkv, P=700, D=10, w=32, r=32,
+                                     key_scale=1.5, q_mean_scales=(0.0, 2.0, 3.0, 5.0))
+    n_replay = wl.w
+    units = sorted(set(_sample_units(wl, 30, seed=B)) | {(0, 0), (B - 1, Hkv - 1)})
+    lens = _run(wl, 0, 10, {n_replay + 3, n_replay + 9}, units, expect_path=2, expect_evictions=True)
+    assert lens.max() - lens.min() > 100          # ragged: the ranked order is in use
+    assert (lens >= wl.r).all() and (lens <= wl.P + 10).all()
+    # every unit, every step: out is rewritten and exactly one key (the step's own) is appended
+    x = inputs.make_layer(wl, 0, device=DEV, n_decode=6, n_replay=n_replay)
+    st = harness.make_state(wl, DEV, Lcap=wl.P + 6, Tcap=wl.P + 6)
+    st.preload(x["K0"], x["V0"])
+    t = torch.full((B,), wl.P, dtype=torch.int32, device=DEV)
+    tf = torch.zeros_like(t)
+    st.prefill_seed(x["Q"][:n_replay].permute(1, 2, 0, 3).contiguous(), t, tf)
+    for j in range(6):
+        q, k, v, tt = harness.step_inputs(wl, x, n_replay + j, n_replay)
+        before = st.lens.clone()
+        st.out.fill_(float("nan"))
+        st.step(q, k, v, torch.full((B,), tt, dtype=torch.int32, device=DEV), tf)
+        torch.cuda.synchronize()
+        assert torch.isfinite(st.out).all(), ("a unit was not served", j)
+        after = st.lens
+        assert (after <= before + 1).all() and (after >= wl.r).all(), ("lens", j)
+        newest = st.pos.gather(2, (after.long() - 1).unsqueeze(-1)).squeeze(-1)
+        assert (newest == tt - 1).all(), ("the step's key is not the newest of every unit", j)
+        second = st.pos.gather(2, (after.long() - 2).unsqueeze(-1)).squeeze(-1)
+        assert (second == tt - 2).all(), ("a unit appended twice or skipped a step", j)
+    assert int(st.status.item()) == 0
