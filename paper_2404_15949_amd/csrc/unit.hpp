@@ -191,7 +191,7 @@ __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, cons
   for (int kt = 0; kt < UNIT_MAX_TILES; ++kt) {
     pos_r[kt] = 0;
     lh_r[kt] = 0;
-    if (kt * UNIT_WG < L) {   // uniform over the workgroup
+    if (kt * UNIT_WG < L && !p.ring_bits) {   // uniform over the workgroup (the bit-ring loop loads its own)
       const int in = min(kt * UNIT_WG + tid, L - 1);
       pos_r[kt] = posb[in];
       lh_r[kt] = lhb[in];
@@ -261,12 +261,19 @@ __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, cons
   // Boolean message (score_dtype CORM_BIT): a plain loop of its own, so that the unrolled loop below
   // keeps its register budget.  The fp32 score itself is compared; bits are set wave by wave.
   if (p.ring_bits) {
+    // (rolled, so the metadata of the next tile is requested while the current one is worked on: the loop
+    // must not pay one memory latency per tile)
+    int pos_nx = posb[min(tid, L - 1)], lh_nx = lhb[min(tid, L - 1)];
 #pragma unroll 1
     for (int tile = 0; tile < L; tile += UNIT_WG) {
       const int i = tile + tid;
       const bool live = i < L && (!LAZY || ((sh_live[i >> 6] >> (i & 63)) & 1ull));
-      const int my_pos = posb[min(i, L - 1)];
-      int lh = lhb[min(i, L - 1)];
+      const int my_pos = pos_nx;
+      int lh = lh_nx;
+      if (tile + UNIT_WG < L) {   // (uniform; slots of the next tile: nobody writes them in this one)
+        pos_nx = posb[min(i + UNIT_WG, L - 1)];
+        lh_nx = lhb[min(i + UNIT_WG, L - 1)];
+      }
       const bool pos_ok = live && my_pos >= 0 && my_pos < p.Tcap;
       if (live && !pos_ok && p.status) atomicOr(p.status, CORM_DEV_BAD_STEP);
       bool hit = false;
