@@ -106,6 +106,27 @@ def test_scores_not_transposed_or_unscaled():
     np.testing.assert_allclose(a, [0, 0, .5, 0, 0, 0, .5, 0], atol=1e-300)
 
 
+def test_parallel_queries_rank_keys_alike():
+    """Section 3.2 (the equation after the cosine similarity): a query that is a positive multiple of
+    another gives every key the same rank; the multiple only sharpens or flattens the distribution, and
+    a negative multiple reverses the order."""
+    rng = np.random.default_rng(8)
+    q = rng.standard_normal(64)
+    K = rng.standard_normal((200, 64))
+    base = O.attention_scores(q, K)
+    for m in (0.25, 3.0, 17.0):
+        a = O.attention_scores(m * q, K)
+        assert np.array_equal(np.argsort(a, kind="stable"), np.argsort(base, kind="stable"))
+        assert (a.max() > base.max()) == (m > 1.0)        # a larger multiple concentrates the scores
+    rev = O.attention_scores(-2.0 * q, K)
+    assert np.array_equal(np.argsort(rev, kind="stable"), np.argsort(base, kind="stable")[::-1])
+    # what is important (Def. 3.1) to the flatter query stays at the top of the sharper one's ranking
+    t = 200
+    imp = O.important(O.round_to_storage(base, "f32"), t)
+    top = np.argsort(O.attention_scores(3.0 * q, K))[::-1][:int(imp.sum())]
+    assert set(top.tolist()) == set(np.flatnonzero(imp).tolist())
+
+
 def test_zero_query_gives_uniform_scores_and_mean_value():
     rng = np.random.default_rng(2)
     K = rng.standard_normal((37, 64)); V = rng.standard_normal((37, 64))
