@@ -392,7 +392,8 @@ def cpu_baseline_leg(args, wl, states, Qs, Kns, Vns, n_replay, pre, layers, kv_o
     from oracle.snapshot import unit_from_device_arrays
 
     rng = np.random.default_rng(0)
-    n_units, n_steps = args.cpu_units, args.cpu_steps
+    # (no more oracle steps than decode inputs were generated: a short --steps / --warmup run has few)
+    n_units, n_steps = args.cpu_units, max(1, min(args.cpu_steps, Kns[0].shape[0] - (n_replay - kv_off)))
     G = wl.G
     picks = [(int(rng.integers(layers)), int(rng.integers(wl.B)), int(rng.integers(wl.Hkv))) for _ in range(n_units)]
     t_prev = wl.P

@@ -921,3 +921,32 @@ def test_layers_round_robin_on_three_streams(lazy):
         for i, (u, v) in enumerate(zip(a, b)):
             assert torch.equal(u, v), ("layer", l, "field", i)
     assert min(int(s[0].min()) for s in results[0][1]) < wl.P
+
+
+def test_bench_prints_one_json_line_with_the_required_fields(launch_path):
+    """bench.py on the smallest workload with a short step count: the last line of stdout is one JSON object
+    with the fields the driver reads, the roofline and the CPU-baseline objects included."""
+    import json
+    import os
+    import subprocess
+    if launch_path != "split":
+        pytest.skip("a process of its own: once is enough")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--workload", "tiny_f32", "--steps", "3",
+                          "--warmup", "1", "--cpu-units", "4"], capture_output=True, text=True, timeout=280)
+    assert res.returncode == 0, res.stderr[-600:]
+    lines = [ln for ln in res.stdout.splitlines() if ln.strip()]
+    assert len(lines) == 1
+    r = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert key in r, key
+    assert r["n_gpus"] == 1 and r["steps"] == 3 and r["warmup"] == 1 and r["value"] > 0 and r["vs_baseline"] is None
+    assert r["config"]["workload"] == "tiny_f32" and r["dtype"] == "f32" and r["data"] == "synthetic"
+    for key in ("bound", "achieved", "peak", "unit", "frac", "traffic"):
+        assert key in r["roofline"], key
+    assert r["roofline"]["bound"] == "hbm" and r["roofline"]["peak"] == 8000.0
+    assert abs(r["roofline"]["frac"] - r["roofline"]["achieved"] / r["roofline"]["peak"]) < 1e-9
+    for key in ("value", "unit", "cores", "kind", "sample"):
+        assert key in r["cpu_baseline"], key
+    assert r["cpu_baseline"]["kind"] == "oracle" and r["cpu_baseline"]["value"] > 0
