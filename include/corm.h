@@ -24,6 +24,9 @@
  * detected on the host before anything is launched.  Conditions only the device can see
  * (a full unit, a step beyond the ring's columns) never fault: the kernel skips the offending
  * write and ORs a bit into the optional `status` word.
+ * Calls that overlap in time (other streams, other host threads) need a workspace each and must not share
+ * any array a call writes; beyond that the library keeps no state, except the two process-wide knobs at
+ * the end of this header (corm_force_path, corm_profile_attend), which are not thread safe.
  *
  * Layouts (row-major, sizes in elements)
  *   q              [B, Hq, d]            kv_dtype        query of the current token per head
