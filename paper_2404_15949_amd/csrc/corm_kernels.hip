@@ -253,6 +253,7 @@ int corm_prefill_seed(const corm_desc* desc, const void* q_tail, int32_t m, void
       misaligned4(kept_idx) || misaligned4(status))
     return CORM_EINVAL;
   if (m < 1 || m > desc->w) return CORM_EINVAL;
+  if ((m + 15) / 16 > 65535) return CORM_EUNSUPPORTED;   // grid rows of the clear / merge launches
   WorkspaceLayout wl;
   rc = check_workspace(desc, workspace, workspace_bytes, &wl);
   if (rc) return rc;
@@ -273,9 +274,9 @@ int corm_prefill_seed(const corm_desc* desc, const void* q_tail, int32_t m, void
   if ((long long)PREFILL_XCDS * ((units + PREFILL_XCDS - 1) / PREFILL_XCDS) * wl.seed_nkb > 2147483647LL)
     return CORM_EUNSUPPORTED;
   const dim3 grid((unsigned)(PREFILL_XCDS * ((units + PREFILL_XCDS - 1) / PREFILL_XCDS) * wl.seed_nkb));
-  const dim3 mgrid((m + 255) / 256, desc->B * desc->Hq);
+  const dim3 mgrid(desc->B * desc->Hq, (m + 255) / 256);
   if (a.ring_bits && score_ring) {
-    hipLaunchKernelGGL(corm_prefill_clear_bits_kernel, dim3((m + 15) / 16, desc->B * desc->Hq), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(corm_prefill_clear_bits_kernel, dim3(desc->B * desc->Hq, (m + 15) / 16), dim3(256), 0, s, a);
     if (launch_status()) return CORM_EHIP;
   }
   if (desc->kv_dtype == CORM_F32)

@@ -450,13 +450,13 @@ __global__ __launch_bounds__(WG) void corm_prefill_scores_kernel(const PrefillAr
 // boolean message: zero the words of the rows of steps tau_0 .. tau_{m-1} that pass 2 may set bits in
 // (positions < tau); workgroup = 16 rows of one head
 __global__ __launch_bounds__(256) void corm_prefill_clear_bits_kernel(const PrefillArgs a) {
-  const int head = blockIdx.y;
+  const int head = blockIdx.x;   // (heads in x: B * Hq may exceed the 65535 rows a grid has in y)
   const int tcur = a.t[head / a.Hq];
   const int tau0 = tcur - a.m + 1;
   if (tau0 < 1 || tcur > a.Tcap) return;
   const int s0 = (tau0 - 1) % a.w;
   for (int jr = 0; jr < 16; ++jr) {
-    const int j = blockIdx.x * 16 + jr;
+    const int j = blockIdx.y * 16 + jr;
     if (j >= a.m) break;
     int slot = s0 + j;
     if (slot >= a.w) slot -= a.w;
@@ -468,8 +468,8 @@ __global__ __launch_bounds__(256) void corm_prefill_clear_bits_kernel(const Pref
 
 // per query: max and 1/sum over the key blocks of its unit
 __global__ __launch_bounds__(256) void corm_prefill_merge_kernel(const PrefillArgs a, const int KB) {
-  const int head = blockIdx.y;
-  const int j = blockIdx.x * 256 + threadIdx.x;
+  const int head = blockIdx.x;   // (heads in x: B * Hq may exceed the 65535 rows a grid has in y)
+  const int j = blockIdx.y * 256 + threadIdx.x;
   if (j >= a.m) return;
   const int unit = (head / a.Hq) * a.Hkv + (head % a.Hq) / (a.Hq / a.Hkv);
   int L = a.lens[unit];

@@ -372,3 +372,13 @@ def test_unit_kernel_pairs_units_of_partial_blocks(B, Hkv):
         second = st.pos.gather(2, (after.long() - 2).unsqueeze(-1)).squeeze(-1)
         assert (second == tt - 2).all(), ("a unit appended twice or skipped a step", j)
     assert int(st.status.item()) == 0
+
+
+def test_more_query_heads_than_grid_rows():
+    """131072 query heads (4096 sequences x 32 heads, 8 KV heads): more than the 65535 rows a launch grid has in
+    its second dimension; seeded by the dense call, then decoded, on a sample of units."""
+    wl = W["gqa_llama3"].replace(name="many_heads", B=4096, Hq=32, Hkv=8, P=40, D=6, w=8, r=4, key_scale=2.0)
+    units = sorted(set(_sample_units(wl, 30, seed=41)) | {(0, 0), (wl.B - 1, wl.Hkv - 1)})
+    rep = harness.run_slaved_trajectory(wl, DEV, check_state_every=2, units=units, seed_kernel=True)
+    say("report", {k: v for k, v in rep.items() if k != "final_lens"})
+    assert rep["evicted_total"] > 0
