@@ -14,9 +14,12 @@ What each function follows in the paper (arXiv 2404.15949):
 * ``attention_output``      Eq. (1): softmax(q K^T / sqrt(d_h)) V for one query.
 * ``importance_threshold``  Def. 3.1: a key is important at step t iff its score >= 1/t.
 * ``important``             Def. 3.1 applied to the scores as they are stored.
-* ``corm_eviction``         Algorithm 1 (Section 4.2), extended to a query group (Section 5.3).
-* ``keep_from_score_window``Def. 4.1 plus the recent-r protection of Section 4.2 "Approach".
-* ``stable_compact``        the ``nonzero`` / gather of Algorithm 1.
+* ``note_of_query``         Section 4.2 "Approach": per query, the keys it considers important.
+* ``long_term_minor``       Def. 4.1, extended to a query group (Section 5.3).
+* ``survivors``             the decision of Section 4.2 / Algorithm 1: window of w queries, r newest keys kept.
+* ``UnitCache.step``        one step of Algorithm 1 around Eq. (1), (2): append, attend, note, decide, gather.
+* ``keep_from_score_window``Def. 4.1 plus the recent-r protection, straight from a window of stored scores.
+* ``stable_compact``        the ascending index list of Algorithm 1's gather.
 
 Readings taken where the paper is silent or inconsistent (each is listed in
 the design notes of this repository):
@@ -24,8 +27,9 @@ the design notes of this repository):
 * Algorithm 1 concatenates the new message row along the *row* axis (the
   listing says dim=1, which cannot work for [m,l] and [1,l]; the row count test
   and the docstring shapes show rows are meant).
-* After the gather the message columns are gathered with the same indices,
-  otherwise the next call's shapes do not match.
+* The listing returns the message with its old column count although the cache
+  has shrunk; the columns must follow the keys.  Here a note is addressed by the
+  key's absolute position instead, so nothing has to follow anything.
 * ``t`` is the 1-based position of the current query in its sequence (tokens
   seen so far), not the live cache length.
 * The comparison is inclusive (>=), done in fp32 on the score as stored, against
@@ -37,7 +41,7 @@ the design notes of this repository):
 
 Parity status: every function here is pinned by tests/test_oracle_pins.py
 (closed forms, library softmax, brute-force subset enumeration, independent
-reformulations).  The paper's quality tables need its datasets and weights and
+reformulations, a hand-derived trace).  The paper's quality tables need its datasets and weights and
 are not reproduced: those numbers are "parity unpinned".
 """
 from __future__ import annotations
@@ -115,41 +119,53 @@ def important_fraction(stored_scores: np.ndarray, t: int, c: float = 1.0) -> flo
 
 
 # --------------------------------------------------------------------------
-# Algorithm 1
+# Section 4.2: the recent message, Def. 4.1, the eviction decision
 
 
-def stable_compact(decision: np.ndarray) -> np.ndarray:
-    """Ascending indices of the kept slots (``nonzero`` of Algorithm 1); always 1-D."""
-    return np.flatnonzero(np.asarray(decision, dtype=bool))
+def stable_compact(keep: np.ndarray) -> np.ndarray:
+    """Ascending slots of the kept keys (what Algorithm 1's index list holds); always 1-D."""
+    return np.flatnonzero(np.asarray(keep, dtype=bool))
 
 
-def corm_eviction(keys, values, message, attn_score, w: int, r: int, t: int, c: float = 1.0):
-    """One call of Algorithm 1 for one KV head and its group of G query heads.
+def note_of_query(stored_scores: np.ndarray, positions: np.ndarray, t: int, width: int,
+                  c: float = 1.0) -> np.ndarray:
+    """What Section 4.2 records for the query of step t: the keys it considers important.
 
-    keys, values : [l, d]   cache including the current token
-    message      : [m, G, l-1] bool, the recorded importance rows (m <= w)
-    attn_score   : [G, l]   the current step's scores *as stored* (fp32 or bf16 values)
-    Returns (keys', values', message', indices) where indices are the kept old slots.
+    stored_scores [G, l] for the live keys, whose absolute positions are ``positions`` [l].
+    Returns bool [G, width] over ABSOLUTE positions: True where head g found the key at that
+    position important (Def. 3.1).  Every position the query did not see -- evicted earlier,
+    or not yet in the sequence -- is False, i.e. minor.
+    """
+    found = np.zeros((stored_scores.shape[0], width), dtype=bool)
+    found[:, positions] = important(stored_scores, t, c)
+    return found
+
+
+def long_term_minor(notes: np.ndarray, positions: np.ndarray) -> np.ndarray:
+    """Def. 4.1 for every live key, extended to a query group (Section 5.3).
+
+    notes [n, G, width]: the notes of the n most recent queries (see ``note_of_query``).
+    A key is a long-term minor key iff no head of its group found it important in any of them.
+    """
+    found_by_someone = notes[:, :, positions].any(axis=(0, 1))
+    return ~found_by_someone
+
+
+def survivors(notes: np.ndarray, positions: np.ndarray, w: int, r: int) -> np.ndarray:
+    """The eviction decision of Section 4.2 for the live keys (ascending slots): bool [l], True = stays.
+
+    Nothing goes before w queries have been observed.  After that a key goes as soon as it is a
+    long-term minor key of the last w queries -- except the keys in the r newest slots, which stay
+    whatever the notes say (too few observations of them yet).
     """
     if r < 1 or w < 1:
         raise ValueError("w and r must be >= 1")
-    l = keys.shape[0]
-    m, G = message.shape[0], message.shape[1]
-    assert message.shape[2] == l - 1 and attn_score.shape == (G, l)
-
-    # update attention message: the new key did not exist in older rows -> minor there
-    message = np.concatenate([message, np.zeros((m, G, 1), dtype=bool)], axis=2)
-    cur_message = important(attn_score, t, c)
-    message = np.concatenate([message, cur_message[None]], axis=0)[-w:]
-
-    if message.shape[0] < w:
-        return keys, values, message, np.arange(l)
-
-    # long-term minor keys: minor for every head of the group in every recorded row
-    decision = message.any(axis=(0, 1))
-    decision[-r:] = True          # always keep the r most recent slots
-    indices = stable_compact(decision)
-    return keys[indices], values[indices], message[:, :, indices], indices
+    l = len(positions)
+    if notes.shape[0] < w:
+        return np.ones(l, dtype=bool)
+    stays = ~long_term_minor(notes[notes.shape[0] - w:], positions)
+    stays[max(l - r, 0):] = True
+    return stays
 
 
 def keep_from_score_window(scores: np.ndarray, row_steps: Sequence[int], w: int, r: int,
@@ -181,8 +197,11 @@ def keep_from_score_window(scores: np.ndarray, row_steps: Sequence[int], w: int,
 class UnitCache:
     """The cache of one KV head (with its G query heads) of one sequence.
 
-    Holds the paper's per-head state: keys, values, the boolean message, plus the
-    absolute position of every live key (for index parity with the device path).
+    State: the live keys and values in slot order, the absolute position of each, and the recent
+    message -- ``notes`` [n <= w, G, width], one note per observed query, oldest first, each a
+    boolean table over absolute positions (``note_of_query``), with the step of each in
+    ``note_steps``.  Because a note is addressed by position and not by slot, an eviction leaves
+    the notes untouched: the columns of evicted keys are simply never looked at again.
     """
 
     def __init__(self, d: int, G: int, w: int, r: int, c: float = 1.0, score_dtype: str = "f32",
@@ -193,21 +212,33 @@ class UnitCache:
         self.keys = np.zeros((0, d), dtype=np.float64)
         self.values = np.zeros((0, d), dtype=np.float64)
         self.positions = np.zeros((0,), dtype=np.int64)
-        self.message = np.zeros((0, G, 0), dtype=bool)
-        self.row_steps: List[int] = []
-
-    # -- bulk load without recording (prompt keys before the window starts)
-    def preload(self, keys: np.ndarray, values: np.ndarray, first_position: int = 0) -> None:
-        n = keys.shape[0]
-        self.keys = np.concatenate([self.keys, np.asarray(keys, dtype=np.float64)], axis=0)
-        self.values = np.concatenate([self.values, np.asarray(values, dtype=np.float64)], axis=0)
-        self.positions = np.concatenate([self.positions, first_position + np.arange(n, dtype=np.int64)])
-        m = self.message.shape[0]
-        self.message = np.concatenate([self.message, np.zeros((m, self.G, n), dtype=bool)], axis=2)
+        self.notes = np.zeros((0, G, 0), dtype=bool)
+        self.note_steps: List[int] = []
 
     @property
     def l(self) -> int:
         return self.keys.shape[0]
+
+    def _widen_notes(self, width: int) -> None:
+        """Make room for positions < width; positions no earlier query saw are minor for it."""
+        n, G, have = self.notes.shape
+        if width > have:
+            grown = np.zeros((n, G, max(width, have + have // 4 + 64)), dtype=bool)
+            grown[:, :, :have] = self.notes
+            self.notes = grown
+
+    def preload(self, keys: np.ndarray, values: np.ndarray, first_position: int = 0) -> None:
+        """Bulk load of keys whose own queries are not observed (the prompt before the window)."""
+        n = keys.shape[0]
+        self.keys = np.concatenate([self.keys, np.asarray(keys, dtype=np.float64)], axis=0)
+        self.values = np.concatenate([self.values, np.asarray(values, dtype=np.float64)], axis=0)
+        self.positions = np.concatenate([self.positions, first_position + np.arange(n, dtype=np.int64)])
+
+    def append(self, k_new: np.ndarray, v_new: np.ndarray, position: int) -> None:
+        """The current token's key and value enter the cache in the next free slot."""
+        self.keys = np.concatenate([self.keys, np.asarray(k_new, dtype=np.float64)[None]], axis=0)
+        self.values = np.concatenate([self.values, np.asarray(v_new, dtype=np.float64)[None]], axis=0)
+        self.positions = np.concatenate([self.positions, np.array([position], dtype=np.int64)])
 
     def attend(self, q: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
         """Eq. (2) and Eq. (1) for the G queries of the group: (alpha [G,l], out [G,d])."""
@@ -215,39 +246,44 @@ class UnitCache:
         out = np.stack([attention_output(alpha[g], self.values) for g in range(self.G)])
         return alpha, out
 
+    def observe_and_evict(self, stored: np.ndarray, t: int) -> Tuple[np.ndarray, np.ndarray]:
+        """The part of a step after attention (Algorithm 1): note what the query of step t found
+        important, forget notes older than the last w, decide, and close the gaps in slot order.
+
+        stored [G, l]: the query's scores as the record stores them.  Returns (keep [l], kept slots).
+        """
+        self._widen_notes(int(self.positions[-1]) + 1)
+        note = note_of_query(stored, self.positions, t, self.notes.shape[2], self.c)
+        self.notes = np.concatenate([self.notes, note[None]], axis=0)
+        self.note_steps = self.note_steps + [t]
+        if len(self.note_steps) > self.w:
+            self.notes, self.note_steps = self.notes[1:], self.note_steps[1:]
+        keep = survivors(self.notes, self.positions, self.w, self.r)
+        slots = stable_compact(keep)
+        self.keys, self.values, self.positions = self.keys[slots], self.values[slots], self.positions[slots]
+        return keep, slots
+
     def step(self, q: np.ndarray, k_new: np.ndarray, v_new: np.ndarray, t: int,
-             recorded: Optional[np.ndarray] = None, evict: bool = True):
+             recorded: Optional[np.ndarray] = None):
         """One decode step at absolute step t (the query is token number t, position t-1).
 
-        Order as in Algorithm 1: append, attend over all l keys, record, decide, gather.
+        Order as in Algorithm 1: the new key is in the cache, the query attends over all l keys,
+        its note is taken, the decision falls, the survivors close ranks.
         ``recorded`` ([G, l], stored values) replaces the oracle's own rounded scores as
-        the input of the record/evict part (slaved-trajectory parity).
+        the input of the note / decision part (slaved-trajectory parity).
         Returns dict(out, alpha, stored, keep, indices).
         """
-        self.keys = np.concatenate([self.keys, np.asarray(k_new, dtype=np.float64)[None]], axis=0)
-        self.values = np.concatenate([self.values, np.asarray(v_new, dtype=np.float64)[None]], axis=0)
-        self.positions = np.concatenate([self.positions, np.array([t - 1], dtype=np.int64)])
-        return self._attend_record_evict(q, t, recorded, evict)
-
-    def _attend_record_evict(self, q, t, recorded, evict):
+        self.append(k_new, v_new, t - 1)
         alpha, out = self.attend(np.asarray(q, dtype=np.float64))
         stored = round_to_storage(alpha, self.score_dtype) if recorded is None \
             else np.asarray(recorded, dtype=np.float32)
-        l = self.l
-        if evict:
-            keys, values, message, indices = corm_eviction(
-                self.keys, self.values, self.message, stored, self.w, self.r, t, self.c)
-        else:  # record only: Algorithm 1 up to and including the row append
-            m = self.message.shape[0]
-            message = np.concatenate([self.message, np.zeros((m, self.G, 1), dtype=bool)], axis=2)
-            message = np.concatenate([message, important(stored, t, self.c)[None]], axis=0)[-self.w:]
-            keys, values, indices = self.keys, self.values, np.arange(l)
-        keep = np.zeros(l, dtype=bool)
-        keep[indices] = True
-        self.keys, self.values, self.message = keys, values, message
-        self.positions = self.positions[indices]
-        self.row_steps = (self.row_steps + [t])[-self.w:]
-        return {"out": out, "alpha": alpha, "stored": stored, "keep": keep, "indices": indices}
+        keep, slots = self.observe_and_evict(stored, t)
+        return {"out": out, "alpha": alpha, "stored": stored, "keep": keep, "indices": slots}
+
+    def message(self) -> np.ndarray:
+        """The recent message restricted to the live keys, [n, G, l] in slot order: the boolean
+        matrix Algorithm 1 carries from call to call."""
+        return self.notes[:, :, self.positions]
 
 
 def seed_from_prompt(unit: UnitCache, K0: np.ndarray, V0: np.ndarray, Qtail: np.ndarray,

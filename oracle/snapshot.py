@@ -23,9 +23,10 @@ def unit_from_device_arrays(K, V, pos, lens, ring, b: int, h: int, G: int, w: in
 
     K, V [B,Hkv,Lcap,d]; pos [B,Hkv,Lcap]; lens [B,Hkv]; ring [B,Hq,w,Tcap] with the row of step
     tau in slot (tau-1) mod w and columns indexed by absolute position (or, int32, the boolean message
-    [B,Hq,w,ceil(Tcap/32)]: bit pos % 32 of word pos // 32).  The boolean message of
-    Algorithm 1 is rebuilt by thresholding each recorded row with its own c/tau (Def. 3.1);
-    keys that did not exist at step tau count as minor in that row.
+    [B,Hq,w,ceil(Tcap/32)]: bit pos % 32 of word pos // 32).  The oracle's notes (which keys each
+    recorded query found important) are rebuilt by thresholding each recorded row with its own c/tau
+    (Def. 3.1); keys that did not exist at step tau count as minor in that row, whatever the array holds
+    there.
     """
     d = K.shape[-1]
     u = O.UnitCache(d, G, w, r, thr_scale, score_dtype=dtype)
@@ -41,11 +42,12 @@ def unit_from_device_arrays(K, V, pos, lens, ring, b: int, h: int, G: int, w: in
         sc_all = ((words >> (pos_t & 31)) & 1).cpu().numpy().astype(bool)
     else:
         sc_all = _f32(ring[b, h * G:(h + 1) * G].index_select(2, pos_t))   # [G, w, l]
-    msg = np.zeros((len(rows), G, l), dtype=bool)
+    width = int(u.positions[-1]) + 1 if l else 0
+    notes = np.zeros((len(rows), G, width), dtype=bool)
     for a, tau in enumerate(rows):
         born = u.positions <= tau - 1
         row = sc_all[:, (tau - 1) % w]
-        msg[a] = (row if bits else O.important(row, tau, thr_scale)) & born[None, :]
-    u.message = msg
-    u.row_steps = rows
+        notes[a][:, u.positions] = (row if bits else O.important(row, tau, thr_scale)) & born[None, :]
+    u.notes = notes
+    u.note_steps = rows
     return u

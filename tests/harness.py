@@ -112,12 +112,14 @@ def check_unit_state(st: corm.LayerState, b: int, h: int, u: O.UnitCache, t: int
     Vd = _f32(V_d).astype(np.float64)
     assert np.array_equal(Kd, u.keys), (b, h, "K rows")
     assert np.array_equal(Vd, u.values), (b, h, "V rows")
-    # last_hit summary vs the oracle's message window
+    # last_hit summary vs the oracle's recent message
     lh = lh_d.cpu().numpy()
-    m = u.message.shape[0]
-    steps = np.asarray(u.row_steps[-m:], dtype=np.int64) if m else np.zeros((0,), dtype=np.int64)
-    hit_any = u.message.any(axis=1) if m else np.zeros((0, l), dtype=bool)       # [m, l]
-    last = np.where(hit_any, steps[:, None], 0).max(axis=0) if m else np.zeros(l, dtype=np.int64)
+    msg = u.message()                                                       # [n, G, l]
+    n = msg.shape[0]
+    steps = np.asarray(u.note_steps, dtype=np.int64)
+    assert len(steps) == n
+    hit_any = msg.any(axis=1)                                               # [n, l]
+    last = np.where(hit_any, steps[:, None], 0).max(axis=0) if n else np.zeros(l, dtype=np.int64)
     lo = t - st.w  # hits at steps <= t-w are outside the window
     assert np.array_equal(np.where(lh > lo, lh, 0), last), (b, h, "last_hit")
 
@@ -241,7 +243,14 @@ def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_sca
                 worst_score = max(worst_score, check_recorded(wl, st, recorded[g], res["alpha"][g], tb, thr_scale,
                                                               (j, b, h, g)))
             own = O.important(O.round_to_storage(res["alpha"], "f32" if st.ring_bits else wl.dtype), tb, thr_scale)
-            flips += int((own != O.important(recorded, tb, thr_scale)).sum())
+            flipped = own != O.important(recorded, tb, thr_scale)
+            if flipped.any():      # a decision may differ from the fp64 one only within the score tolerance of c/t
+                a = res["alpha"]
+                thr = float(O.importance_threshold(tb, thr_scale))
+                bound = (np.full_like(a, 1e-4 * thr) if st.ring_bits else
+                         SCORE_RTOL[wl.dtype] * a + SCORE_ATOL_OF_MAX[wl.dtype] * a.max(axis=1, keepdims=True))
+                assert (np.abs(a - thr)[flipped] <= bound[flipped]).all(), ("importance flip far from c/t", j, b, h)
+                flips += int(flipped.sum())
             if check_state_every and ((j + 1) % check_state_every == 0 or j == n_steps - 1):
                 check_unit_state(st, b, h, u, tb, lazy=lazy is not None)
     return {"compactions": compactions, "steps": n_steps, "units": len(units), "worst_out_rel_err": worst_out,

@@ -10,12 +10,15 @@ import textwrap
 import pytest
 
 from oracle import corm_oracle as O
+from oracle import snapshot as SNAP
 from tests import test_oracle_pins as pins
 
 PIN_PARAMS = {
     "test_keep_set_is_the_unique_subset_satisfying_the_definition": [{"G": 1}, {"G": 2}],
     "test_three_formulations_agree": [{"variant": "mha"}, {"variant": "gqa"}, {"variant": "bf16"}],
     "test_prompt_seeding_equals_the_causal_attention_matrix": [{"G": 1}, {"G": 2}],
+    "test_unit_rebuilt_from_header_layout_arrays_is_the_unit_that_wrote_them":
+        [{"ring_kind": "f32"}, {"ring_kind": "bf16"}, {"ring_kind": "bits"}],
 }
 
 
@@ -51,26 +54,40 @@ MUTANTS = [
      "np.float32(np.float32(c) * np.float32(1.0 / t))", "reciprocal then multiply: doubly rounded"),
     ("important", ">= importance_threshold", "> importance_threshold", "strict compare in Def. 3.1"),
     ("important_fraction", "float(imp.mean())", "float(1.0 - imp.mean())", "share of minor, not important, keys"),
-    ("stable_compact", "np.flatnonzero(np.asarray(decision, dtype=bool))",
-     "np.flatnonzero(np.asarray(decision, dtype=bool))[::-1]", "kept indices in descending order"),
-    ("corm_eviction", "np.zeros((m, G, 1), dtype=bool)", "np.ones((m, G, 1), dtype=bool)",
-     "a new key counts as important in the rows recorded before it existed"),
-    ("corm_eviction", "[-w:]", "[-(w + 1):]", "window holds w+1 rows"),
-    ("corm_eviction", "message.shape[0] < w", "message.shape[0] <= w", "first eviction one step late"),
-    ("corm_eviction", "message.shape[0] < w", "message.shape[0] < w - 1", "first eviction one step early"),
-    ("corm_eviction", "message.any(axis=(0, 1))", "message.any(axis=0).all(axis=0)",
-     "group rule: AND over the heads instead of OR"),
-    ("corm_eviction", "message.any(axis=(0, 1))", "message[-1].any(axis=0)", "only the current query decides"),
-    ("corm_eviction", "message.any(axis=(0, 1))", "message[:-1].any(axis=(0, 1))", "current query left out"),
-    ("corm_eviction", "decision[-r:] = True", "decision[-(r + 1):] = True", "r+1 recent slots protected"),
-    ("corm_eviction", "decision[-r:] = True", "decision[-(r - 1):] = True", "r-1 recent slots protected"),
-    ("corm_eviction", "decision[-r:] = True", "decision[:r] = True", "oldest, not newest, slots protected"),
-    ("corm_eviction", "decision[-r:] = True", "pass", "no recent protection"),
-    ("corm_eviction", "important(attn_score, t, c)", "important(attn_score, l, c)",
+    ("stable_compact", "np.flatnonzero(np.asarray(keep, dtype=bool))",
+     "np.flatnonzero(np.asarray(keep, dtype=bool))[::-1]", "kept indices in descending order"),
+    ("note_of_query", "np.zeros((stored_scores.shape[0], width), dtype=bool)",
+     "np.ones((stored_scores.shape[0], width), dtype=bool)",
+     "a key counts as important to the queries that never saw it"),
+    ("note_of_query", "important(stored_scores, t, c)", "important(stored_scores, len(positions), c)",
      "threshold from the live length instead of the step"),
-    ("corm_eviction", "message[:, :, indices], indices", "message, indices", "message columns not gathered"),
-    ("corm_eviction", "return keys[indices], values[indices]", "return keys[indices], values",
-     "values not gathered"),
+    ("note_of_query", "found[:, positions] =", "found[:, np.arange(len(positions))] =",
+     "note addressed by slot, not by position: wrong after the first eviction"),
+    ("long_term_minor", ".any(axis=(0, 1))", ".any(axis=0).all(axis=0)", "group rule: AND over the heads instead of OR"),
+    ("long_term_minor", "notes[:, :, positions]", "notes[-1:, :, positions]", "only the current query decides"),
+    ("long_term_minor", "notes[:, :, positions]", "notes[:-1, :, positions]", "current query left out"),
+    ("long_term_minor", "return ~found_by_someone", "return found_by_someone", "the important keys are evicted"),
+    ("survivors", "notes.shape[0] < w", "notes.shape[0] <= w", "first eviction one step late"),
+    ("survivors", "notes.shape[0] < w", "notes.shape[0] < w - 1", "first eviction one step early"),
+    ("survivors", "notes[notes.shape[0] - w:]", "notes[notes.shape[0] - w + 1:]", "window of w-1 queries"),
+    ("survivors", "stays[max(l - r, 0):] = True", "stays[max(l - r - 1, 0):] = True", "r+1 recent slots protected"),
+    ("survivors", "stays[max(l - r, 0):] = True", "stays[max(l - r + 1, 0):] = True", "r-1 recent slots protected"),
+    ("survivors", "stays[max(l - r, 0):] = True", "stays[:r] = True", "oldest, not newest, slots protected"),
+    ("survivors", "stays[max(l - r, 0):] = True", "pass", "no recent protection"),
+    ("UnitCache.observe_and_evict", "if len(self.note_steps) > self.w:", "if len(self.note_steps) > self.w + 1:",
+     "window holds w+1 notes"),
+    ("UnitCache.observe_and_evict", "self.notes[1:], self.note_steps[1:]", "self.notes[:-1], self.note_steps[:-1]",
+     "the newest note is dropped instead of the oldest"),
+    ("UnitCache.observe_and_evict", "self.keys[slots], self.values[slots], self.positions[slots]",
+     "self.keys[slots], self.values, self.positions[slots]", "values not gathered"),
+    ("UnitCache.observe_and_evict", "self.keys[slots], self.values[slots], self.positions[slots]",
+     "self.keys[slots], self.values[slots], self.positions", "positions not gathered"),
+    ("UnitCache._widen_notes", "grown[:, :, :have] = self.notes", "pass", "older notes lost when the table grows"),
+    ("UnitCache.step", "self.append(k_new, v_new, t - 1)", "self.append(k_new, v_new, t)",
+     "position of the new key off by one"),
+    ("UnitCache.step", "if recorded is None", "if True", "fed scores ignored"),
+    ("UnitCache.message", "self.notes[:, :, self.positions]", "self.notes[:, :, :self.l]",
+     "message read by slot instead of by position"),
     ("keep_from_score_window", "important(scores[j], tj, c)", "important(scores[j], row_steps[-1], c)",
      "every row thresholded with the current step"),
     ("keep_from_score_window", "scores = scores[-w:]", "scores = scores[:w]", "oldest w rows instead of newest"),
@@ -81,30 +98,53 @@ MUTANTS = [
     ("round_to_bf16", "(bits + np.uint64(0x7FFF) + lsb)", "(bits + np.uint64(0x8000))", "ties away from zero"),
     ("round_to_storage", "s = round_to_bf16(s)", "pass", "bf16 ring not rounded"),
     ("round_to_storage", "astype(np.float32)", "astype(np.float16).astype(np.float32)", "scores stored through fp16"),
-    ("UnitCache.step", "np.array([t - 1], dtype=np.int64)", "np.array([t], dtype=np.int64)",
-     "position of the new key off by one"),
     ("UnitCache.attend", "attention_scores(q[g], self.keys, self.sm_scale)",
      "attention_scores(q[0], self.keys, self.sm_scale)", "every head of the group uses the first head's query"),
     ("UnitCache.attend", "attention_output(alpha[g], self.values)", "attention_output(alpha[g], self.keys)",
      "output mixes keys instead of values"),
-    ("UnitCache._attend_record_evict", "self.positions = self.positions[indices]", "pass",
-     "positions not gathered"),
     ("UnitCache.preload", "first_position + np.arange(n, dtype=np.int64)",
      "first_position + 1 + np.arange(n, dtype=np.int64)", "prompt positions 1-based"),
     ("seed_from_prompt", "p + 1, recorded=rec", "p, recorded=rec", "prompt step numbers 0-based"),
     ("seed_from_prompt", "unit.preload(K0[:P - n], V0[:P - n], 0)", "unit.preload(K0[:P - n], V0[:P - n], 0)\n"
-     "    unit.row_steps = []\n    n = n - 1", "last prompt query not recorded"),
+     "    n = n - 1", "last prompt query not recorded"),
+    # rebuilding a unit from plain arrays (oracle/snapshot.py)
+    ("snapshot:unit_from_device_arrays", "row = sc_all[:, (tau - 1) % w]", "row = sc_all[:, tau % w]",
+     "ring slot of a step off by one"),
+    ("snapshot:unit_from_device_arrays", "born = u.positions <= tau - 1", "born = u.positions < tau - 1",
+     "a step's own key counts as not yet there"),
+    ("snapshot:unit_from_device_arrays", "born = u.positions <= tau - 1", "born = u.positions <= tau",
+     "the next step's key counts as already there"),
+    ("snapshot:unit_from_device_arrays", "& born[None, :]", "", "junk in columns of keys not yet born is believed"),
+    ("snapshot:unit_from_device_arrays", "pos_t >> 5", "pos_t >> 4", "wrong word of the bit ring"),
+    ("snapshot:unit_from_device_arrays", "(pos_t & 31)", "(pos_t & 15)", "wrong bit of the word"),
+    ("snapshot:unit_from_device_arrays", "max(t_first, t_prev - w + 1)", "max(t_first, t_prev - w)",
+     "window of w+1 rows"),
+    ("snapshot:unit_from_device_arrays", "max(t_first, t_prev - w + 1)", "max(1, t_prev - w + 1)",
+     "rows from before the first recorded step"),
+    ("snapshot:unit_from_device_arrays", "O.important(row, tau, thr_scale)", "O.important(row, t_prev, thr_scale)",
+     "every row thresholded with the latest step"),
+    ("snapshot:unit_from_device_arrays", "ring[b, h * G:(h + 1) * G].index_select(2, pos_t))",
+     "ring[b, h:h + G].index_select(2, pos_t))", "query heads of the wrong group (score ring)"),
+    ("snapshot:unit_from_device_arrays", "ring[b, h * G:(h + 1) * G].index_select(2, pos_t >> 5)",
+     "ring[b, h:h + G].index_select(2, pos_t >> 5)", "query heads of the wrong group (bit ring)"),
+    ("snapshot:unit_from_device_arrays", "u.keys = _f32(K[b, h, :l])", "u.keys = _f32(K[h, b, :l])",
+     "sequence and head swapped"),
+    ("snapshot:unit_from_device_arrays", "u.values = _f32(V[b, h, :l])", "u.values = _f32(K[b, h, :l])",
+     "values read from the key array"),
 ]
 
 
 def _mutated(where, old, new):
     """Returns (owner, attribute name, original, replacement) with one snippet of the source rewritten."""
-    owner, name = (O, where) if "." not in where else (getattr(O, where.split(".")[0]), where.split(".")[1])
+    mod = O
+    if ":" in where:
+        mod, where = SNAP, where.split(":")[1]
+    owner, name = (mod, where) if "." not in where else (getattr(mod, where.split(".")[0]), where.split(".")[1])
     orig = inspect.getattr_static(owner, name)
     src = textwrap.dedent(inspect.getsource(orig))
     assert src.count(old) == 1, f"{where}: snippet {old!r} occurs {src.count(old)} times: the oracle's text changed"
     ns = {}
-    exec(compile(src.replace(old, new), f"<mutant of {where}>", "exec"), vars(O), ns)   # module globals, own locals
+    exec(compile(src.replace(old, new), f"<mutant of {where}>", "exec"), vars(mod), ns)   # module globals, own locals
     return owner, name, orig, ns[name]
 
 

@@ -188,24 +188,22 @@ def test_hand_derived_trace_of_algorithm1():
     lines = [ln for ln in open(os.path.join(GOLDEN, "algorithm1_worked_example.txt"))
              if ln.strip() and not ln.startswith("#")]
     d = 4
-    keys = np.arange(3 * d, dtype=np.float64).reshape(3, d)
-    values = -keys
-    positions = np.arange(3)
-    message = np.zeros((0, 1, 2), dtype=bool)
-    for ln in lines:
+    u = O.UnitCache(d, 1, w=2, r=1, score_dtype="f32")
+    first = np.arange(3 * d, dtype=np.float64).reshape(3, d)
+    u.preload(first, -first)
+    for n_seen, ln in enumerate(lines, start=1):
         t_s, scores_s, pos_s = ln.split("|")
         t = int(t_s)
         scores = np.array([float(v) for v in scores_s.split()], dtype=np.float32)[None]
         want = [int(v) for v in pos_s.split()]
-        if t > 3:  # append the key of position t-1
-            keys = np.concatenate([keys, np.full((1, d), float(t - 1) * 100)])
-            values = np.concatenate([values, np.full((1, d), -float(t - 1))])
-            positions = np.concatenate([positions, [t - 1]])
-        keys, values, message, idx = O.corm_eviction(keys, values, message, scores, w=2, r=1, t=t)
-        positions = positions[idx]
-        assert positions.tolist() == want, (t, positions)
-        assert keys.shape[0] == len(want) and message.shape[2] == len(want)
-    assert keys[:, 0].tolist() == [400.0, 500.0] and values[:, 0].tolist() == [-4.0, -5.0]
+        if t > 3:  # the key of position t-1 enters
+            u.append(np.full(d, float(t - 1) * 100), np.full(d, -float(t - 1)), t - 1)
+        before = u.positions.copy()
+        keep, slots = u.observe_and_evict(scores, t)
+        assert u.positions.tolist() == want, (t, u.positions)
+        assert before[slots].tolist() == want and before[keep].tolist() == want
+        assert u.keys.shape[0] == len(want) and u.message().shape == (min(n_seen, 2), 1, len(want))
+    assert u.keys[:, 0].tolist() == [400.0, 500.0] and u.values[:, 0].tolist() == [-4.0, -5.0]
 
 
 def _long_term_minor_per_key(history, i_pos, t, w, c):
@@ -436,6 +434,13 @@ def test_window_function_agrees_with_algorithm1_state():
                     win[a, :, jj] = hist[tt][p]
         keep = O.keep_from_score_window(win, rows, wl.w, wl.r)
         assert np.array_equal(keep, res["keep"]), t
+        # the recent message as Algorithm 1 would carry it: rows = recorded steps, columns = the live keys
+        msg = u.message()
+        assert msg.shape == (len(rows), wl.G, u.l) and u.note_steps == rows
+        for a, tt in enumerate(rows):
+            for jj, p in enumerate(u.positions.tolist()):
+                want = O.important(hist[tt][p], tt) if p in hist[tt] else np.zeros(wl.G, dtype=bool)
+                assert np.array_equal(msg[a, :, jj], want), (t, tt, p)
         results.append(res)
     assert any(not r["keep"].all() for r in results)
 
@@ -460,7 +465,7 @@ def test_compaction_invariants_along_a_trajectory():
         assert u.positions[-k:].tolist() == list(range(t - k, t))
         assert u.l >= min(t, wl.r)
         assert np.array_equal(u.keys, allK[u.positions])        # rows moved bit for bit, in order
-        assert u.message.shape == (wl.w, 1, u.l)
+        assert u.message().shape == (wl.w, 1, u.l)
     ones = np.ones(u.l, dtype=bool)
     assert O.stable_compact(ones).tolist() == list(range(u.l))   # keep-all is the identity
     keep = np.array([1, 0, 1, 1, 0, 1], dtype=bool)
@@ -481,6 +486,176 @@ def test_recent_keys_survive_even_when_minor():
         u.step(q, np.zeros(d), np.ones(d), t)
         want = [0] + list(range(max(1, t - r), t)) if t >= w else list(range(t))
         assert u.positions.tolist() == want
+
+
+# ------------------------------------------------------------------ slaved mode (recorded scores fed in)
+
+def _free_run(G, w, r, steps, seed, dtype="f32", d=8):
+    rng = np.random.default_rng(seed)
+    ins = [(rng.standard_normal((G, d)) * 3.0, rng.standard_normal(d) * 2, rng.standard_normal(d))
+           for _ in range(steps)]
+    u = O.UnitCache(d, G, w, r, score_dtype=dtype)
+    return ins, [u.step(q, k, v, t) for t, (q, k, v) in enumerate(ins, start=1)], u
+
+
+def test_recorded_scores_fed_back_reproduce_the_free_run():
+    """The slaved path (`recorded=`) with the oracle's own stored scores is the free run, step for step;
+    the fed scores replace the oracle's in the note and the decision, and only there."""
+    for G, dtype in ((1, "f32"), (2, "bf16")):
+        ins, free, u_free = _free_run(G, 3, 2, 40, seed=21 + G, dtype=dtype)
+        assert any(not f["keep"].all() for f in free)
+        u = O.UnitCache(8, G, 3, 2, score_dtype=dtype)
+        for t, ((q, k, v), f) in enumerate(zip(ins, free), start=1):
+            res = u.step(q, k, v, t, recorded=f["stored"].copy())
+            assert np.array_equal(res["keep"], f["keep"]) and np.array_equal(res["indices"], f["indices"])
+            assert np.array_equal(res["stored"], f["stored"])
+            assert np.array_equal(res["alpha"], f["alpha"]) and np.array_equal(res["out"], f["out"])
+        assert np.array_equal(u.positions, u_free.positions) and np.array_equal(u.notes, u_free.notes)
+        assert u.note_steps == u_free.note_steps
+
+
+def _positions_seen(free, j):
+    """Absolute positions of the live keys at step j+1 of a free run (after the append, before eviction)."""
+    pos = np.zeros(0, dtype=np.int64)
+    for t in range(1, j + 2):
+        pos = np.concatenate([pos, [t - 1]])
+        if t <= j:
+            pos = pos[free[t - 1]["indices"]]
+    return pos
+
+
+def test_one_flipped_recorded_entry_flips_exactly_that_keys_decision():
+    """Feeding the free run's scores with ONE key's entry changed changes that key's decision and no other:
+    a long-term minor key that one head now finds important stays; a key whose only supporter in the current
+    query is silenced goes, unless an older query of the window (looked up in the free run's own history,
+    by position) still vouches for it."""
+    G, w, r, steps = 2, 3, 2, 40
+    ins, free, _ = _free_run(G, w, r, steps, seed=33)
+    went_up = went_down = stayed = 0
+    for j in range(w, steps):
+        keep = free[j]["keep"]
+        l = len(keep)
+        pos_now = _positions_seen(free, j)
+        older = {}                                           # step -> positions some head found important
+        for tt in range(j + 2 - w, j + 1):
+            hit = O.important(free[tt - 1]["stored"], tt).any(axis=0)
+            older[tt] = set(_positions_seen(free, tt - 1)[hit].tolist())
+        for case, cands in (("up", np.flatnonzero(~keep).tolist()), ("down", list(range(l - r)))):
+            for i in cands:
+                rec = free[j]["stored"].copy()
+                want = keep.copy()
+                if case == "up":
+                    rec[1, i] = 1.0                          # one head now finds key i important
+                    want[i] = True
+                    went_up += 1
+                else:
+                    if O.important(rec[:, i], j + 1).sum() != 1:
+                        continue
+                    rec[:, i] = 0.0                          # its only supporter in this query is silenced
+                    want[i] = any(int(pos_now[i]) in older[tt] for tt in older)
+                    went_down += int(not want[i])
+                    stayed += int(want[i])
+                u = O.UnitCache(8, G, w, r, score_dtype="f32")
+                for t in range(1, j + 1):
+                    u.step(*ins[t - 1], t, recorded=free[t - 1]["stored"])
+                res = u.step(*ins[j], j + 1, recorded=rec)
+                assert np.array_equal(res["keep"], want), (case, j, i)
+    assert went_up > 5 and went_down > 0 and stayed > 0
+
+
+# ------------------------------------------------------------------ rebuilding a unit from plain state arrays
+
+def _trajectory_in_header_layout(ring_kind, n_steps, B=2, Hkv=2, G=2, d=8, w=5, r=3, Lcap=40, Tcap=70, seed=50):
+    """Runs B*Hkv oracle units on the CPU and, beside them, writes what a device would hold into plain torch
+    CPU tensors in the layouts the C header documents: K, V [B,Hkv,Lcap,d], pos [B,Hkv,Lcap], lens [B,Hkv],
+    ring [B,Hq,w,Tcap] (row of step tau in slot (tau-1) mod w, column = absolute position) or, for
+    ring_kind "bits", int32 [B,Hq,w,ceil(Tcap/32)] (bit pos%32 of word pos//32).  Sequence b has seen
+    first[b] - 1 unrecorded tokens before its first recorded step, so t_first differs per sequence and
+    is > 1.  The arrays start full of junk that reads as "important"; slots >= lens hold junk too."""
+    rng = np.random.default_rng(seed)
+    Hq = Hkv * G
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "bits": torch.float32}[ring_kind]
+    sdt = "f32" if ring_kind == "bits" else ring_kind
+
+    def stored_dtype(x):            # round once to the storage type so that both sides hold the same values
+        return torch.from_numpy(np.asarray(x, dtype=np.float32)).to(tdt).float().numpy()
+
+    K = torch.full((B, Hkv, Lcap, d), 7.0, dtype=tdt)
+    V = torch.full((B, Hkv, Lcap, d), -7.0, dtype=tdt)
+    pos = torch.full((B, Hkv, Lcap), 12345, dtype=torch.int32)
+    lens = torch.zeros((B, Hkv), dtype=torch.int32)
+    if ring_kind == "bits":
+        ring_np = np.full((B, Hq, w, (Tcap + 31) // 32), 0xFFFFFFFF, dtype=np.uint32)
+    else:
+        ring_np = np.ones((B, Hq, w, Tcap), dtype=np.float32)
+    first = [7 + 4 * b for b in range(B)]                   # t_first per sequence
+    units = {}
+    for b in range(B):
+        for h in range(Hkv):
+            u = O.UnitCache(d, G, w, r, score_dtype=sdt)
+            n0 = first[b] - 1
+            u.preload(stored_dtype(rng.standard_normal((n0, d)) * 2), stored_dtype(rng.standard_normal((n0, d))))
+            units[(b, h)] = u
+    t_now = list(f - 1 for f in first)
+    for _ in range(n_steps):
+        for b in range(B):
+            t_now[b] += 1
+            t = t_now[b]
+            for h in range(Hkv):
+                u = units[(b, h)]
+                seen = np.concatenate([u.positions, [t - 1]])      # what the query of this step sees
+                res = u.step(stored_dtype(rng.standard_normal((G, d)) * 1.5), stored_dtype(rng.standard_normal(d) * 2),
+                             stored_dtype(rng.standard_normal(d)), t)
+                for g in range(G):
+                    hq = h * G + g
+                    if ring_kind == "bits":
+                        for p, hit in zip(seen, O.important(res["stored"][g], t)):
+                            word, bit = int(p) // 32, int(p) % 32
+                            if hit:
+                                ring_np[b, hq, (t - 1) % w, word] |= np.uint32(1 << bit)
+                            else:
+                                ring_np[b, hq, (t - 1) % w, word] &= np.uint32(~(1 << bit) & 0xFFFFFFFF)
+                    else:
+                        ring_np[b, hq, (t - 1) % w, seen] = res["stored"][g]
+    for (b, h), u in units.items():
+        K[b, h, :u.l] = torch.from_numpy(u.keys).to(tdt)
+        V[b, h, :u.l] = torch.from_numpy(u.values).to(tdt)
+        pos[b, h, :u.l] = torch.from_numpy(u.positions).to(torch.int32)
+        lens[b, h] = u.l
+    ring = torch.from_numpy(ring_np.view(np.int32)) if ring_kind == "bits" else torch.from_numpy(ring_np).to(tdt)
+    return dict(K=K, V=V, pos=pos, lens=lens, ring=ring, units=units, t_now=t_now, first=first,
+                G=G, w=w, r=r, d=d, sdt=sdt, rng=rng, stored_dtype=stored_dtype)
+
+
+@pytest.mark.parametrize("ring_kind", ["f32", "bf16", "bits"])
+def test_unit_rebuilt_from_header_layout_arrays_is_the_unit_that_wrote_them(ring_kind):
+    """oracle/snapshot.py against a writer of its own: a CPU trajectory's state, laid out as the C header says
+    (score ring and bit ring, a wrapped ring and one not yet full, t_first > 1 and different per sequence,
+    holes in pos, junk wherever nothing was written), is rebuilt and must be the unit that wrote it: same
+    rows, positions, recent message and steps, and the same next steps."""
+    from oracle.snapshot import unit_from_device_arrays
+    for n_steps in (3, 13):                                  # fewer than w recorded rows; ring wrapped twice
+        S = _trajectory_in_header_layout(ring_kind, n_steps)
+        G, w, r, d = S["G"], S["w"], S["r"], S["d"]
+        holes = 0
+        for (b, h), u in S["units"].items():
+            t_prev = S["t_now"][b]
+            got = unit_from_device_arrays(S["K"], S["V"], S["pos"], S["lens"], S["ring"], b, h, G, w, r,
+                                          t_prev, S["first"][b], S["sdt"])
+            assert np.array_equal(got.keys, u.keys) and np.array_equal(got.values, u.values)
+            assert np.array_equal(got.positions, u.positions)
+            assert got.note_steps == u.note_steps == list(range(max(S["first"][b], t_prev - w + 1), t_prev + 1))
+            assert np.array_equal(got.message(), u.message())
+            holes += int((np.diff(u.positions) > 1).sum())
+            for k in range(w + 2):                           # until every rebuilt note has left the window
+                q = S["stored_dtype"](S["rng"].standard_normal((G, d)) * 3)
+                kn = S["stored_dtype"](S["rng"].standard_normal(d) * 2)
+                vn = S["stored_dtype"](S["rng"].standard_normal(d))
+                ra, rb = u.step(q, kn, vn, t_prev + 1 + k), got.step(q, kn, vn, t_prev + 1 + k)
+                for key in ("out", "alpha", "stored", "keep", "indices"):
+                    assert np.array_equal(ra[key], rb[key]), (key, n_steps, b, h, k)
+                assert np.array_equal(u.positions, got.positions)
+        assert holes > 0 or n_steps < w, "no unit has a hole in its positions: vacuous"
 
 
 # ------------------------------------------------------------------ byte accounting
