@@ -19,9 +19,10 @@ LIB_PATH = os.path.join(_HERE, "libcorm.so")
 CORM_F32, CORM_BF16, CORM_BIT = 0, 1, 2
 CORM_OK, CORM_EINVAL, CORM_EUNSUPPORTED, CORM_ECAPACITY, CORM_EHIP = 0, -1, -2, -3, -4
 CORM_DEV_UNIT_FULL, CORM_DEV_BAD_STEP, CORM_DEV_BAD_LENS = 1, 2, 4
+CORM_STATIC_SCRATCH_BYTES = 40 << 20
 
 EXPORTS = ("corm_version", "corm_strerror", "corm_workspace_bytes", "corm_workspace_init", "corm_append",
-           "corm_decode_attend", "corm_evict_mask", "corm_evict_mask_summary", "corm_row_density", "corm_compact",
+           "corm_decode_attend", "corm_decode_attend_static", "corm_evict_mask", "corm_evict_mask_summary", "corm_row_density", "corm_compact",
            "corm_decode_step", "corm_step_attend", "corm_step_evict", "corm_decode_step_lazy", "corm_prefill_seed", "corm_force_path",
            "corm_selected_path", "corm_profile_attend", "corm_threshold")
 
@@ -60,6 +61,7 @@ def lib() -> ctypes.CDLL:
         L.corm_workspace_init.argtypes = [dp, vp, sz, vp]
         L.corm_append.argtypes = [dp, vp, vp, i32p, i32p, i32p, vp, vp, i32p, i32p, vp]
         L.corm_decode_attend.argtypes = [dp, vp, vp, vp, i32p, i32p, i32p, vp, i32p, vp, vp, sz, i32p, vp]
+        L.corm_decode_attend_static.argtypes = [dp, vp, vp, vp, i32p, i32p, i32p, vp, i32p, vp, i32p, vp]
         L.corm_evict_mask.argtypes = [dp, vp, i32p, i32p, i32p, i32p, vp, vp]
         L.corm_evict_mask_summary.argtypes = [dp, i32p, i32p, i32p, i32p, vp, vp]
         L.corm_row_density.argtypes = [dp, vp, i32p, i32p, i32p, vp, vp]
@@ -156,6 +158,14 @@ def corm_decode_attend(desc, q, K, V, lens, pos, t, score_ring, last_hit, out, w
                                   _ptr(score_ring), _ptr(last_hit), _ptr(out), _ptr(workspace), nbytes,
                                   _ptr(status), _stream(stream))
     return _check(rc, "corm_decode_attend") if check else rc
+
+
+def corm_decode_attend_static(desc, q, K, V, lens, pos, t, score_ring, last_hit, out, status=None, stream=None,
+                              check=True) -> int:
+    rc = lib().corm_decode_attend_static(ctypes.byref(desc), _ptr(q), _ptr(K), _ptr(V), _ptr(lens), _ptr(pos),
+                                         _ptr(t), _ptr(score_ring), _ptr(last_hit), _ptr(out), _ptr(status),
+                                         _stream(stream))
+    return _check(rc, "corm_decode_attend_static") if check else rc
 
 
 def corm_evict_mask(desc, score_ring, lens, pos, t, t_first, keep, stream=None, check=True) -> int:

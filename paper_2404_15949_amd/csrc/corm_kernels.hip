@@ -23,6 +23,7 @@
 #include <stdint.h>
 #include <math.h>
 #include <cmath>
+#include <mutex>
 
 #include "corm.h"
 
@@ -35,6 +36,35 @@
 #include "standalone.hpp"
 #include "host.hpp"
 
+// ---- corm_decode_attend_static: the attend call for callers that cannot allocate
+//
+// The split partials and raw logits that corm_decode_attend keeps in the caller's workspace live in this
+// file-scope device array instead.  In host code the array's name is only a stand-in: its device address
+// is asked for once per device (with that device current) and kept; only that address is ever used.
+static __device__ __align__(256) unsigned char scratch[CORM_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[MAX_DEVICES] = {};
+
+// device address of `scratch` on the current device
+int static_scratch(void** ptr) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return CORM_EHIP;
+  if (dev < 0 || dev >= MAX_DEVICES) return CORM_EUNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return CORM_EHIP;
+    if (reinterpret_cast<uintptr_t>(p) & 255u) return CORM_EHIP;
+    g_scratch_ptr[dev] = p;
+  }
+  *ptr = g_scratch_ptr[dev];
+  return CORM_OK;
+}
+}  // namespace
+
 // ---------------------------------------------------------------- C ABI
 
 extern "C" {
@@ -46,7 +76,7 @@ const char* corm_strerror(int status) {
     case CORM_OK: return "ok";
     case CORM_EINVAL: return "invalid argument (null or misaligned pointer, bad shape, w < 1, r < 1, c < 0)";
     case CORM_EUNSUPPORTED: return "unsupported configuration (d not in {64,128}, group size not in {1,2,4,8}, dtype)";
-    case CORM_ECAPACITY: return "capacity exceeded (workspace too small)";
+    case CORM_ECAPACITY: return "capacity exceeded (workspace too small, or shape beyond the static scratch)";
     case CORM_EHIP: return "HIP launch failed";
     default: return "unknown status";
   }
@@ -104,6 +134,29 @@ int corm_decode_attend(const corm_desc* desc, const void* q, const void* K, cons
   p.t = t; p.t_first = t; p.ring = score_ring; p.out = out; p.status = status;
   p.do_append = 0; p.do_evict = 0;
   bind_params(desc, wl, workspace, p);
+  return launch_attend_record(desc, p, (hipStream_t)stream);
+}
+
+int corm_decode_attend_static(const corm_desc* desc, const void* q, const void* K, const void* V,
+                              const int32_t* lens, const int32_t* pos, const int32_t* t, void* score_ring,
+                              int32_t* last_hit, float* out, int32_t* status, void* stream) {
+  int rc = validate_desc(desc);
+  if (rc) return rc;
+  rc = check_step_pointers(q, K, V, K, V, lens, pos, last_hit, t, t, score_ring, out, nullptr, status);
+  if (rc) return rc;
+  // what attend + record keep in scratch memory: everything in front of the compaction's staging area
+  const WorkspaceLayout wl = workspace_layout(*desc);
+  if (wl.stage_meta_off > CORM_STATIC_SCRATCH_BYTES) return CORM_ECAPACITY;
+  void* ws = nullptr;
+  rc = static_scratch(&ws);
+  if (rc) return rc;
+  Params p = {};
+  p.q = q; p.k_new = K; p.v_new = V;
+  p.K = const_cast<void*>(K); p.V = const_cast<void*>(V);
+  p.lens = const_cast<int32_t*>(lens); p.pos = const_cast<int32_t*>(pos); p.last_hit = last_hit;
+  p.t = t; p.t_first = t; p.ring = score_ring; p.out = out; p.status = status;
+  p.do_append = 0; p.do_evict = 0;
+  bind_params(desc, wl, ws, p);
   return launch_attend_record(desc, p, (hipStream_t)stream);
 }
 

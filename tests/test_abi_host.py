@@ -102,6 +102,23 @@ def test_null_and_misaligned_pointers_are_rejected_on_the_host():
     assert corm.corm_threshold(-1.0, a, 4, a, check=False) == corm.CORM_EINVAL
 
 
+def test_static_scratch_entry_checks_its_arguments_and_its_limit_on_the_host():
+    """corm_decode_attend_static: bad pointers and shapes beyond the library's device array are refused
+    before any device call (so this runs without a GPU)."""
+    a = 4096
+    ok = _desc()
+    assert corm.corm_decode_attend_static(ok, a, a, a, a, a, a, a, None, a, check=False) == corm.CORM_EINVAL
+    assert corm.corm_decode_attend_static(ok, a + 4, a, a, a, a, a, a, a, a, check=False) == corm.CORM_EINVAL
+    assert corm.corm_decode_attend_static(_desc(d=96), a, a, a, a, a, a, a, a, a, check=False) == corm.CORM_EUNSUPPORTED
+    # logits alone: B*Hq*Lcap*4 bytes
+    big = _desc(B=16, Hq=32, Hkv=32, Lcap=32768, Tcap=32768)
+    assert 16 * 32 * 32768 * 4 > corm.CORM_STATIC_SCRATCH_BYTES
+    assert corm.corm_decode_attend_static(big, a, a, a, a, a, a, a, a, a, check=False) == corm.CORM_ECAPACITY
+    text = open(os.path.join(ROOT, "include", "corm.h")).read()
+    assert re.search(r"#define\s+CORM_STATIC_SCRATCH_BYTES\s+\(40u << 20\)", text)
+    assert corm.CORM_STATIC_SCRATCH_BYTES == 40 << 20
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(corm, "_lib", None)
     monkeypatch.setattr(corm, "LIB_PATH", "/nonexistent/libcorm.so")
