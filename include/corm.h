@@ -25,8 +25,9 @@
  * (a full unit, a step beyond the ring's columns) never fault: the kernel skips the offending
  * write and ORs a bit into the optional `status` word.
  * Calls that overlap in time (other streams, other host threads) need a workspace each and must not share
- * any array a call writes; beyond that the library keeps no state, except the two process-wide knobs at
- * the end of this header (corm_force_path, corm_profile_attend), which are not thread safe.
+ * any array a call writes; beyond that the library keeps no mutable state: what a call does depends on its
+ * arguments alone (the only things remembered are, per device, the number of compute units and the address
+ * of the static scratch array, both looked up once under a lock), so every call may be made from any thread.
  *
  * Layouts (row-major, sizes in elements)
  *   q              [B, Hq, d]            kv_dtype        query of the current token per head
@@ -103,6 +104,24 @@ typedef struct corm_desc {
   float sm_scale;        /* logit scale; 0 selects 1/sqrt(d) (Eq. 1)                              */
 } corm_desc;
 
+/* Optional per-call launch options of the attend / step calls (NULL = all defaults).
+ *   path   how attend + record are launched: 0 = chosen by shape (default); 1 = split kernels (several
+ *          workgroups per unit, partials merged by a second launch; grouped bf16 d=128 queries take q.K^T on
+ *          the matrix cores); 2 = one workgroup per unit with the logits in LDS (taken only if they fit);
+ *          3 = as 1 but q.K^T always on the vector ALU.  Every path produces the same keep mask, indices
+ *          and cache; out and the recorded scores agree within fp32 rounding.  A tuning and test knob.
+ *   attend_start_event, attend_stop_event   hipEvent_t handles (as void*), both or neither: recorded on the
+ *          call's stream immediately before and after the launch that streams K and V (the split attend
+ *          kernel or the fused unit kernel), so that its duration can be measured in place.  Not for use
+ *          under graph capture.
+ * CORM_EINVAL for a path outside 0..3 or a single event. */
+typedef struct corm_launch_opts {
+  int32_t path;
+  int32_t reserved;            /* 0 */
+  void* attend_start_event;
+  void* attend_stop_event;
+} corm_launch_opts;
+
 int corm_version(void);
 const char* corm_strerror(int status);
 
@@ -126,7 +145,7 @@ int corm_append(const corm_desc* desc, void* K, void* V, int32_t* lens, int32_t*
 int corm_decode_attend(const corm_desc* desc, const void* q, const void* K, const void* V,
                        const int32_t* lens, const int32_t* pos, const int32_t* t, void* score_ring,
                        int32_t* last_hit, float* out, void* workspace, size_t workspace_bytes,
-                       int32_t* status, void* stream);
+                       int32_t* status, const corm_launch_opts* opts, void* stream);
 
 /* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc): corm_decode_attend without a workspace argument.  The split partials
@@ -143,7 +162,8 @@ int corm_decode_attend(const corm_desc* desc, const void* q, const void* K, cons
 #define CORM_STATIC_SCRATCH_BYTES (40u << 20)
 int corm_decode_attend_static(const corm_desc* desc, const void* q, const void* K, const void* V,
                               const int32_t* lens, const int32_t* pos, const int32_t* t, void* score_ring,
-                              int32_t* last_hit, float* out, int32_t* status, void* stream);
+                              int32_t* last_hit, float* out, int32_t* status, const corm_launch_opts* opts,
+                              void* stream);
 
 /* Eviction decision from the ring alone (Def. 4.1 + recent-r rule + Section 5.3 group rule),
  * evaluated literally: keep[i] = OR over the recorded rows tau in [max(t_first, t-w+1), t] and the
@@ -178,7 +198,7 @@ int corm_decode_step(const corm_desc* desc, const void* q, const void* k_new, co
                      void* K, void* V, int32_t* lens, int32_t* pos, int32_t* last_hit,
                      const int32_t* t, const int32_t* t_first, void* score_ring, float* out,
                      uint8_t* keep, int32_t* kept_idx, void* workspace, size_t workspace_bytes,
-                     int32_t* status, void* stream);
+                     int32_t* status, const corm_launch_opts* opts, void* stream);
 
 /* The fused step in two phases, for callers that overlap the compaction with other work (another
  * layer's attention, the model's GEMMs) on a second stream:
@@ -194,7 +214,7 @@ int corm_decode_step(const corm_desc* desc, const void* q, const void* k_new, co
 int corm_step_attend(const corm_desc* desc, const void* q, const void* k_new, const void* v_new, void* K, void* V,
                      const int32_t* lens, int32_t* pos, int32_t* last_hit, const int32_t* t, const int32_t* t_first,
                      void* score_ring, float* out, uint8_t* keep, void* workspace, size_t workspace_bytes,
-                     int32_t* status, void* stream);
+                     int32_t* status, const corm_launch_opts* opts, void* stream);
 int corm_step_evict(const corm_desc* desc, void* K, void* V, int32_t* lens, int32_t* pos, int32_t* last_hit,
                     int32_t* kept_idx, void* workspace, size_t workspace_bytes, void* stream);
 
@@ -220,7 +240,7 @@ int corm_decode_step_lazy(const corm_desc* desc, const void* q, const void* k_ne
                           int32_t* lens, uint64_t* live, int32_t* pos, int32_t* last_hit, const int32_t* t,
                           const int32_t* t_first, void* score_ring, float* out, uint8_t* keep, int32_t* nlive,
                           int32_t dead_num, int32_t dead_den, void* workspace, size_t workspace_bytes,
-                          int32_t* status, void* stream);
+                          int32_t* status, const corm_launch_opts* opts, void* stream);
 
 /* Seeds the recent-query window from a prompt, in place of replaying its last m tokens through
  * corm_decode_step.  The paper starts Algorithm 1 from an existing message and does not say how a prompt
@@ -250,8 +270,8 @@ int corm_prefill_seed(const corm_desc* desc, const void* q_tail, int32_t m, void
 
 /* HIP graph capture.  The step, seeding and standalone calls enqueue kernels only (no allocation, no memset,
  * no host synchronization), so a caller may capture them in a HIP graph on `stream` and replay it with the
- * inputs refreshed in place.  The first call of a process queries the device once (number of compute
- * units): make one call eagerly before capturing.  corm_profile_attend must not be armed during capture. */
+ * inputs refreshed in place.  The first call on a device queries it once (number of compute units): make one
+ * call eagerly before capturing, and pass no events in corm_launch_opts while capturing. */
 
 /* Summary-only state.  corm_decode_attend, corm_step_attend, corm_decode_step, corm_decode_step_lazy and
  * corm_prefill_seed accept score_ring == NULL: the scores are still formed, rounded to score_dtype and
@@ -261,25 +281,9 @@ int corm_prefill_seed(const corm_desc* desc, const void* q_tail, int32_t m, void
  * reads the ring, is then unavailable.  Saves B*Hq*w*Tcap score elements of memory (the paper's own
  * message is w x l booleans; this keeps one int32 per key instead). */
 
-/* Tuning / test knob (host call, process-wide, not thread safe): how attend + record are launched.
- * 0 = choose by shape (default); 1 = split kernels (several workgroups per unit, partials merged by a
- * second launch; grouped bf16 d=128 queries take q.K^T on the matrix cores); 2 = one workgroup per unit
- * with the logits in LDS (taken only if they fit); 3 = as 1 but q.K^T always on the vector ALU.
- * Every path produces the same keep mask, indices and cache; out and the recorded scores agree within
- * fp32 rounding. */
-int corm_force_path(int path);
-
-/* The path (1 or 2, see corm_force_path) the attend/step calls take for this descriptor on the current
- * device; a negative corm_status for a bad descriptor. */
-int corm_selected_path(const corm_desc* desc);
-
-/* Measurement hook (host call, not thread safe): the NEXT corm_decode_attend / corm_step_attend / corm_decode_step call
- * records start_event immediately before and stop_event immediately after its attend launch (the
- * launch that streams K and V: the split attend kernel or the fused unit kernel), on
- * that call's stream, then forgets them.  Both are hipEvent_t handles passed as void*; both NULL
- * cancels.  The attend kernel streams K and V (the step's dominant traffic); this is how its
- * duration is measured in place, without instrumenting any other call. */
-int corm_profile_attend(void* start_event, void* stop_event);
+/* The path (1 or 2, see corm_launch_opts) the attend / step calls take for this descriptor and these options
+ * (NULL = defaults) on the current device; a negative corm_status for a bad descriptor or bad options. */
+int corm_selected_path(const corm_desc* desc, const corm_launch_opts* opts);
 
 /* Diagnostic: thr[i] = fp32(c) / fp32(t[i]) exactly as the kernels compute it (Def. 3.1). */
 int corm_threshold(float c, const int32_t* t, int32_t n, float* thr, void* stream);

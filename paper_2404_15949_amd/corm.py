@@ -23,8 +23,8 @@ CORM_STATIC_SCRATCH_BYTES = 40 << 20
 
 EXPORTS = ("corm_version", "corm_strerror", "corm_workspace_bytes", "corm_workspace_init", "corm_append",
            "corm_decode_attend", "corm_decode_attend_static", "corm_evict_mask", "corm_evict_mask_summary", "corm_row_density", "corm_compact",
-           "corm_decode_step", "corm_step_attend", "corm_step_evict", "corm_decode_step_lazy", "corm_prefill_seed", "corm_force_path",
-           "corm_selected_path", "corm_profile_attend", "corm_threshold")
+           "corm_decode_step", "corm_step_attend", "corm_step_evict", "corm_decode_step_lazy", "corm_prefill_seed",
+           "corm_selected_path", "corm_threshold")
 
 
 class corm_desc(ctypes.Structure):
@@ -32,6 +32,11 @@ class corm_desc(ctypes.Structure):
                 ("Lcap", ctypes.c_int32), ("Tcap", ctypes.c_int32), ("w", ctypes.c_int32), ("r", ctypes.c_int32),
                 ("kv_dtype", ctypes.c_int32), ("score_dtype", ctypes.c_int32),
                 ("thr_scale", ctypes.c_float), ("sm_scale", ctypes.c_float)]
+
+
+class corm_launch_opts(ctypes.Structure):
+    _fields_ = [("path", ctypes.c_int32), ("reserved", ctypes.c_int32),
+                ("attend_start_event", ctypes.c_void_p), ("attend_stop_event", ctypes.c_void_p)]
 
 
 class CormError(RuntimeError):
@@ -53,6 +58,7 @@ def lib() -> ctypes.CDLL:
         L = ctypes.CDLL(LIB_PATH)
         vp, i32p, sz = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t
         dp = ctypes.POINTER(corm_desc)
+        op = ctypes.POINTER(corm_launch_opts)
         L.corm_version.restype = ctypes.c_int
         L.corm_version.argtypes = []
         L.corm_strerror.restype = ctypes.c_char_p
@@ -60,25 +66,23 @@ def lib() -> ctypes.CDLL:
         L.corm_workspace_bytes.argtypes = [dp, ctypes.POINTER(ctypes.c_size_t)]
         L.corm_workspace_init.argtypes = [dp, vp, sz, vp]
         L.corm_append.argtypes = [dp, vp, vp, i32p, i32p, i32p, vp, vp, i32p, i32p, vp]
-        L.corm_decode_attend.argtypes = [dp, vp, vp, vp, i32p, i32p, i32p, vp, i32p, vp, vp, sz, i32p, vp]
-        L.corm_decode_attend_static.argtypes = [dp, vp, vp, vp, i32p, i32p, i32p, vp, i32p, vp, i32p, vp]
+        L.corm_decode_attend.argtypes = [dp, vp, vp, vp, i32p, i32p, i32p, vp, i32p, vp, vp, sz, i32p, op, vp]
+        L.corm_decode_attend_static.argtypes = [dp, vp, vp, vp, i32p, i32p, i32p, vp, i32p, vp, i32p, op, vp]
         L.corm_evict_mask.argtypes = [dp, vp, i32p, i32p, i32p, i32p, vp, vp]
         L.corm_evict_mask_summary.argtypes = [dp, i32p, i32p, i32p, i32p, vp, vp]
         L.corm_row_density.argtypes = [dp, vp, i32p, i32p, i32p, vp, vp]
         L.corm_compact.argtypes = [dp, vp, vp, i32p, i32p, i32p, vp, i32p, vp, sz, vp]
         L.corm_step_attend.argtypes = [dp, vp, vp, vp, vp, vp, i32p, i32p, i32p, i32p, i32p, vp, vp, vp, vp, sz,
-                                       i32p, vp]
+                                       i32p, op, vp]
         L.corm_step_evict.argtypes = [dp, vp, vp, i32p, i32p, i32p, i32p, vp, sz, vp]
-        L.corm_force_path.argtypes = [ctypes.c_int]
-        L.corm_selected_path.argtypes = [dp]
+        L.corm_selected_path.argtypes = [dp, op]
         L.corm_decode_step.argtypes = [dp, vp, vp, vp, vp, vp, i32p, i32p, i32p, i32p, i32p, vp, vp, vp, i32p,
-                                       vp, sz, i32p, vp]
+                                       vp, sz, i32p, op, vp]
         L.corm_decode_step_lazy.argtypes = [dp, vp, vp, vp, vp, vp, i32p, vp, i32p, i32p, i32p, i32p, vp, vp, vp,
-                                            i32p, ctypes.c_int32, ctypes.c_int32, vp, sz, i32p, vp]
+                                            i32p, ctypes.c_int32, ctypes.c_int32, vp, sz, i32p, op, vp]
         L.corm_prefill_seed.argtypes = [dp, vp, ctypes.c_int32, vp, vp, i32p, i32p, i32p, i32p, i32p, vp, vp, i32p,
                                         vp, sz, i32p, vp]
         L.corm_threshold.argtypes = [ctypes.c_float, i32p, ctypes.c_int32, vp, vp]
-        L.corm_profile_attend.argtypes = [vp, vp]
         for name in EXPORTS:
             if name not in ("corm_version", "corm_strerror"):
                 getattr(L, name).restype = ctypes.c_int
@@ -105,6 +109,35 @@ def _stream(stream) -> Optional[int]:
     if isinstance(stream, torch.cuda.Stream):
         return stream.cuda_stream
     return int(stream)
+
+
+# Launch options of the attend / step wrappers below when a call passes none: a setting of this BINDING (the
+# library itself keeps no such state), so that a test fixture or the benchmark can route every call of a
+# run through one launch path.
+_default_path = 0
+
+
+def set_default_path(path: int) -> None:
+    """0 = by shape, 1 = split kernels, 2 = one workgroup per unit, 3 = split kernels without MFMA."""
+    global _default_path
+    if path not in (0, 1, 2, 3):
+        raise ValueError("path must be 0..3")
+    _default_path = path
+
+
+def make_opts(path: Optional[int] = None, attend_events=None) -> corm_launch_opts:
+    """attend_events: (start, stop) raw hipEvent_t handles (ints), recorded around the launch that streams K and V."""
+    ev = attend_events or (None, None)
+    return corm_launch_opts(_default_path if path is None else path, 0, ev[0], ev[1])
+
+
+def _opts(opts):
+    """The pointer argument for a call: the caller's options, or the binding's defaults (NULL when there are none)."""
+    if opts is None:
+        if _default_path == 0:
+            return None
+        opts = make_opts()
+    return ctypes.byref(opts)
 
 
 def _check(code: int, what: str) -> int:
@@ -152,19 +185,19 @@ def corm_append(desc, K, V, lens, pos, last_hit, k_new, v_new, t, status=None, s
 
 
 def corm_decode_attend(desc, q, K, V, lens, pos, t, score_ring, last_hit, out, workspace, workspace_bytes=None,
-                       status=None, stream=None, check=True) -> int:
+                       status=None, stream=None, check=True, opts=None) -> int:
     nbytes = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
     rc = lib().corm_decode_attend(ctypes.byref(desc), _ptr(q), _ptr(K), _ptr(V), _ptr(lens), _ptr(pos), _ptr(t),
                                   _ptr(score_ring), _ptr(last_hit), _ptr(out), _ptr(workspace), nbytes,
-                                  _ptr(status), _stream(stream))
+                                  _ptr(status), _opts(opts), _stream(stream))
     return _check(rc, "corm_decode_attend") if check else rc
 
 
 def corm_decode_attend_static(desc, q, K, V, lens, pos, t, score_ring, last_hit, out, status=None, stream=None,
-                              check=True) -> int:
+                              check=True, opts=None) -> int:
     rc = lib().corm_decode_attend_static(ctypes.byref(desc), _ptr(q), _ptr(K), _ptr(V), _ptr(lens), _ptr(pos),
                                          _ptr(t), _ptr(score_ring), _ptr(last_hit), _ptr(out), _ptr(status),
-                                         _stream(stream))
+                                         _opts(opts), _stream(stream))
     return _check(rc, "corm_decode_attend_static") if check else rc
 
 
@@ -194,11 +227,11 @@ def corm_compact(desc, K, V, pos, last_hit, lens, keep, kept_idx=None, workspace
 
 
 def corm_step_attend(desc, q, k_new, v_new, K, V, lens, pos, last_hit, t, t_first, score_ring, out, keep=None,
-                     workspace=None, workspace_bytes=None, status=None, stream=None, check=True) -> int:
+                     workspace=None, workspace_bytes=None, status=None, stream=None, check=True, opts=None) -> int:
     rc = lib().corm_step_attend(ctypes.byref(desc), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(K), _ptr(V), _ptr(lens),
                                 _ptr(pos), _ptr(last_hit), _ptr(t), _ptr(t_first), _ptr(score_ring), _ptr(out),
                                 _ptr(keep), _ptr(workspace), _nbytes(workspace, workspace_bytes), _ptr(status),
-                                _stream(stream))
+                                _opts(opts), _stream(stream))
     return _check(rc, "corm_step_attend") if check else rc
 
 
@@ -215,40 +248,36 @@ def corm_row_density(desc, score_ring, lens, pos, t, density, stream=None, check
     return _check(rc, "corm_row_density") if check else rc
 
 
-def corm_selected_path(desc) -> int:
-    rc = lib().corm_selected_path(ctypes.byref(desc))
-    if rc < 0:
+def corm_selected_path(desc, opts=None, check=True) -> int:
+    rc = lib().corm_selected_path(ctypes.byref(desc), _opts(opts))
+    if rc < 0 and check:
         raise CormError(rc, "corm_selected_path")
     return rc
 
 
-def corm_force_path(path: int, check=True) -> int:
-    """0 = by shape, 1 = split kernels, 2 = one workgroup per unit, 3 = split kernels without MFMA."""
-    rc = lib().corm_force_path(path)
-    return _check(rc, "corm_force_path") if check else rc
-
-
 def corm_decode_step(desc, q, k_new, v_new, K, V, lens, pos, last_hit, t, t_first, score_ring, out, keep=None,
-                     kept_idx=None, workspace=None, workspace_bytes=None, status=None, stream=None, check=True) -> int:
+                     kept_idx=None, workspace=None, workspace_bytes=None, status=None, stream=None, check=True,
+                     opts=None) -> int:
     nbytes = workspace_bytes
     if nbytes is None:
         nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     rc = lib().corm_decode_step(ctypes.byref(desc), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(K), _ptr(V), _ptr(lens),
                                 _ptr(pos), _ptr(last_hit), _ptr(t), _ptr(t_first), _ptr(score_ring), _ptr(out),
-                                _ptr(keep), _ptr(kept_idx), _ptr(workspace), nbytes, _ptr(status), _stream(stream))
+                                _ptr(keep), _ptr(kept_idx), _ptr(workspace), nbytes, _ptr(status), _opts(opts),
+                                _stream(stream))
     return _check(rc, "corm_decode_step") if check else rc
 
 
 def corm_decode_step_lazy(desc, q, k_new, v_new, K, V, lens, live, pos, last_hit, t, t_first, score_ring, out,
                           keep=None, nlive=None, dead_num=1, dead_den=4, workspace=None, workspace_bytes=None,
-                          status=None, stream=None, check=True) -> int:
+                          status=None, stream=None, check=True, opts=None) -> int:
     nbytes = workspace_bytes
     if nbytes is None:
         nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     rc = lib().corm_decode_step_lazy(ctypes.byref(desc), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(K), _ptr(V),
                                      _ptr(lens), _ptr(live), _ptr(pos), _ptr(last_hit), _ptr(t), _ptr(t_first),
                                      _ptr(score_ring), _ptr(out), _ptr(keep), _ptr(nlive), dead_num, dead_den,
-                                     _ptr(workspace), nbytes, _ptr(status), _stream(stream))
+                                     _ptr(workspace), nbytes, _ptr(status), _opts(opts), _stream(stream))
     return _check(rc, "corm_decode_step_lazy") if check else rc
 
 
@@ -261,12 +290,6 @@ def corm_prefill_seed(desc, q_tail, m, K, V, lens, pos, last_hit, t, t_first, sc
                                  _ptr(last_hit), _ptr(t), _ptr(t_first), _ptr(score_ring), _ptr(keep), _ptr(kept_idx),
                                  _ptr(workspace), nbytes, _ptr(status), _stream(stream))
     return _check(rc, "corm_prefill_seed") if check else rc
-
-
-def corm_profile_attend(start_event, stop_event, check=True) -> int:
-    """start_event / stop_event: raw hipEvent_t handles (ints) or None."""
-    rc = lib().corm_profile_attend(start_event, stop_event)
-    return _check(rc, "corm_profile_attend") if check else rc
 
 
 def corm_threshold(c: float, t, n: int, thr, stream=None, check=True) -> int:
@@ -320,25 +343,26 @@ class LayerState:
         self.last_hit[:, :, :n] = 0
         self.lens.fill_(n)
 
-    def step_attend(self, q, k_new, v_new, t, t_first, stream=None, workspace=None) -> None:
+    def step_attend(self, q, k_new, v_new, t, t_first, stream=None, workspace=None, opts=None) -> None:
         corm_step_attend(self.desc, q, k_new, v_new, self.K, self.V, self.lens, self.pos, self.last_hit, t, t_first,
                          self.ring, self.out, self.keep, self.workspace if workspace is None else workspace,
-                         status=self.status, stream=stream)
+                         status=self.status, stream=stream, opts=opts)
 
     def step_evict(self, stream=None, workspace=None) -> None:
         corm_step_evict(self.desc, self.K, self.V, self.lens, self.pos, self.last_hit, self.kept_idx,
                         self.workspace if workspace is None else workspace, stream=stream)
 
-    def step(self, q, k_new, v_new, t, t_first, stream=None) -> None:
+    def step(self, q, k_new, v_new, t, t_first, stream=None, opts=None) -> None:
         corm_decode_step(self.desc, q, k_new, v_new, self.K, self.V, self.lens, self.pos, self.last_hit, t, t_first,
                          self.ring, self.out, self.keep, self.kept_idx, self.workspace, status=self.status,
-                         stream=stream)
+                         stream=stream, opts=opts)
 
-    def step_lazy(self, q, k_new, v_new, t, t_first, dead_num=1, dead_den=4, stream=None, workspace=None) -> None:
+    def step_lazy(self, q, k_new, v_new, t, t_first, dead_num=1, dead_den=4, stream=None, workspace=None,
+                  opts=None) -> None:
         corm_decode_step_lazy(self.desc, q, k_new, v_new, self.K, self.V, self.lens, self.live, self.pos,
                               self.last_hit, t, t_first, self.ring, self.out, self.keep, self.nlive, dead_num,
                               dead_den, self.workspace if workspace is None else workspace, status=self.status,
-                              stream=stream)
+                              stream=stream, opts=opts)
 
     def prefill_seed(self, q_tail, t, t_first, stream=None, workspace=None) -> None:
         """q_tail [B,Hq,m,d]; the cache must already hold the whole prompt (preload)."""

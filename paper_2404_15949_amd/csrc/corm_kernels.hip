@@ -44,7 +44,6 @@
 static __device__ __align__(256) unsigned char scratch[CORM_STATIC_SCRATCH_BYTES];
 
 namespace {
-constexpr int MAX_DEVICES = 64;
 std::mutex g_scratch_mutex;
 void* g_scratch_ptr[MAX_DEVICES] = {};
 
@@ -119,13 +118,17 @@ int corm_append(const corm_desc* desc, void* K, void* V, int32_t* lens, int32_t*
 
 int corm_decode_attend(const corm_desc* desc, const void* q, const void* K, const void* V, const int32_t* lens,
                        const int32_t* pos, const int32_t* t, void* score_ring, int32_t* last_hit, float* out,
-                       void* workspace, size_t workspace_bytes, int32_t* status, void* stream) {
+                       void* workspace, size_t workspace_bytes, int32_t* status, const corm_launch_opts* opts,
+                       void* stream) {
   int rc = validate_desc(desc);
   if (rc) return rc;
   rc = check_step_pointers(q, K, V, K, V, lens, pos, last_hit, t, t, score_ring, out, nullptr, status);
   if (rc) return rc;
   WorkspaceLayout wl;
   rc = check_workspace(desc, workspace, workspace_bytes, &wl);
+  if (rc) return rc;
+  LaunchCtx ctx;
+  rc = make_ctx(opts, &ctx);
   if (rc) return rc;
   Params p = {};
   p.q = q; p.k_new = K; p.v_new = V;  // k_new/v_new are not read without an append; kept non-null
@@ -134,12 +137,13 @@ int corm_decode_attend(const corm_desc* desc, const void* q, const void* K, cons
   p.t = t; p.t_first = t; p.ring = score_ring; p.out = out; p.status = status;
   p.do_append = 0; p.do_evict = 0;
   bind_params(desc, wl, workspace, p);
-  return launch_attend_record(desc, p, (hipStream_t)stream);
+  return launch_attend_record(desc, p, ctx, (hipStream_t)stream);
 }
 
 int corm_decode_attend_static(const corm_desc* desc, const void* q, const void* K, const void* V,
                               const int32_t* lens, const int32_t* pos, const int32_t* t, void* score_ring,
-                              int32_t* last_hit, float* out, int32_t* status, void* stream) {
+                              int32_t* last_hit, float* out, int32_t* status, const corm_launch_opts* opts,
+                              void* stream) {
   int rc = validate_desc(desc);
   if (rc) return rc;
   rc = check_step_pointers(q, K, V, K, V, lens, pos, last_hit, t, t, score_ring, out, nullptr, status);
@@ -147,6 +151,9 @@ int corm_decode_attend_static(const corm_desc* desc, const void* q, const void* 
   // what attend + record keep in scratch memory: everything in front of the compaction's staging area
   const WorkspaceLayout wl = workspace_layout(*desc);
   if (wl.stage_meta_off > CORM_STATIC_SCRATCH_BYTES) return CORM_ECAPACITY;
+  LaunchCtx ctx;
+  rc = make_ctx(opts, &ctx);
+  if (rc) return rc;
   void* ws = nullptr;
   rc = static_scratch(&ws);
   if (rc) return rc;
@@ -157,7 +164,7 @@ int corm_decode_attend_static(const corm_desc* desc, const void* q, const void* 
   p.t = t; p.t_first = t; p.ring = score_ring; p.out = out; p.status = status;
   p.do_append = 0; p.do_evict = 0;
   bind_params(desc, wl, ws, p);
-  return launch_attend_record(desc, p, (hipStream_t)stream);
+  return launch_attend_record(desc, p, ctx, (hipStream_t)stream);
 }
 
 int corm_evict_mask(const corm_desc* desc, const void* score_ring, const int32_t* lens, const int32_t* pos,
@@ -217,7 +224,7 @@ int corm_compact(const corm_desc* desc, void* K, void* V, int32_t* pos, int32_t*
 int corm_step_attend(const corm_desc* desc, const void* q, const void* k_new, const void* v_new, void* K, void* V,
                      const int32_t* lens, int32_t* pos, int32_t* last_hit, const int32_t* t, const int32_t* t_first,
                      void* score_ring, float* out, uint8_t* keep, void* workspace, size_t workspace_bytes,
-                     int32_t* status, void* stream) {
+                     int32_t* status, const corm_launch_opts* opts, void* stream) {
   int rc = validate_desc(desc);
   if (rc) return rc;
   rc = check_step_pointers(q, k_new, v_new, K, V, lens, pos, last_hit, t, t_first, score_ring, out, nullptr, status);
@@ -225,13 +232,16 @@ int corm_step_attend(const corm_desc* desc, const void* q, const void* k_new, co
   WorkspaceLayout wl;
   rc = check_workspace(desc, workspace, workspace_bytes, &wl);
   if (rc) return rc;
+  LaunchCtx ctx;
+  rc = make_ctx(opts, &ctx);
+  if (rc) return rc;
   Params p = {};
   p.q = q; p.k_new = k_new; p.v_new = v_new; p.K = K; p.V = V; p.lens = const_cast<int32_t*>(lens); p.pos = pos;
   p.last_hit = last_hit; p.t = t; p.t_first = t_first; p.ring = score_ring; p.out = out; p.keep = keep;
   p.status = status;
   p.do_append = 1; p.do_evict = 1;
   bind_params(desc, wl, workspace, p);
-  return launch_attend_record(desc, p, (hipStream_t)stream);
+  return launch_attend_record(desc, p, ctx, (hipStream_t)stream);
 }
 
 int corm_step_evict(const corm_desc* desc, void* K, void* V, int32_t* lens, int32_t* pos, int32_t* last_hit,
@@ -252,12 +262,12 @@ int corm_step_evict(const corm_desc* desc, void* K, void* V, int32_t* lens, int3
 int corm_decode_step(const corm_desc* desc, const void* q, const void* k_new, const void* v_new, void* K, void* V,
                      int32_t* lens, int32_t* pos, int32_t* last_hit, const int32_t* t, const int32_t* t_first,
                      void* score_ring, float* out, uint8_t* keep, int32_t* kept_idx, void* workspace,
-                     size_t workspace_bytes, int32_t* status, void* stream) {
+                     size_t workspace_bytes, int32_t* status, const corm_launch_opts* opts, void* stream) {
   int rc = validate_desc(desc);
   if (rc) return rc;
   if (misaligned4(kept_idx)) return CORM_EINVAL;
   rc = corm_step_attend(desc, q, k_new, v_new, K, V, lens, pos, last_hit, t, t_first, score_ring, out, keep,
-                        workspace, workspace_bytes, status, stream);
+                        workspace, workspace_bytes, status, opts, stream);
   if (rc) return rc;
   return corm_step_evict(desc, K, V, lens, pos, last_hit, kept_idx, workspace, workspace_bytes, stream);
 }
@@ -266,7 +276,7 @@ int corm_decode_step_lazy(const corm_desc* desc, const void* q, const void* k_ne
                           int32_t* lens, uint64_t* live, int32_t* pos, int32_t* last_hit, const int32_t* t,
                           const int32_t* t_first, void* score_ring, float* out, uint8_t* keep, int32_t* nlive,
                           int32_t dead_num, int32_t dead_den, void* workspace, size_t workspace_bytes,
-                          int32_t* status, void* stream) {
+                          int32_t* status, const corm_launch_opts* opts, void* stream) {
   int rc = validate_desc(desc);
   if (rc) return rc;
   rc = check_step_pointers(q, k_new, v_new, K, V, lens, pos, last_hit, t, t_first, score_ring, out, nlive, status);
@@ -276,6 +286,9 @@ int corm_decode_step_lazy(const corm_desc* desc, const void* q, const void* k_ne
   WorkspaceLayout wl;
   rc = check_workspace(desc, workspace, workspace_bytes, &wl);
   if (rc) return rc;
+  LaunchCtx ctx;
+  rc = make_ctx(opts, &ctx);
+  if (rc) return rc;
   Params p = {};
   p.q = q; p.k_new = k_new; p.v_new = v_new; p.K = K; p.V = V; p.lens = lens; p.pos = pos;
   p.last_hit = last_hit; p.t = t; p.t_first = t_first; p.ring = score_ring; p.out = out; p.keep = keep;
@@ -284,7 +297,7 @@ int corm_decode_step_lazy(const corm_desc* desc, const void* q, const void* k_ne
   bind_params(desc, wl, workspace, p);
   p.lazy = 1;
   p.keepbits = reinterpret_cast<unsigned long long*>(live);   // the live masks are read, then replaced by the new ones
-  rc = launch_attend_record(desc, p, (hipStream_t)stream);
+  rc = launch_attend_record(desc, p, ctx, (hipStream_t)stream);
   if (rc) return rc;
   CompactPolicy pol;
   pol.lazy = 1; pol.dead_num = dead_num; pol.dead_den = dead_den;
@@ -347,23 +360,13 @@ int corm_prefill_seed(const corm_desc* desc, const void* q_tail, int32_t m, void
   return launch_compact(desc, wl, workspace, K, V, pos, last_hit, lens, nullptr, kept_idx, 0, false, CompactPolicy(), s);
 }
 
-int corm_selected_path(const corm_desc* desc) {
-  const int rc = validate_desc(desc);
+int corm_selected_path(const corm_desc* desc, const corm_launch_opts* opts) {
+  int rc = validate_desc(desc);
   if (rc) return rc;
-  return use_unit_path(desc) ? 2 : 1;
-}
-
-int corm_force_path(int path) {
-  if (path < 0 || path > 3) return CORM_EINVAL;
-  g_force_path = path;
-  return CORM_OK;
-}
-
-int corm_profile_attend(void* start_event, void* stop_event) {
-  if ((start_event == nullptr) != (stop_event == nullptr)) return CORM_EINVAL;
-  g_prof_start = (hipEvent_t)start_event;
-  g_prof_stop = (hipEvent_t)stop_event;
-  return CORM_OK;
+  LaunchCtx ctx;
+  rc = make_ctx(opts, &ctx);
+  if (rc) return rc;
+  return use_unit_path(desc, ctx) ? 2 : 1;
 }
 
 int corm_threshold(float c, const int32_t* t, int32_t n, float* thr, void* stream) {

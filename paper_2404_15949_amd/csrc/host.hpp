@@ -62,8 +62,45 @@ bool misaligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) !
 
 int launch_status() { return hipGetLastError() == hipSuccess ? CORM_OK : CORM_EHIP; }
 
-// optional events recorded around the attend launch of the next step call (corm_profile_attend)
-hipEvent_t g_prof_start = nullptr, g_prof_stop = nullptr;
+// Per-call launch context: what corm_launch_opts asks for, plus the compute-unit count of the current
+// device.  Nothing here outlives the call.
+struct LaunchCtx {
+  int path = 0;                               // 0 = choose by shape, 1 = split kernels (attend + record), 2 = fused
+                                              // unit kernel, 3 = split kernels with q.K^T on the vector ALU even
+                                              // where the MFMA kernel applies
+  hipEvent_t ev0 = nullptr, ev1 = nullptr;    // recorded around the launch that streams K and V
+  int cus = 256;
+};
+
+// Compute units of the current device, asked once per device (thread safe); 256 where no device answers.
+constexpr int MAX_DEVICES = 64;
+std::mutex g_device_mutex;
+int g_device_cus[MAX_DEVICES] = {};
+
+int device_cus() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return 256;
+  std::lock_guard<std::mutex> lock(g_device_mutex);
+  if (g_device_cus[dev] == 0) {
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) n = 256;
+    g_device_cus[dev] = n;
+  }
+  return g_device_cus[dev];
+}
+
+int make_ctx(const corm_launch_opts* o, LaunchCtx* c) {
+  *c = LaunchCtx();
+  if (o) {
+    if (o->path < 0 || o->path > 3) return CORM_EINVAL;
+    if ((o->attend_start_event == nullptr) != (o->attend_stop_event == nullptr)) return CORM_EINVAL;
+    c->path = o->path;
+    c->ev0 = (hipEvent_t)o->attend_start_event;
+    c->ev1 = (hipEvent_t)o->attend_stop_event;
+  }
+  c->cus = device_cus();
+  return CORM_OK;
+}
 
 int check_workspace(const corm_desc* d, void* workspace, size_t workspace_bytes, WorkspaceLayout* wl) {
   *wl = workspace_layout(*d);
@@ -92,11 +129,6 @@ void bind_params(const corm_desc* d, const WorkspaceLayout& wl, void* workspace,
   p.ring_words = (d->Tcap + 31) / 32;
 }
 
-// 0 = choose by shape, 1 = split kernels (attend + record), 2 = fused unit kernel,
-// 3 = split kernels with q.K^T on the vector ALU even where the MFMA kernel applies
-int g_force_path = 0;
-int g_num_cus = 0;
-
 template <typename DT, int D, bool LAZY>
 int launch_attend_g(const Params& p, int G, dim3 grid, hipStream_t s) {
   switch (G) {
@@ -121,23 +153,21 @@ int launch_attend_gqa(const Params& p, int G, dim3 grid, hipStream_t s) {
 }
 
 template <bool LAZY>
-int launch_attend_dt(const corm_desc* d, const Params& p, int G, dim3 grid, hipStream_t s) {
+int launch_attend_dt(const corm_desc* d, const Params& p, const LaunchCtx& c, int G, dim3 grid, hipStream_t s) {
   if (d->kv_dtype == CORM_F32)
     return d->d == 64 ? launch_attend_g<F32, 64, LAZY>(p, G, grid, s) : launch_attend_g<F32, 128, LAZY>(p, G, grid, s);
   // grouped queries, bf16, d = 128: q.K^T on the matrix cores
-  if (d->d == 128 && G > 1 && g_force_path != 3) return launch_attend_gqa<LAZY>(p, G, grid, s);
+  if (d->d == 128 && G > 1 && c.path != 3) return launch_attend_gqa<LAZY>(p, G, grid, s);
   return d->d == 64 ? launch_attend_g<BF16, 64, LAZY>(p, G, grid, s) : launch_attend_g<BF16, 128, LAZY>(p, G, grid, s);
 }
 
-int launch_attend(const corm_desc* d, const Params& p, hipStream_t s) {
+int launch_attend(const corm_desc* d, const Params& p, const LaunchCtx& c, hipStream_t s) {
   const int G = d->Hq / d->Hkv;
   const dim3 grid((d->Lcap + p.part_keys - 1) / p.part_keys, d->B * d->Hkv);
-  const hipEvent_t ev0 = g_prof_start, ev1 = g_prof_stop;
-  g_prof_start = g_prof_stop = nullptr;
-  if (ev0 && hipEventRecord(ev0, s) != hipSuccess) return CORM_EHIP;
-  const int rc = p.lazy ? launch_attend_dt<true>(d, p, G, grid, s) : launch_attend_dt<false>(d, p, G, grid, s);
+  if (c.ev0 && hipEventRecord(c.ev0, s) != hipSuccess) return CORM_EHIP;
+  const int rc = p.lazy ? launch_attend_dt<true>(d, p, c, G, grid, s) : launch_attend_dt<false>(d, p, c, G, grid, s);
   if (rc) return rc;
-  if (ev1 && hipEventRecord(ev1, s) != hipSuccess) return CORM_EHIP;
+  if (c.ev1 && hipEventRecord(c.ev1, s) != hipSuccess) return CORM_EHIP;
   return CORM_OK;
 }
 
@@ -151,27 +181,20 @@ size_t unit_lds_bytes(const corm_desc* d, int* lstride) {
 
 // The unit kernel needs the unit's logits in LDS (48 KiB of dynamic LDS at most here, so that two
 // workgroups fit a compute unit) and pays off once there are at least as many units as compute units.
-bool use_unit_path(const corm_desc* d) {
+bool use_unit_path(const corm_desc* d, const LaunchCtx& c) {
   int lstride;
   const bool fits = unit_lds_bytes(d, &lstride) <= 48 * 1024 && d->Hq / d->Hkv <= 4;  // G = 8 exceeds the register file
-  if (g_force_path == 1 || g_force_path == 3 || !fits) return false;
-  if (g_force_path == 2) return true;
-  if (g_num_cus == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-      n = 256;
-    g_num_cus = n;
-  }
-  return d->B * d->Hkv >= g_num_cus;
+  if (c.path == 1 || c.path == 3 || !fits) return false;
+  if (c.path == 2) return true;
+  return d->B * d->Hkv >= c.cus;
 }
 
 template <typename DT, int D, bool LAZY>
-int launch_unit_g(const Params& p, int G, int units, size_t lds, int lstride, hipStream_t s) {
+int launch_unit_g(const Params& p, const LaunchCtx& c, int G, int units, size_t lds, int lstride, hipStream_t s) {
   // grouped queries: the small-stage instance (two workgroups per compute unit) once there are two units per
   // compute unit; measured on 32 query / 8 KV heads: 1024 units 161 -> 134 us per step, 512 units 139 -> 133 us,
   // but 256 units 81 -> 91 us
-  const bool small = (long)p.B * p.Hkv >= 2L * (g_num_cus > 0 ? g_num_cus : 256);
+  const bool small = (long)p.B * p.Hkv >= 2L * c.cus;
   const dim3 grid(units), wg(UNIT_WG);
   switch (G) {
     case 1: hipLaunchKernelGGL((corm_unit_kernel<DT, D, 1, LAZY, UNROLL>), grid, wg, lds, s, p, lstride); break;
@@ -189,31 +212,30 @@ int launch_unit_g(const Params& p, int G, int units, size_t lds, int lstride, hi
 }
 
 template <bool LAZY>
-int launch_unit_dt(const corm_desc* d, const Params& p, int G, int units, size_t lds, int lstride, hipStream_t s) {
+int launch_unit_dt(const corm_desc* d, const Params& p, const LaunchCtx& c, int G, int units, size_t lds, int lstride,
+                   hipStream_t s) {
   if (d->kv_dtype == CORM_F32)
-    return d->d == 64 ? launch_unit_g<F32, 64, LAZY>(p, G, units, lds, lstride, s)
-                      : launch_unit_g<F32, 128, LAZY>(p, G, units, lds, lstride, s);
-  return d->d == 64 ? launch_unit_g<BF16, 64, LAZY>(p, G, units, lds, lstride, s)
-                    : launch_unit_g<BF16, 128, LAZY>(p, G, units, lds, lstride, s);
+    return d->d == 64 ? launch_unit_g<F32, 64, LAZY>(p, c, G, units, lds, lstride, s)
+                      : launch_unit_g<F32, 128, LAZY>(p, c, G, units, lds, lstride, s);
+  return d->d == 64 ? launch_unit_g<BF16, 64, LAZY>(p, c, G, units, lds, lstride, s)
+                    : launch_unit_g<BF16, 128, LAZY>(p, c, G, units, lds, lstride, s);
 }
 
-int launch_unit(const corm_desc* d, const Params& p, hipStream_t s) {
+int launch_unit(const corm_desc* d, const Params& p, const LaunchCtx& c, hipStream_t s) {
   int lstride;
   const size_t lds = unit_lds_bytes(d, &lstride);
   const int G = d->Hq / d->Hkv;
   const int units = (d->B * d->Hkv + UNIT_XCDS - 1) / UNIT_XCDS * UNIT_XCDS;   // grid: whole rounds over the XCDs
-  const hipEvent_t ev0 = g_prof_start, ev1 = g_prof_stop;
-  g_prof_start = g_prof_stop = nullptr;
-  if (ev0 && hipEventRecord(ev0, s) != hipSuccess) return CORM_EHIP;
-  const int rc = p.lazy ? launch_unit_dt<true>(d, p, G, units, lds, lstride, s)
-                        : launch_unit_dt<false>(d, p, G, units, lds, lstride, s);
+  if (c.ev0 && hipEventRecord(c.ev0, s) != hipSuccess) return CORM_EHIP;
+  const int rc = p.lazy ? launch_unit_dt<true>(d, p, c, G, units, lds, lstride, s)
+                        : launch_unit_dt<false>(d, p, c, G, units, lds, lstride, s);
   if (rc) return rc;
-  if (ev1 && hipEventRecord(ev1, s) != hipSuccess) return CORM_EHIP;
+  if (c.ev1 && hipEventRecord(c.ev1, s) != hipSuccess) return CORM_EHIP;
   return CORM_OK;
 }
 
 // append (if p.do_append) + attend + record: one fused launch or the attend / record pair
-int launch_attend_record(const corm_desc* d, const Params& p, hipStream_t s);
+int launch_attend_record(const corm_desc* d, const Params& p, const LaunchCtx& c, hipStream_t s);
 
 template <int RC>
 int launch_record_rc(const corm_desc* d, const Params& p, hipStream_t s) {
@@ -229,10 +251,10 @@ int launch_record_rc(const corm_desc* d, const Params& p, hipStream_t s) {
   return launch_status();
 }
 
-int launch_record(const corm_desc* d, const Params& p, hipStream_t s) {
+int launch_record(const corm_desc* d, const Params& p, const LaunchCtx& c, hipStream_t s) {
   // the largest workgroup that still leaves about four workgroups per compute unit
   const long units = (long)d->B * d->Hkv;
-  const long want = 4L * (g_num_cus > 0 ? g_num_cus : 256);
+  const long want = 4L * c.cus;
   if (units * ((p.nsplit + 3) / 4) >= want) return launch_record_rc<4>(d, p, s);
   if (units * ((p.nsplit + 1) / 2) >= want) return launch_record_rc<2>(d, p, s);
   return launch_record_rc<1>(d, p, s);
@@ -241,24 +263,24 @@ int launch_record(const corm_desc* d, const Params& p, hipStream_t s) {
 // Keys per attend workgroup on the split path: a whole chunk, or a half / a quarter of one while the
 // launch would otherwise have fewer than about two workgroups per compute unit.  A part must hold whole
 // pairs of pipeline stages of the kernel that runs.
-int attend_part_keys(const corm_desc* d) {
+int attend_part_keys(const corm_desc* d, const LaunchCtx& c) {
   const int G = d->Hq / d->Hkv;
-  const bool mfma = d->kv_dtype == CORM_BF16 && d->d == 128 && G > 1 && g_force_path != 3;
+  const bool mfma = d->kv_dtype == CORM_BF16 && d->d == 128 && G > 1 && c.path != 3;
   const int stage_rows = mfma ? WAVES * 16 : WAVES * (64 / (row_bytes(d) / 16)) * UNROLL;
-  const long want = 2L * (g_num_cus > 0 ? g_num_cus : 256);
+  const long want = 2L * c.cus;
   const long wgs = (long)d->B * d->Hkv * ((d->Lcap + CHUNK - 1) / CHUNK);
   int part = CHUNK;
   while (part / 2 >= 2 * stage_rows && CHUNK / (part / 2) <= MAX_PARTS_PER_CHUNK && wgs * (CHUNK / part) < want) part /= 2;
   return part;
 }
 
-int launch_attend_record(const corm_desc* d, const Params& p0, hipStream_t s) {
-  if (use_unit_path(d)) return launch_unit(d, p0, s);
+int launch_attend_record(const corm_desc* d, const Params& p0, const LaunchCtx& c, hipStream_t s) {
+  if (use_unit_path(d, c)) return launch_unit(d, p0, c, s);
   Params p = p0;
-  p.part_keys = attend_part_keys(d);
-  const int rc = launch_attend(d, p, s);
+  p.part_keys = attend_part_keys(d, c);
+  const int rc = launch_attend(d, p, c, s);
   if (rc) return rc;
-  return launch_record(d, p, s);
+  return launch_record(d, p, c, s);
 }
 
 // Policy of the compaction launches: exact mode compacts every unit that lost a key; lazy mode only

@@ -33,7 +33,7 @@ using workspace_bytes_fn = int (*)(const corm_desc*, size_t*);
 using workspace_init_fn = int (*)(const corm_desc*, void*, size_t, void*);
 using decode_step_fn = int (*)(const corm_desc*, const void*, const void*, const void*, void*, void*, int32_t*,
                                int32_t*, int32_t*, const int32_t*, const int32_t*, void*, float*, uint8_t*,
-                               int32_t*, void*, size_t, int32_t*, void*);
+                               int32_t*, void*, size_t, int32_t*, const corm_launch_opts*, void*);
 using strerror_fn = const char* (*)(int);
 
 // deterministic inputs: a small linear congruential generator mapped to (-1, 1)
@@ -163,7 +163,7 @@ int run(void* lib, float c, int P, int steps) {
     HIP_OK(hipMemcpy(vn, hvn.data(), hvn.size() * 4, hipMemcpyHostToDevice));
     HIP_OK(hipMemcpy(t, ht.data(), B * 4, hipMemcpyHostToDevice));
     rc = step_fn(&desc, q, kn, vn, K, V, lens, pos, last_hit, t, tf, ring, out, nullptr, nullptr, ws, wsb, status,
-                 nullptr);
+                 nullptr, nullptr);
     if (rc != CORM_OK) {
       std::printf("FAIL corm_decode_step: %s\n", err_str(rc));
       return 1;

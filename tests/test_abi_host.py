@@ -95,11 +95,52 @@ def test_null_and_misaligned_pointers_are_rejected_on_the_host():
     assert corm.corm_step_attend(d, a, a, a, a, a, a, a, a, None, a, a, a, workspace=a, workspace_bytes=1 << 30,
                                  check=False) == corm.CORM_EINVAL
     assert corm.corm_step_evict(d, a, a, None, a, a, workspace=a, workspace_bytes=1 << 30, check=False) == corm.CORM_EINVAL
-    assert corm.corm_force_path(4, check=False) == corm.CORM_EINVAL
-    assert corm.corm_force_path(0) == corm.CORM_OK
+    # launch options: a path outside 0..3, or one event without the other
+    bad = corm.corm_launch_opts(4, 0, None, None)
+    assert corm.corm_decode_step(d, *[args[k] for k in order], workspace=a, workspace_bytes=1 << 30, check=False,
+                                 opts=bad) == corm.CORM_EINVAL
+    one = corm.corm_launch_opts(0, 0, a, None)
+    assert corm.corm_decode_step(d, *[args[k] for k in order], workspace=a, workspace_bytes=1 << 30, check=False,
+                                 opts=one) == corm.CORM_EINVAL
+    assert corm.corm_selected_path(d, bad, check=False) == corm.CORM_EINVAL
     assert corm.corm_evict_mask(d, a, a, a, a, None, a, check=False) == corm.CORM_EINVAL
     assert corm.corm_append(d, a, a, a, a, a, a + 4, a, a, check=False) == corm.CORM_EINVAL
     assert corm.corm_threshold(-1.0, a, 4, a, check=False) == corm.CORM_EINVAL
+
+
+def test_two_threads_with_different_options_do_not_see_each_other():
+    """What a call does depends on its arguments alone: two host threads that ask, in a tight loop, for
+    different launch paths, different shapes' workspace sizes and different argument errors each get their
+    own answers every time (ctypes releases the interpreter lock during a call, so the calls do overlap)."""
+    import threading
+    small, large = _desc(), _desc(B=64, Hq=32, Hkv=32, Lcap=4096, Tcap=4096)
+    n_small, n_large = corm.corm_workspace_bytes(small), corm.corm_workspace_bytes(large)
+    assert n_small != n_large
+    a = 4096
+    failures = []
+
+    def worker(path, desc, want_bytes, bad_opts):
+        opts = corm.corm_launch_opts(path, 0, None, None)
+        for _ in range(3000):
+            got = corm.corm_selected_path(desc, opts)
+            if got != path:
+                failures.append(("path", path, got))
+            if corm.corm_workspace_bytes(desc) != want_bytes:
+                failures.append(("bytes", path))
+            rc = corm.corm_decode_attend(desc, a, a, a, a, a, a, a, a, a, a, workspace_bytes=1 << 40, check=False,
+                                         opts=bad_opts)
+            if rc != corm.CORM_EINVAL:
+                failures.append(("opts", path, rc))
+
+    th = [threading.Thread(target=worker, args=(1, small, n_small, corm.corm_launch_opts(7, 0, None, None))),
+          threading.Thread(target=worker, args=(2, large, n_large, corm.corm_launch_opts(2, 0, None, a)))]
+    for t in th:
+        t.start()
+    for t in th:
+        t.join()
+    assert not failures, failures[:5]
+    # by shape (path 0), with no device to ask: 256 compute units are assumed
+    assert corm.corm_selected_path(small) == 1 and corm.corm_selected_path(large) == 2
 
 
 def test_static_scratch_entry_checks_its_arguments_and_its_limit_on_the_host():

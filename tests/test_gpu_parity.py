@@ -18,9 +18,9 @@ W = inputs.WORKLOADS
 def launch_path(request):
     """Every test runs with both ways of launching attend + record: split kernels (several workgroups
     per unit) and the fused one-workgroup-per-unit kernel."""
-    corm.corm_force_path({"split": 1, "unit": 2, "split_valu": 3}[request.param])
+    corm.set_default_path({"split": 1, "unit": 2, "split_valu": 3}[request.param])
     yield request.param
-    corm.corm_force_path(0)
+    corm.set_default_path(0)
 
 
 def say(*a):
@@ -951,3 +951,18 @@ def test_bench_prints_one_json_line_with_the_required_fields(launch_path):
     for key in ("value", "unit", "cores", "kind", "sample"):
         assert key in r["cpu_baseline"], key
     assert r["cpu_baseline"]["kind"] == "oracle" and r["cpu_baseline"]["value"] > 0
+    assert r["cpu_baseline"]["cores"] == os.cpu_count() and 1 <= r["cpu_baseline"]["threads"] <= 16
+    assert r["config"]["streams"] == 1 and "sequence" in r["value_is"] and "traffic_source" in r["roofline"]
+    assert r["overlapped"]["streams"] == 3 and r["overlapped"]["steps_per_s"] > 0 and r["eviction_heavy"] is None
+    # two layers of the headline shape: the eviction-heavy leg runs too, and really evicts
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--layers", "2", "--steps", "3", "--warmup", "1",
+                          "--cpu-units", "2", "--cpu-steps", "2"], capture_output=True, text=True, timeout=280)
+    assert res.returncode == 0, res.stderr[-600:]
+    r = json.loads([ln for ln in res.stdout.splitlines() if ln.strip()][-1])
+    assert r["config"]["workload"] == "llama7b_b16" and r["roofline"]["kernel"] == "corm_unit_kernel"
+    assert r["roofline"]["bytes_per_key"] == 2 * 128 * 2 + 2 + 8
+    eh = r["eviction_heavy"]
+    for mode in ("compaction_at_every_step", "deferred_compaction_1_4"):
+        assert eh[mode]["steps_per_s"] > 0 and 0.2 < eh[mode]["live_fraction_end"] < 0.6, (mode, eh[mode])
+        assert eh[mode]["live_fraction_per_head"]["min"] < eh[mode]["live_fraction_per_head"]["max"]
+    assert eh["compaction_at_every_step"]["keys_evicted"] > 0 and eh["compaction_at_every_step"]["moved_bytes_per_step"] > 0
