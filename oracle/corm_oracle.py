@@ -147,8 +147,8 @@ def long_term_minor(notes: np.ndarray, positions: np.ndarray) -> np.ndarray:
     notes [n, G, width]: the notes of the n most recent queries (see ``note_of_query``).
     A key is a long-term minor key iff no head of its group found it important in any of them.
     """
-    found_by_someone = notes[:, :, positions].any(axis=(0, 1))
-    return ~found_by_someone
+    found_by_someone = notes.any(axis=(0, 1))          # per absolute position: some head, in some note
+    return ~found_by_someone[positions]
 
 
 def survivors(notes: np.ndarray, positions: np.ndarray, w: int, r: int) -> np.ndarray:

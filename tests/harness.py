@@ -10,6 +10,8 @@ rows, positions and the ring window), computes one step, and is compared the sam
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
 from typing import Dict, List, Optional, Sequence, Tuple
 
 import numpy as np
@@ -162,24 +164,18 @@ def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_sca
         u.preload(_f32(x_cpu["K0"][b, h, :pre]), _f32(x_cpu["V0"][b, h, :pre]), first_position=int(offs[b]))
         oracles[(b, h)] = u
     t_first = (torch.full((wl.B,), pre + 1, dtype=torch.int32, device=device) + offs_dev)
-    tol = OUT_TOL[wl.dtype]
-    worst_out = 0.0
-    worst_score = 0.0
-    flips = 0
-    evicted_total = 0
-    compactions = 0
-    cap = st.Lcap
-    slots_before = {u: np.arange(pre) for u in units}     # lazy mode: live slots and slots in use before a step
-    used_before = {u: pre for u in units}
+    slaves = Slaves(wl, st, oracles, units, offs, thr_scale, lazy,
+                    slots_before={u: np.arange(pre) for u in units}, used_before={u: pre for u in units})
     j_first = 0
     if seed_kernel:
         assert not use_split_calls and n_steps >= n_replay
         j_first = n_replay
-        worst_score = _seed_with_kernel(wl, st, x, x_cpu, oracles, units, offs, offs_dev, n_replay, t_first, thr_scale)
-        evicted_total += sum(wl.P - oracles[u].l for u in units)
+        slaves.worst_score = _seed_with_kernel(wl, st, x, x_cpu, oracles, units, offs, offs_dev, n_replay, t_first,
+                                               thr_scale)
+        slaves.evicted_total += sum(wl.P - oracles[u].l for u in units)
         for u in units:     # the seeding call leaves every unit compacted: slots 0 .. l-1 hold the live keys
-            slots_before[u] = np.arange(oracles[u].l)
-            used_before[u] = oracles[u].l
+            slaves.slots_before[u] = np.arange(oracles[u].l)
+            slaves.used_before[u] = oracles[u].l
     for j in range(j_first, n_steps):
         q, k, v, t = step_inputs(wl, x, j, n_replay)
         t_dev = torch.full((wl.B,), t, dtype=torch.int32, device=device) + offs_dev
@@ -199,63 +195,147 @@ def run_slaved_trajectory(wl: inputs.Workload, device="cuda:0", layer=0, thr_sca
             st.step_lazy(q, k, v, t_dev, t_first, dead_num=lazy[0], dead_den=lazy[1])
         else:
             st.step(q, k, v, t_dev, t_first)
+        slaves.after_step(j, q, k, v, t,
+                          check_state=bool(check_state_every) and ((j + 1) % check_state_every == 0 or j == n_steps - 1))
+    return slaves.report(n_steps)
+
+
+class Slaves:
+    """One oracle per checked unit, slaved to the device: after every device step each oracle takes the same
+    step, fed the scores the device recorded, and is compared with what the device left (keep mask, kept
+    indices, lens bit for bit; out and the recorded scores within tolerance; every importance decision that
+    differs from the fp64 one within the score tolerance of c/t).  The oracles of different units are
+    independent, so they step on a pool of host threads (numpy releases the interpreter lock)."""
+
+    def __init__(self, wl, st, oracles, units, offs, thr_scale, lazy, slots_before, used_before, threads=None):
+        self.wl, self.st, self.oracles, self.units, self.offs = wl, st, oracles, list(units), offs
+        self.thr_scale, self.lazy = thr_scale, lazy
+        self.slots_before, self.used_before = slots_before, used_before   # lazy mode: live slots / slots in use
+        self.worst_out = self.worst_score = 0.0
+        self.flips = self.evicted_total = self.compactions = 0
+        n = min(16, os.cpu_count() or 1) if threads is None else threads
+        self.pool = ThreadPoolExecutor(max_workers=n) if n > 1 and len(self.units) > 1 else None
+
+    def after_step(self, j, q, k, v, t, check_state=True):
+        wl, st, lazy, thr_scale, G = self.wl, self.st, self.lazy, self.thr_scale, self.wl.G
         torch.cuda.synchronize()
         assert int(st.status.item()) == 0, ("device status", int(st.status.item()), j)
-        ring_all = st.ring
         out = st.out.cpu().numpy()
         keep_d = st.keep.cpu().numpy()
         idx_d = st.kept_idx.cpu().numpy()
         lens_d = st.lens.cpu().numpy()
+        live_d = st.live.cpu().numpy() if lazy is not None else None
         qc, kc, vc = _f32(q), _f32(k), _f32(v)
-        ring_rows = {}
-        for (b, h) in units:
-            u = oracles[(b, h)]
-            tb = t + int(offs[b])
-            if b not in ring_rows:
-                ring_rows[b] = ring_row(st, b, (tb - 1) % wl.w)              # [Hq, Tcap]
+        ring_rows = {b: ring_row(st, b, (t + int(self.offs[b]) - 1) % wl.w) for b in sorted({u[0] for u in self.units})}
+        tol = OUT_TOL[wl.dtype]
+        cap = st.Lcap
+
+        def one(unit):
+            b, h = unit
+            u = self.oracles[unit]
+            tb = t + int(self.offs[b])
             live_pos = np.concatenate([u.positions, [tb - 1]])
             recorded = ring_rows[b][h * G:(h + 1) * G][:, live_pos]
             res = u.step(qc[b, h * G:(h + 1) * G], kc[b, h], vc[b, h], tb, recorded=recorded)
             l = len(live_pos)
+            compacted = 0
             if lazy is None:
                 assert np.array_equal(keep_d[b, h, :l].astype(bool), res["keep"]), ("keep", j, b, h)
                 assert int(lens_d[b, h]) == u.l, ("lens", j, b, h, int(lens_d[b, h]), u.l)
                 assert np.array_equal(idx_d[b, h, :u.l].astype(np.int64), res["indices"]), ("kept_idx", j, b, h)
             else:
-                L = used_before[(b, h)] + 1                                   # slots in use after the append
-                sl = np.concatenate([slots_before[(b, h)], [L - 1]])           # slots of the oracle's keys
+                L = self.used_before[unit] + 1                                # slots in use after the append
+                sl = np.concatenate([self.slots_before[unit], [L - 1]])        # slots of the oracle's keys
                 kd = keep_d[b, h, :L].astype(bool)
                 assert np.array_equal(kd[sl], res["keep"]), ("keep (live slots)", j, b, h)
                 assert int(kd.sum()) == int(res["keep"].sum()), ("a dead slot was revived", j, b, h)
                 T = u.l
                 want_compact = T < L and ((L - T) * lazy[1] >= L * lazy[0] or L + 1 >= cap)
                 assert int(lens_d[b, h]) == (T if want_compact else L), ("lens / policy", j, b, h, L, T)
-                compactions += int(want_compact)
-                now = live_slots(st, b, h)
+                compacted = int(want_compact)
+                bits = np.unpackbits(live_d[b, h].view(np.uint8), bitorder="little")[:int(lens_d[b, h])]
+                now = np.nonzero(bits)[0]
                 assert np.array_equal(now, np.arange(T) if want_compact else sl[res["keep"]]), ("live", j, b, h)
-                slots_before[(b, h)] = now
-                used_before[(b, h)] = int(lens_d[b, h])
-            evicted_total += l - u.l
+                self.slots_before[unit] = now
+                self.used_before[unit] = int(lens_d[b, h])
+            w_out = w_score = 0.0
             for g in range(G):
                 e = out_rel_err(out[b, h * G + g].astype(np.float64), res["out"][g])
-                worst_out = max(worst_out, e)
+                w_out = max(w_out, e)
                 assert e <= tol, ("out", j, b, h, g, e)
-                worst_score = max(worst_score, check_recorded(wl, st, recorded[g], res["alpha"][g], tb, thr_scale,
-                                                              (j, b, h, g)))
+                w_score = max(w_score, check_recorded(wl, st, recorded[g], res["alpha"][g], tb, thr_scale, (j, b, h, g)))
             own = O.important(O.round_to_storage(res["alpha"], "f32" if st.ring_bits else wl.dtype), tb, thr_scale)
             flipped = own != O.important(recorded, tb, thr_scale)
+            n_flip = 0
             if flipped.any():      # a decision may differ from the fp64 one only within the score tolerance of c/t
                 a = res["alpha"]
                 thr = float(O.importance_threshold(tb, thr_scale))
                 bound = (np.full_like(a, 1e-4 * thr) if st.ring_bits else
                          SCORE_RTOL[wl.dtype] * a + SCORE_ATOL_OF_MAX[wl.dtype] * a.max(axis=1, keepdims=True))
                 assert (np.abs(a - thr)[flipped] <= bound[flipped]).all(), ("importance flip far from c/t", j, b, h)
-                flips += int(flipped.sum())
-            if check_state_every and ((j + 1) % check_state_every == 0 or j == n_steps - 1):
-                check_unit_state(st, b, h, u, tb, lazy=lazy is not None)
-    return {"compactions": compactions, "steps": n_steps, "units": len(units), "worst_out_rel_err": worst_out,
-            "worst_score_err_over_bound": worst_score, "importance_flips_vs_fp64": flips,
-            "evicted_total": evicted_total, "final_lens": st.lens.cpu().numpy().tolist()}
+                n_flip = int(flipped.sum())
+            return w_out, w_score, n_flip, l - u.l, compacted
+
+        results = list(self.pool.map(one, self.units)) if self.pool else [one(u) for u in self.units]
+        for w_out, w_score, n_flip, gone, compacted in results:
+            self.worst_out, self.worst_score = max(self.worst_out, w_out), max(self.worst_score, w_score)
+            self.flips += n_flip
+            self.evicted_total += gone
+            self.compactions += compacted
+        if check_state:
+            for (b, h) in self.units:
+                check_unit_state(st, b, h, self.oracles[(b, h)], t + int(self.offs[b]), lazy=lazy is not None)
+
+    def report(self, n_steps) -> Dict:
+        if self.pool:
+            self.pool.shutdown()
+        return {"compactions": self.compactions, "steps": n_steps, "units": len(self.units),
+                "worst_out_rel_err": self.worst_out, "worst_score_err_over_bound": self.worst_score,
+                "importance_flips_vs_fp64": self.flips, "evicted_total": self.evicted_total,
+                "final_lens": self.st.lens.cpu().numpy().tolist()}
+
+
+def run_slaved_from_seeded_state(wl: inputs.Workload, device, layer: int, units: Sequence[Tuple[int, int]],
+                                 n_decode: int, check_state_every: int = 0, lazy: Optional[Tuple[int, int]] = None,
+                                 expect_path: Optional[int] = None, progress=None) -> Dict:
+    """A whole decode trajectory at a workload's full size, as the benchmark runs it: inputs generated on the
+    device, the whole prompt preloaded, the window seeded by one corm_prefill_seed call (checked by tests of
+    its own), then n_decode fused steps on ALL units of the layer.  The oracles of the listed units are rebuilt
+    from the device state after the prompt and slaved from there on, every step."""
+    m = min(wl.w, wl.P)
+    x = inputs.make_layer(wl, layer, device=device, n_decode=n_decode, n_replay=m)
+    st = make_state(wl, device, Lcap=wl.P + n_decode, Tcap=wl.P + n_decode)
+    if expect_path is not None:
+        assert corm.corm_selected_path(st.desc) == expect_path
+    st.preload(x["K0"], x["V0"])
+    t = torch.full((wl.B,), wl.P, dtype=torch.int32, device=device)
+    tf = torch.zeros_like(t)
+    st.prefill_seed(x["Q"][:m].permute(1, 2, 0, 3).contiguous(), t, tf)
+    torch.cuda.synchronize()
+    assert int(st.status.item()) == 0
+    t_first = wl.P - m + 1
+    assert int(tf.min().item()) == int(tf.max().item()) == t_first
+    oracles = {u: oracle_from_snapshot(st, u[0], u[1], wl.P, t_first, wl.dtype, 1.0) for u in units}
+    slaves = Slaves(wl, st, oracles, units, np.zeros(wl.B, dtype=np.int64), 1.0, lazy,
+                    slots_before={u: np.arange(oracles[u].l) for u in units},
+                    used_before={u: oracles[u].l for u in units})
+    seeded_evictions = sum(wl.P - oracles[u].l for u in units)
+    for j in range(n_decode):
+        q, k, v, tt = step_inputs(wl, x, m + j, m)
+        t_dev = torch.full((wl.B,), tt, dtype=torch.int32, device=device)
+        if lazy is not None:
+            st.step_lazy(q, k, v, t_dev, tf, dead_num=lazy[0], dead_den=lazy[1])
+        else:
+            st.step(q, k, v, t_dev, tf)
+        last = j == n_decode - 1
+        slaves.after_step(j, q, k, v, tt, check_state=last or (bool(check_state_every) and (j + 1) % check_state_every == 0))
+        if progress and ((j + 1) % 32 == 0 or last):
+            progress(f"step {j + 1}/{n_decode}: evicted so far {slaves.evicted_total}, worst out err {slaves.worst_out:.2e}")
+    rep = slaves.report(n_decode)
+    rep["evicted_by_the_prompt"] = seeded_evictions
+    lens = np.asarray(rep.pop("final_lens"))
+    rep["final_lens_min_mean_max"] = (int(lens.min()), float(lens.mean()), int(lens.max()))
+    return rep
 
 
 def _seed_with_kernel(wl, st, x, x_cpu, oracles, units, offs, offs_dev, n_replay, t_first, thr_scale) -> float:
@@ -269,30 +349,42 @@ def _seed_with_kernel(wl, st, x, x_cpu, oracles, units, offs, offs_dev, n_replay
     torch.cuda.synchronize()
     assert int(st.status.item()) == 0, ("device status", int(st.status.item()))
     assert torch.equal(tf_out, t_first), "t_first"
-    worst = 0.0
     keep_d = st.keep.cpu().numpy()
     idx_d = st.kept_idx.cpu().numpy()
-    ring_b = {}
-    for (b, h) in units:
-        u = oracles[(b, h)]
-        if b not in ring_b:
-            ring_b[b] = np.stack([ring_row(st, b, sl) for sl in range(wl.w)], axis=1)   # [Hq, w, Tcap]
+    lens_d = st.lens.cpu().numpy()
+    ring_b = {b: np.stack([ring_row(st, b, sl) for sl in range(wl.w)], axis=1)            # [Hq, w, Tcap]
+              for b in sorted({u[0] for u in units})}
+    Qc = _f32(x_cpu["Q"][:n_replay])
+
+    def one(unit):
+        b, h = unit
+        u = oracles[unit]
+        worst = 0.0
         res = None
         for j in range(n_replay):
             p = wl.P - n_replay + j
             tb = p + 1 + int(offs[b])
             live_pos = np.concatenate([u.positions, [tb - 1]])
             recorded = ring_b[b][h * G:(h + 1) * G, (tb - 1) % wl.w][:, live_pos]
-            res = u.step(_f32(x_cpu["Q"][j, b, h * G:(h + 1) * G]), _f32(x_cpu["K0"][b, h, p]),
-                         _f32(x_cpu["V0"][b, h, p]), tb, recorded=recorded)
+            res = u.step(Qc[j, b, h * G:(h + 1) * G], _f32(x_cpu["K0"][b, h, p]), _f32(x_cpu["V0"][b, h, p]), tb,
+                         recorded=recorded)
             for g in range(G):
                 worst = max(worst, check_recorded(wl, st, recorded[g], res["alpha"][g], tb, thr_scale,
                                                   ("seeded", j, b, h, g)))
         assert np.array_equal(keep_d[b, h, :wl.P].astype(bool), res["keep"]), ("keep after seeding", b, h)
-        assert int(st.lens[b, h].item()) == u.l, ("lens after seeding", b, h)
+        assert int(lens_d[b, h]) == u.l, ("lens after seeding", b, h)
         assert np.array_equal(idx_d[b, h, :u.l].astype(np.int64), res["indices"]), ("kept_idx after seeding", b, h)
-        check_unit_state(st, b, h, u, wl.P + int(offs[b]))
-    return worst
+        return worst
+
+    n_threads = min(16, os.cpu_count() or 1)
+    if n_threads > 1 and len(units) > 1:
+        with ThreadPoolExecutor(max_workers=n_threads) as pool:
+            worsts = list(pool.map(one, units))
+    else:
+        worsts = [one(u) for u in units]
+    for (b, h) in units:
+        check_unit_state(st, b, h, oracles[(b, h)], wl.P + int(offs[b]))
+    return max(worsts) if worsts else 0.0
 
 
 # ------------------------------------------------------------------ snapshot mode

@@ -156,6 +156,83 @@ def test_config4_long_context_more_units():
     _run(wl, 0, 1, set(), _all_units(wl)[3::8], expect_path=1, seed_kernel=True)
 
 
+# ------------------------------------------------------------------ whole trajectories at full size
+
+def _report(name, rep):
+    say(name, {k: v for k, v in rep.items() if k != "final_lens"})
+
+
+def test_config2_whole_trajectory_every_unit():
+    """llama7b_1layer exactly as defined: all 32 units; the window seeded from the 4096-token prompt by the
+    dense call, the oracles replaying its last 1024 positions as steps of Algorithm 1 on the scores the call
+    recorded; then all 256 decode steps on the split path, every unit slaved at every step (ring wrap-around
+    from step w + 1 on, lengths running towards Lcap)."""
+    wl = W["llama7b_1layer"]
+    st = harness.make_state(wl, DEV)
+    assert corm.corm_selected_path(st.desc) == 1
+    del st
+    say("whole trajectory", wl)
+    rep = harness.run_slaved_trajectory(wl, DEV, check_state_every=64, seed_kernel=True)
+    _report("config 2", rep)
+    assert rep["steps"] == wl.w + wl.D and rep["units"] == 32
+
+
+@pytest.mark.parametrize("variant", ["literal", "structured"])
+def test_config3_whole_decode_trajectory_of_a_sparse_layer(variant):
+    """One sparse layer of llama7b_b16 over all 512 decode steps, in the launch configuration the benchmark
+    times (fused unit kernel, all 512 units on the device); 16 units, spread over sequences and the four
+    head classes, are slaved at every step.  Literal generator (nothing evicted: lengths reach Lcap) and the
+    eviction-heavy variant (heads diverge, compaction at every step)."""
+    wl = W["llama7b_b16"]
+    if variant == "structured":
+        wl = wl.replace(q_mean_scales=inputs.STRUCTURED_Q_MEAN)
+    units = [(b, (5 * b + 3) % wl.Hkv) for b in range(wl.B)]                  # every sequence, heads of all classes
+    say("whole decode trajectory", variant, wl.name, "units", units)
+    rep = harness.run_slaved_from_seeded_state(wl, DEV, 2, units, wl.D, check_state_every=128, expect_path=2,
+                                               progress=say)
+    _report("config 3 " + variant, rep)
+    assert rep["steps"] == 512 and rep["units"] == 16
+    if variant == "structured":
+        assert rep["evicted_total"] > 1000 and rep["final_lens_min_mean_max"][0] < 2000
+
+
+def test_config3_whole_decode_trajectory_deferred_compaction():
+    """The same eviction-heavy layer with corm_decode_step_lazy (dead fraction 1/4) over all 512 steps."""
+    wl = W["llama7b_b16"].replace(q_mean_scales=inputs.STRUCTURED_Q_MEAN)
+    units = [(b, (7 * b + 1) % wl.Hkv) for b in range(wl.B)]
+    say("whole decode trajectory, deferred compaction", wl.name, "units", units)
+    rep = harness.run_slaved_from_seeded_state(wl, DEV, 3, units, wl.D, check_state_every=128, lazy=(1, 4),
+                                               expect_path=2, progress=say)
+    _report("config 3 structured, deferred", rep)
+    assert rep["evicted_total"] > 1000 and rep["compactions"] > 0
+
+
+def test_config4_long_context_both_head_classes():
+    """long32k: 32 of the 128 units (every sequence; even heads and odd heads, whose keys are twice as long),
+    three decode steps after the seeded 32768-token prompt."""
+    wl = W["long32k"]
+    units = [(b, h) for b in range(wl.B) for h in (0, 1, 6, 13, 18, 23, 28, 31)]
+    assert len(units) == 32 and {h % 2 for _, h in units} == {0, 1}
+    say("long32k", "units", units)
+    rep = harness.run_slaved_from_seeded_state(wl, DEV, 0, units, 3, check_state_every=1, expect_path=1, progress=say)
+    _report("config 4", rep)
+
+
+@pytest.mark.parametrize("variant", ["literal", "structured"])
+def test_config5_gqa_64_decode_steps(variant):
+    """gqa_llama3: 16 of the 128 units over 64 decode steps after the seeded 8192-token prompt (MFMA attend
+    kernel, four query heads per unit)."""
+    wl = W["gqa_llama3"]
+    if variant == "structured":
+        wl = wl.replace(q_mean_scales=(3.0, 5.0), key_scale=1.5)
+    units = [(b, (3 * b + 1) % wl.Hkv) for b in range(wl.B)]
+    say("gqa_llama3", variant, "units", units)
+    rep = harness.run_slaved_from_seeded_state(wl, DEV, 0, units, 64, check_state_every=32, expect_path=1, progress=say)
+    _report("config 5 " + variant, rep)
+    if variant == "structured":
+        assert rep["evicted_total"] > 0
+
+
 # ------------------------------------------------------------------ the largest shapes the interface accepts
 
 def test_longest_unit_the_interface_accepts():

@@ -63,10 +63,13 @@ MUTANTS = [
      "threshold from the live length instead of the step"),
     ("note_of_query", "found[:, positions] =", "found[:, np.arange(len(positions))] =",
      "note addressed by slot, not by position: wrong after the first eviction"),
-    ("long_term_minor", ".any(axis=(0, 1))", ".any(axis=0).all(axis=0)", "group rule: AND over the heads instead of OR"),
-    ("long_term_minor", "notes[:, :, positions]", "notes[-1:, :, positions]", "only the current query decides"),
-    ("long_term_minor", "notes[:, :, positions]", "notes[:-1, :, positions]", "current query left out"),
-    ("long_term_minor", "return ~found_by_someone", "return found_by_someone", "the important keys are evicted"),
+    ("long_term_minor", "notes.any(axis=(0, 1))", "notes.any(axis=0).all(axis=0)", "group rule: AND over the heads instead of OR"),
+    ("long_term_minor", "notes.any(axis=(0, 1))", "notes[-1:].any(axis=(0, 1))", "only the current query decides"),
+    ("long_term_minor", "notes.any(axis=(0, 1))", "notes[:-1].any(axis=(0, 1))", "current query left out"),
+    ("long_term_minor", "return ~found_by_someone[positions]", "return found_by_someone[positions]",
+     "the important keys are evicted"),
+    ("long_term_minor", "return ~found_by_someone[positions]", "return ~found_by_someone[:len(positions)]",
+     "notes read by slot, not by position"),
     ("survivors", "notes.shape[0] < w", "notes.shape[0] <= w", "first eviction one step late"),
     ("survivors", "notes.shape[0] < w", "notes.shape[0] < w - 1", "first eviction one step early"),
     ("survivors", "notes[notes.shape[0] - w:]", "notes[notes.shape[0] - w + 1:]", "window of w-1 queries"),
