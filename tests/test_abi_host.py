@@ -160,6 +160,27 @@ def test_static_scratch_entry_checks_its_arguments_and_its_limit_on_the_host():
     assert corm.CORM_STATIC_SCRATCH_BYTES == 40 << 20
 
 
+def test_host_code_under_address_and_undefined_behaviour_sanitizers():
+    """tests/host_checks: the library's host code (descriptor validation, workspace layout, pointer and option
+    checks, path selection, the static-scratch limit) compiled with ASan + UBSan and driven at and beyond the
+    interface limits (4194303 slots, 65520 units, products beyond 32 bits), from two threads; any report from
+    a sanitizer ends the program with a non-zero status.  Built by build(); built here if it is missing."""
+    import subprocess
+    import sys
+    exe = os.path.join(ROOT, "tests", "host_checks", "host_checks")
+    if not os.path.exists(exe):
+        sys.path.insert(0, ROOT)
+        import __graft_entry__
+        __graft_entry__.build_host_checks()
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=300,
+                       env={**os.environ, "ASAN_OPTIONS": "detect_leaks=0:abort_on_error=0",
+                            "UBSAN_OPTIONS": "print_stacktrace=1:halt_on_error=1"})
+    assert r.returncode == 0 and "host checks ok" in r.stdout, (r.returncode, r.stdout[-600:], r.stderr[-1200:])
+    assert "Sanitizer" not in r.stderr and "runtime error" not in r.stderr, r.stderr[-1200:]
+    syms = subprocess.run(["nm", exe], capture_output=True, text=True).stdout
+    assert "__asan_init" in syms and "__ubsan_handle" in syms, "the program is not instrumented"
+
+
 def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(corm, "_lib", None)
     monkeypatch.setattr(corm, "LIB_PATH", "/nonexistent/libcorm.so")
