@@ -392,7 +392,7 @@ def main():
     layers = wl.layers if args.layers is None else args.layers
     K_steps, W_steps = args.steps, args.warmup
     lazy = tuple(int(v) for v in args.lazy_frac.split("/")) if args.lazy_frac else None
-    n_over = K_steps if args.overlap_streams and args.streams == 1 else 0
+    n_over = K_steps if args.overlap_streams and args.streams == 1 and layers > 1 else 0   # (one layer: nothing to overlap)
     hip = HipEvents()
 
     stack = Stack(args, wl, layers, W_steps + K_steps + n_over + 2, dev)

@@ -29,6 +29,10 @@ struct Params {
   unsigned long long* keepbits;  // keep flags as wave ballots [B*Hkv, ceil(Lcap/64)] (workspace)
   int32_t* kept_idx;   // optional
   int32_t* counts;     // survivors per (unit, split)
+  int32_t* any_dirty;  // one word of the workspace: set to t[0] by a step launch in which some unit has to be
+                       // compacted; while it differs from t[0] the compaction launches know, from one load,
+                       // that only their per-unit bookkeeping is left to do.  A stale or foreign value that
+                       // happens to equal t[0] only sends them down the ordinary path.
   float* partials;     // [B*Hq, nsplit, d+2]
   float* logits;       // [B*Hq, Lcap], log2 domain
   int32_t* status;
@@ -41,6 +45,7 @@ struct Params {
   int32_t npart;        // partials per head in the workspace: nsplit * (CHUNK / smallest part)
   int32_t kb_stride;    // 64-bit words per unit in keepbits
   int32_t lazy;         // lazy mode: keepbits are the caller's persistent live masks; dead slots are skipped
+  int32_t dead_num, dead_den;   // lazy mode: the compaction policy (a unit is compacted once dead_num/dead_den of its slots are dead)
 };
 
 // ---------------------------------------------------------------- small device helpers
@@ -187,6 +192,15 @@ __device__ __forceinline__ UnitLen unit_len_of(const Params& p, int lens_value) 
 }
 
 __device__ __forceinline__ UnitLen unit_len(const Params& p, int unit) { return unit_len_of(p, p.lens[unit]); }
+
+// Does a unit with L slots in use, T of them live after this step, get compacted in this step?  Exact mode:
+// whenever a key went.  Lazy mode: once its dead slots reach dead_num / dead_den of its slots, or its slots
+// are about to run out.
+__device__ __forceinline__ bool compact_policy(int lazy, int dead_num, int dead_den, int Lcap, int L, int T) {
+  if (T == L) return false;
+  if (!lazy) return true;
+  return (long long)(L - T) * dead_den >= (long long)L * dead_num || L + 1 >= Lcap;
+}
 
 // ---------------------------------------------------------------- boolean message (bit ring)
 //

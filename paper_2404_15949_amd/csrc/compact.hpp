@@ -49,13 +49,18 @@ struct CompactArgs {
   int32_t* stage_meta;           // [units, nsplit, CHUNK, 2] (pos, last_hit)
   int32_t nsplit, Lcap, do_append, kb_stride;
   int32_t lazy, dead_num, dead_den;
+  const int32_t* any_dirty;      // optional (with t): *any_dirty != t[0] means no unit of this launch is compacted
+  const int32_t* t;
 };
 
-// does this unit get compacted in this step?  L slots, T survivors
+// No unit of this launch has to be compacted (told by the step launch before, in one word): only the first
+// workgroup of every unit still has its bookkeeping to do (the unit's length, lens, the live count).
+__device__ __forceinline__ bool nothing_to_compact(const CompactArgs& a) {
+  return a.any_dirty != nullptr && *a.any_dirty != a.t[0];
+}
+
 __device__ __forceinline__ bool compact_now(const CompactArgs& a, int L, int T) {
-  if (T == L) return false;
-  if (!a.lazy) return true;
-  return (long long)(L - T) * a.dead_den >= (long long)L * a.dead_num || L + 1 >= a.Lcap;
+  return compact_policy(a.lazy, a.dead_num, a.dead_den, a.Lcap, L, T);
 }
 
 // Moves the n_rows survivors listed in src_of (ascending) to consecutive destinations starting at
@@ -184,6 +189,7 @@ __global__ __launch_bounds__(WG) void corm_compact_local_kernel(const CompactArg
   __shared__ CompactShared sh_c;
   const int split = blockIdx.x, unit = blockIdx.y;
   const int tid = threadIdx.x;
+  if (split != 0 && nothing_to_compact(a)) return;
   const int L = compact_unit_len(a, unit);
   if (split == 0 && tid == 0) a.unit_len[unit] = L;
   const int nlive = (L + CHUNK - 1) / CHUNK;
@@ -257,6 +263,7 @@ __global__ __launch_bounds__(WG) void corm_compact_boundary_kernel(const Compact
   constexpr int LPR = ROWB / 16;
   const int split = blockIdx.x, unit = blockIdx.y;
   const int tid = threadIdx.x;
+  if (split != 0 && nothing_to_compact(a)) return;
   const int L = a.unit_len[unit];
   const int nlive = (L + CHUNK - 1) / CHUNK;
   if (split >= nlive && split != 0) return;

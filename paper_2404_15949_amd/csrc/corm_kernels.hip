@@ -244,8 +244,10 @@ int corm_step_attend(const corm_desc* desc, const void* q, const void* k_new, co
   return launch_attend_record(desc, p, ctx, (hipStream_t)stream);
 }
 
-int corm_step_evict(const corm_desc* desc, void* K, void* V, int32_t* lens, int32_t* pos, int32_t* last_hit,
-                    int32_t* kept_idx, void* workspace, size_t workspace_bytes, void* stream) {
+// t: the step's t array when the attend launch of the same step maintained the workspace's dirty word (the
+// compaction launches then leave at once where nothing is to be compacted); NULL: no such shortcut
+static int step_evict_impl(const corm_desc* desc, void* K, void* V, int32_t* lens, int32_t* pos, int32_t* last_hit,
+                           int32_t* kept_idx, void* workspace, size_t workspace_bytes, const int32_t* t, void* stream) {
   int rc = validate_desc(desc);
   if (rc) return rc;
   if (!K || !V || !pos || !last_hit || !lens) return CORM_EINVAL;
@@ -255,8 +257,15 @@ int corm_step_evict(const corm_desc* desc, void* K, void* V, int32_t* lens, int3
   WorkspaceLayout wl;
   rc = check_workspace(desc, workspace, workspace_bytes, &wl);
   if (rc) return rc;
-  return launch_compact(desc, wl, workspace, K, V, pos, last_hit, lens, nullptr, kept_idx, 1, false, CompactPolicy(),
+  CompactPolicy pol;
+  pol.t = t;
+  return launch_compact(desc, wl, workspace, K, V, pos, last_hit, lens, nullptr, kept_idx, 1, false, pol,
                         (hipStream_t)stream);
+}
+
+int corm_step_evict(const corm_desc* desc, void* K, void* V, int32_t* lens, int32_t* pos, int32_t* last_hit,
+                    int32_t* kept_idx, void* workspace, size_t workspace_bytes, void* stream) {
+  return step_evict_impl(desc, K, V, lens, pos, last_hit, kept_idx, workspace, workspace_bytes, nullptr, stream);
 }
 
 int corm_decode_step(const corm_desc* desc, const void* q, const void* k_new, const void* v_new, void* K, void* V,
@@ -269,7 +278,7 @@ int corm_decode_step(const corm_desc* desc, const void* q, const void* k_new, co
   rc = corm_step_attend(desc, q, k_new, v_new, K, V, lens, pos, last_hit, t, t_first, score_ring, out, keep,
                         workspace, workspace_bytes, status, opts, stream);
   if (rc) return rc;
-  return corm_step_evict(desc, K, V, lens, pos, last_hit, kept_idx, workspace, workspace_bytes, stream);
+  return step_evict_impl(desc, K, V, lens, pos, last_hit, kept_idx, workspace, workspace_bytes, t, stream);
 }
 
 int corm_decode_step_lazy(const corm_desc* desc, const void* q, const void* k_new, const void* v_new, void* K, void* V,
@@ -296,6 +305,7 @@ int corm_decode_step_lazy(const corm_desc* desc, const void* q, const void* k_ne
   p.do_append = 1; p.do_evict = 1;
   bind_params(desc, wl, workspace, p);
   p.lazy = 1;
+  p.dead_num = dead_num; p.dead_den = dead_den;
   p.keepbits = reinterpret_cast<unsigned long long*>(live);   // the live masks are read, then replaced by the new ones
   rc = launch_attend_record(desc, p, ctx, (hipStream_t)stream);
   if (rc) return rc;
@@ -303,6 +313,7 @@ int corm_decode_step_lazy(const corm_desc* desc, const void* q, const void* k_ne
   pol.lazy = 1; pol.dead_num = dead_num; pol.dead_den = dead_den;
   pol.live = reinterpret_cast<unsigned long long*>(live);
   pol.nlive = nlive;
+  pol.t = use_unit_path(desc, ctx) ? t : nullptr;   // (the unit kernel evaluates the policy per unit; the split kernels cannot)
   return launch_compact(desc, wl, workspace, K, V, pos, last_hit, lens, nullptr, nullptr, 1, false, pol,
                         (hipStream_t)stream);
 }

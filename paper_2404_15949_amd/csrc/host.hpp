@@ -8,7 +8,7 @@ namespace {
 // ---------------------------------------------------------------- host side
 
 struct WorkspaceLayout {
-  size_t counts_off, unit_len_off, keepbits_off, partials_off, logits_off, stage_meta_off, stage_k_off, stage_v_off;
+  size_t counts_off, unit_len_off, dirty_off, keepbits_off, partials_off, logits_off, stage_meta_off, stage_k_off, stage_v_off;
   size_t seed_part_off, seed_stats_off, total;
   int nsplit, kb_stride;
   int seed_kb, seed_nkb;   // prompt seeding: keys per workgroup, key blocks per unit
@@ -26,7 +26,8 @@ WorkspaceLayout workspace_layout(const corm_desc& d) {
   w.counts_off = 0;
   w.kb_stride = (d.Lcap + 63) / 64;
   w.unit_len_off = align_up(units * w.nsplit * sizeof(int32_t), 256);
-  w.keepbits_off = align_up(w.unit_len_off + units * sizeof(int32_t), 256);
+  w.dirty_off = w.unit_len_off + units * sizeof(int32_t);   // one word: see Params::any_dirty
+  w.keepbits_off = align_up(w.dirty_off + sizeof(int32_t), 256);
   w.partials_off = align_up(w.keepbits_off + units * w.kb_stride * sizeof(unsigned long long), 256);
   w.logits_off = align_up(w.partials_off + heads * w.nsplit * MAX_PARTS_PER_CHUNK * (d.d + 2) * sizeof(float), 256);
   w.stage_meta_off = align_up(w.logits_off + heads * d.Lcap * sizeof(float), 256);
@@ -113,6 +114,7 @@ int check_workspace(const corm_desc* d, void* workspace, size_t workspace_bytes,
 void bind_params(const corm_desc* d, const WorkspaceLayout& wl, void* workspace, Params& p) {
   char* ws = reinterpret_cast<char*>(workspace);
   p.counts = reinterpret_cast<int32_t*>(ws + wl.counts_off);
+  p.any_dirty = reinterpret_cast<int32_t*>(ws + wl.dirty_off);
   p.keepbits = reinterpret_cast<unsigned long long*>(ws + wl.keepbits_off);
   p.kb_stride = wl.kb_stride;
   p.partials = reinterpret_cast<float*>(ws + wl.partials_off);
@@ -289,6 +291,7 @@ struct CompactPolicy {
   int lazy = 0, dead_num = 0, dead_den = 1;
   unsigned long long* live = nullptr;   // lazy mode: the caller's live masks take the place of the keep masks
   int32_t* nlive = nullptr;             // optional output: live keys per unit
+  const int32_t* t = nullptr;           // the step's t array, if the launch before maintains the workspace's dirty word
 };
 
 // local + boundary launches of the compaction; count_first: derive the per-split counts from the mask
@@ -311,6 +314,9 @@ int launch_compact(const corm_desc* d, const WorkspaceLayout& wl, void* workspac
   a.stage_meta = reinterpret_cast<int32_t*>(ws + wl.stage_meta_off);
   a.nsplit = wl.nsplit; a.Lcap = d->Lcap; a.do_append = do_append;
   a.lazy = pol.lazy; a.dead_num = pol.dead_num; a.dead_den = pol.dead_den;
+  // (a caller who wants kept_idx gets the identity written for untouched units: every workgroup has work then)
+  a.any_dirty = pol.t && !kept_idx ? reinterpret_cast<const int32_t*>(ws + wl.dirty_off) : nullptr;
+  a.t = pol.t;
   const dim3 grid(wl.nsplit, d->B * d->Hkv);
   if (count_first) {
     hipLaunchKernelGGL(corm_count_kernel, grid, dim3(WG), 0, s, a, counts);

@@ -301,6 +301,60 @@ def test_summary_only_state_equals_the_ring_state(name, mode):
     assert int(a.status.item()) == 0 and int(b.status.item()) == 0
 
 
+@pytest.mark.parametrize("mode", ["exact", "lazy"])
+@pytest.mark.parametrize("name", ["bf16_mha", "bf16_gqa4", "structured", "sparse_layer"])
+def test_step_without_mask_outputs_equals_the_step_with_them(name, mode):
+    """The calls as the benchmark makes them -- keep = kept_idx = NULL, where the compaction launches may leave
+    at once on one word of the workspace -- against the same calls with the mask outputs, whose parity with
+    the oracle the other tests establish: lens, the live masks and counts, out, K, V, pos, last_hit and the
+    ring must be the same bits after every step; some steps evict in some units only, some in none.  Two
+    layers share one workspace, as the layers of a stack do."""
+    wl, _ = TRAJ[name]
+    layers = (2, 0) if name == "sparse_layer" else (0, 1)
+    xs = [{k: v.to(DEV) for k, v in inputs.make_layer(wl, l, device="cpu").items() if k != "sinks"} for l in layers]
+    m = min(wl.w, wl.P)
+    pre = wl.P - m
+    ws = None
+    pairs = []
+    for x in xs:
+        a = harness.make_state(wl, DEV, want_masks=True)
+        ws = a.workspace if ws is None else ws
+        b = harness.make_state(wl, DEV, want_masks=False, workspace=ws)      # every maskless layer on one workspace
+        for st in (a, b):
+            st.preload(x["K0"][:, :, :pre], x["V0"][:, :, :pre])
+        pairs.append((a, b, x))
+    tf = torch.full((wl.B,), pre + 1, dtype=torch.int32, device=DEV)
+    evicting_steps = quiet_steps = 0
+    for j in range(m + wl.D):
+        for a, b, x in pairs:
+            q, k, v, tt = harness.step_inputs(wl, x, j, m)
+            td = torch.full((wl.B,), tt, dtype=torch.int32, device=DEV)
+            before = (a.lens if mode == "exact" else (a.nlive if j else torch.full_like(a.nlive, pre))).clone()
+            for st in (a, b):
+                if mode == "lazy":
+                    st.step_lazy(q, k, v, td, tf, dead_num=1, dead_den=8)
+                else:
+                    st.step(q, k, v, td, tf)
+            torch.cuda.synchronize()
+            assert torch.equal(a.lens, b.lens) and torch.equal(a.out, b.out), (j, "lens / out")
+            if mode == "lazy":
+                assert torch.equal(a.live, b.live) and torch.equal(a.nlive, b.nlive), (j, "live")
+            after = a.lens if mode == "exact" else a.nlive
+            lost = int((before + 1 - after).sum().item())       # keys evicted in this step, all units
+            assert lost >= 0
+            evicting_steps += int(lost > 0)
+            quiet_steps += int(lost == 0)
+            used = torch.arange(a.Lcap, device=DEV).view(1, 1, -1) < a.lens.unsqueeze(-1)
+            for nm in ("pos", "last_hit"):
+                assert torch.equal(getattr(a, nm) * used, getattr(b, nm) * used), (nm, j)
+            for nm in ("K", "V"):
+                assert torch.equal(getattr(a, nm) * used.unsqueeze(-1), getattr(b, nm) * used.unsqueeze(-1)), (nm, j)
+    for a, b, _ in pairs:
+        assert torch.equal(a.ring, b.ring)
+        assert int(a.status.item()) == 0 and int(b.status.item()) == 0
+    assert evicting_steps > 0 and quiet_steps > 0, (evicting_steps, quiet_steps)
+
+
 # the boolean message (score_dtype "bit"): the ring holds what Algorithm 1 itself keeps
 BITS = ["tiny_f32", "bf16_mha", "bf16_gqa4", "bf16_gqa8", "r_lt_w", "structured"]
 
@@ -953,7 +1007,7 @@ def test_bench_prints_one_json_line_with_the_required_fields(launch_path):
     assert r["cpu_baseline"]["kind"] == "oracle" and r["cpu_baseline"]["value"] > 0
     assert r["cpu_baseline"]["cores"] == os.cpu_count() and 1 <= r["cpu_baseline"]["threads"] <= 16
     assert r["config"]["streams"] == 1 and "sequence" in r["value_is"] and "traffic_source" in r["roofline"]
-    assert r["overlapped"]["streams"] == 3 and r["overlapped"]["steps_per_s"] > 0 and r["eviction_heavy"] is None
+    assert r["overlapped"] is None and r["eviction_heavy"] is None      # one layer: nothing to overlap
     # two layers of the headline shape: the eviction-heavy leg runs too, and really evicts
     res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--layers", "2", "--steps", "3", "--warmup", "1",
                           "--cpu-units", "2", "--cpu-steps", "2"], capture_output=True, text=True, timeout=280)
@@ -961,8 +1015,9 @@ def test_bench_prints_one_json_line_with_the_required_fields(launch_path):
     r = json.loads([ln for ln in res.stdout.splitlines() if ln.strip()][-1])
     assert r["config"]["workload"] == "llama7b_b16" and r["roofline"]["kernel"] == "corm_unit_kernel"
     assert r["roofline"]["bytes_per_key"] == 2 * 128 * 2 + 2 + 8
+    assert r["overlapped"]["streams"] == 3 and r["overlapped"]["steps_per_s"] > 0
     eh = r["eviction_heavy"]
     for mode in ("compaction_at_every_step", "deferred_compaction_1_4"):
-        assert eh[mode]["steps_per_s"] > 0 and 0.2 < eh[mode]["live_fraction_end"] < 0.6, (mode, eh[mode])
+        assert eh[mode]["steps_per_s"] > 0 and 0.2 < eh[mode]["live_fraction_end"] < 0.9, (mode, eh[mode])   # (the first two layers are the dense ones)
         assert eh[mode]["live_fraction_per_head"]["min"] < eh[mode]["live_fraction_per_head"]["max"]
     assert eh["compaction_at_every_step"]["keys_evicted"] > 0 and eh["compaction_at_every_step"]["moved_bytes_per_step"] > 0
