@@ -162,19 +162,22 @@ def _report(name, rep):
     say(name, {k: v for k, v in rep.items() if k != "final_lens"})
 
 
-def test_config2_whole_trajectory_every_unit():
-    """llama7b_1layer exactly as defined: all 32 units; the window seeded from the 4096-token prompt by the
-    dense call, the oracles replaying its last 1024 positions as steps of Algorithm 1 on the scores the call
-    recorded; then all 256 decode steps on the split path, every unit slaved at every step (ring wrap-around
-    from step w + 1 on, lengths running towards Lcap)."""
+@pytest.mark.parametrize("half", [0, 1])
+def test_config2_whole_trajectory_every_unit(half):
+    """llama7b_1layer exactly as defined; the window seeded from the 4096-token prompt by the dense call, the
+    oracles replaying its last 1024 positions as steps of Algorithm 1 on the scores the call recorded; then
+    all 256 decode steps on the split path, every unit slaved at every step (ring wrap-around from step w + 1
+    on, lengths running towards Lcap).  The device runs all 32 units; the two cases slave heads 0-15 and
+    16-31 (half the host work each), together every unit."""
     wl = W["llama7b_1layer"]
     st = harness.make_state(wl, DEV)
     assert corm.corm_selected_path(st.desc) == 1
     del st
-    say("whole trajectory", wl)
-    rep = harness.run_slaved_trajectory(wl, DEV, check_state_every=64, seed_kernel=True)
+    units = [(0, h) for h in range(16 * half, 16 * half + 16)]
+    say("whole trajectory", wl, "units", units)
+    rep = harness.run_slaved_trajectory(wl, DEV, check_state_every=64, seed_kernel=True, units=units)
     _report("config 2", rep)
-    assert rep["steps"] == wl.w + wl.D and rep["units"] == 32
+    assert rep["steps"] == wl.w + wl.D and rep["units"] == 16
 
 
 @pytest.mark.parametrize("variant", ["literal", "structured"])
