@@ -18,7 +18,8 @@
  * Conventions
  * -----------
  * Every pointer is a DEVICE pointer to caller-owned memory unless it says "host".  The library
- * allocates and frees nothing; scratch lives in a caller-provided workspace.  Calls are
+ * allocates and frees nothing; scratch lives in a caller-provided workspace (one call,
+ * corm_decode_attend_static, keeps it in a device array of the library instead).  Calls are
  * asynchronous on `stream` (a hipStream_t passed as void*, NULL = the default stream) and never
  * synchronize.  Every call returns 0 (CORM_OK) or a negative corm_status; argument errors are
  * detected on the host before anything is launched.  Conditions only the device can see
