@@ -156,10 +156,11 @@ int corm_decode_attend(const corm_desc* desc, const void* q, const void* K, cons
  * Limit: the scratch the shape needs -- per-unit survivor counts and keep words, B*Hq*ceil(Lcap/512)*4*(d+2)
  * floats of partials and B*Hq*Lcap floats of logits, each part rounded up to 256 bytes -- must fit, else
  * CORM_ECAPACITY and nothing is launched (d = 128: 32 heads x 4352 slots need 1.2 MB, 512 heads x 4608 slots
- * 19 MB, 512 query / 128 KV heads x 8704 slots 36 MB; 128 heads x 66000 slots, 70 MB, are refused).  Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU (other
- * streams, other threads) race; calls on one stream are ordered.  Nothing in the array has to start at
- * zero or survive between calls (a call writes every partial and logit it later reads).  The first call
- * on a device looks the array's address up once: make one call eagerly before capturing a graph. */
+ * 19 MB, 512 query / 128 KV heads x 8704 slots 36 MB; 128 heads x 66000 slots, 70 MB, are refused).
+ * Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU (other streams, other
+ * threads) race; calls on one stream are ordered.  Nothing in the array has to start at zero or survive
+ * between calls (a call writes every partial and logit it later reads).  The first call on a device looks
+ * the array's address up once: make one call eagerly before capturing a graph. */
 #define CORM_STATIC_SCRATCH_BYTES (40u << 20)
 int corm_decode_attend_static(const corm_desc* desc, const void* q, const void* K, const void* V,
                               const int32_t* lens, const int32_t* pos, const int32_t* t, void* score_ring,
