@@ -29,10 +29,10 @@ struct Params {
   unsigned long long* keepbits;  // keep flags as wave ballots [B*Hkv, ceil(Lcap/64)] (workspace)
   int32_t* kept_idx;   // optional
   int32_t* counts;     // survivors per (unit, split)
-  int32_t* any_dirty;  // one word of the workspace: set to t[0] by a step launch in which some unit has to be
-                       // compacted; while it differs from t[0] the compaction launches know, from one load,
-                       // that only their per-unit bookkeeping is left to do.  A stale or foreign value that
-                       // happens to equal t[0] only sends them down the ordinary path.
+  int32_t* unit_dirty; // [units] words of the workspace: a step launch sets a unit's word to the call's dirty_tag
+                       // if the unit has to be compacted; while it differs from the tag the compaction
+                       // launches know, from one load, that only the unit's bookkeeping is left to do.  A stale
+                       // or foreign value that happens to equal the tag only sends them down the ordinary path.
   float* partials;     // [B*Hq, nsplit, d+2]
   float* logits;       // [B*Hq, Lcap], log2 domain
   int32_t* status;
@@ -196,6 +196,12 @@ __device__ __forceinline__ UnitLen unit_len(const Params& p, int unit) { return 
 // Does a unit with L slots in use, T of them live after this step, get compacted in this step?  Exact mode:
 // whenever a key went.  Lazy mode: once its dead slots reach dead_num / dead_den of its slots, or its slots
 // are about to run out.
+// What marks a unit's dirty word for one call: its step and the cache it works on.  Layers that share a
+// workspace run the same step one after the other: the word a layer left must not look set to the next one.
+__device__ __forceinline__ int32_t dirty_tag(const int32_t* t, const void* K) {
+  return (int32_t)((uint32_t)t[0] * 0x9E3779B1u ^ (uint32_t)(reinterpret_cast<uintptr_t>(K) >> 8));
+}
+
 __device__ __forceinline__ bool compact_policy(int lazy, int dead_num, int dead_den, int Lcap, int L, int T) {
   if (T == L) return false;
   if (!lazy) return true;

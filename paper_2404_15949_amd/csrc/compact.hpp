@@ -13,7 +13,7 @@ namespace {
 //   local     grid (splits, units).  R_c = survivors before chunk c (from the per-split counts).
 //             The workgroup of chunk c = slots [a_c, a_c + CHUNK) moves its survivors with rho >= a_c
 //             to slot rho -- inside its own chunk, so it reads and writes only its own slots -- in
-//             ascending tiles (every destination <= its source; inside a tile all loads complete
+//             ascending batches (every destination <= its source; inside a batch all loads complete
 //             before any store).  Its first survivors, those with rho < a_c ("boundary rows", at most
 //             as many as slots were freed before the chunk), belong in earlier chunks, whose owners
 //             may not have read those slots yet: they go to the chunk's staging area instead.
@@ -27,9 +27,16 @@ namespace {
 // slots (or its slots are about to run out); otherwise both launches leave it alone, its dead rows
 // stay in place and the attend kernels skip them by their live masks.  Exact mode: dead_num = 0.
 
+// The local launch runs one thread per slot of a chunk: a chunk is scanned in one step and its rows are requested
+// 64 to 256 at a time (four passes of the workgroup), so a unit that lost a single key (the common case of a
+// dense cache) costs a few memory latencies.
+constexpr int CWG = CHUNK;
+constexpr int CWAVES = CWG / 64;
+
 struct CompactShared {
-  int32_t wave_count[WAVES];
-  int32_t src_of[WG];
+  int32_t wave_count[CWAVES];
+  int32_t first_hole;   // first slot of the chunk (relative) that does not survive
+  int32_t src_of[CWG];
 };
 
 struct CompactArgs {
@@ -49,14 +56,14 @@ struct CompactArgs {
   int32_t* stage_meta;           // [units, nsplit, CHUNK, 2] (pos, last_hit)
   int32_t nsplit, Lcap, do_append, kb_stride;
   int32_t lazy, dead_num, dead_den;
-  const int32_t* any_dirty;      // optional (with t): *any_dirty != t[0] means no unit of this launch is compacted
+  const int32_t* unit_dirty;     // optional (with t) [units]: a value other than dirty_tag(t, K) means the unit is not compacted
   const int32_t* t;
 };
 
-// No unit of this launch has to be compacted (told by the step launch before, in one word): only the first
-// workgroup of every unit still has its bookkeeping to do (the unit's length, lens, the live count).
-__device__ __forceinline__ bool nothing_to_compact(const CompactArgs& a) {
-  return a.any_dirty != nullptr && *a.any_dirty != a.t[0];
+// The unit does not have to be compacted (told by the step launch before, in one word): only its first
+// workgroup still has the bookkeeping to do (the unit's length, lens, the live count).
+__device__ __forceinline__ bool nothing_to_compact(const CompactArgs& a, int unit) {
+  return a.unit_dirty != nullptr && a.unit_dirty[unit] != dirty_tag(a.t, a.K);
 }
 
 __device__ __forceinline__ bool compact_now(const CompactArgs& a, int L, int T) {
@@ -64,58 +71,56 @@ __device__ __forceinline__ bool compact_now(const CompactArgs& a, int L, int T) 
 }
 
 // Moves the n_rows survivors listed in src_of (ascending) to consecutive destinations starting at
-// survivor number rho0: slot rho if rho >= own_begin, else staging row (rho - stage_rho0).
+// survivor number rho0: slot rho if rho >= own_begin, else staging row (rho - stage_rho0).  Every destination
+// is <= its source; all loads of a batch complete before any of its stores.
 template <int ROWB>
 __device__ __forceinline__ void move_rows(char* Kb, char* Vb, char* sk, char* sv, const int32_t* src_of, int n_rows,
                                           int rho0, int own_begin, int stage_rho0) {
   constexpr int LPR = ROWB / 16;
-  constexpr int RPP = WG / LPR;  // rows per pass of the workgroup
+  constexpr int RPP = CWG / LPR;  // rows per pass of the workgroup
+  // Four passes in flight together, in named registers (an indexed array would be demoted to scratch).  Eight
+  // (94 registers, two workgroups per compute unit) moved a full launch 2 % faster and made the launches that
+  // find nothing to do slower: the workgroups that only look at their unit's word then come in more rounds.
+  constexpr int NP = 4;
   const int tid = threadIdx.x;
   const int sub = tid / LPR;
   const size_t col = (size_t)(tid % LPR) * 16;
-  // four passes are in flight together (named registers: an indexed array would be demoted to scratch)
-  for (int base = 0; base < n_rows; base += RPP * 4) {
-    const int j0 = base + sub, j1 = j0 + RPP, j2 = j1 + RPP, j3 = j2 + RPP;
-    const int last = n_rows - 1;
+  const int last = n_rows - 1;
+  for (int base = 0; base < n_rows; base += RPP * NP) {
     // clamped row numbers: every load reads a valid row, stores are predicated
-    const size_t o0 = (size_t)src_of[min(j0, last)] * ROWB + col;
-    const size_t o1 = (size_t)src_of[min(j1, last)] * ROWB + col;
-    const size_t o2 = (size_t)src_of[min(j2, last)] * ROWB + col;
-    const size_t o3 = (size_t)src_of[min(j3, last)] * ROWB + col;
-    const uint4 k0 = *reinterpret_cast<const uint4*>(Kb + o0);
-    const uint4 k1 = *reinterpret_cast<const uint4*>(Kb + o1);
-    const uint4 k2 = *reinterpret_cast<const uint4*>(Kb + o2);
-    const uint4 k3 = *reinterpret_cast<const uint4*>(Kb + o3);
-    const uint4 v0 = *reinterpret_cast<const uint4*>(Vb + o0);
-    const uint4 v1 = *reinterpret_cast<const uint4*>(Vb + o1);
-    const uint4 v2 = *reinterpret_cast<const uint4*>(Vb + o2);
-    const uint4 v3 = *reinterpret_cast<const uint4*>(Vb + o3);
+#define CORM_LOAD_ROW(U)                                                                          \
+    const size_t o##U = (size_t)src_of[min(base + sub + (U) * RPP, last)] * ROWB + col;            \
+    const uint4 k##U = *reinterpret_cast<const uint4*>(Kb + o##U);                                \
+    const uint4 v##U = *reinterpret_cast<const uint4*>(Vb + o##U);
+    CORM_LOAD_ROW(0) CORM_LOAD_ROW(1) CORM_LOAD_ROW(2) CORM_LOAD_ROW(3)
+#undef CORM_LOAD_ROW
     wait_vm_loads();
     __syncthreads();
-#define CORM_STORE_ROW(J, KR, VR)                                              \
-    if ((J) < n_rows) {                                                          \
-      const int rho = rho0 + (J);                                                \
-      if (rho >= own_begin) {                                                    \
-        const size_t d = (size_t)rho * ROWB + col;                               \
-        *reinterpret_cast<uint4*>(Kb + d) = (KR);                                \
-        *reinterpret_cast<uint4*>(Vb + d) = (VR);                                \
-      } else {                                                                   \
-        const size_t d = (size_t)(rho - stage_rho0) * ROWB + col;                \
-        *reinterpret_cast<uint4*>(sk + d) = (KR);                                \
-        *reinterpret_cast<uint4*>(sv + d) = (VR);                                \
+#define CORM_STORE_ROW(U)                                                      \
+    {                                                                            \
+      const int j = base + sub + (U) * RPP;                                      \
+      if (j < n_rows) {                                                          \
+        const int rho = rho0 + j;                                                \
+        if (rho >= own_begin) {                                                  \
+          const size_t d = (size_t)rho * ROWB + col;                             \
+          *reinterpret_cast<uint4*>(Kb + d) = k##U;                              \
+          *reinterpret_cast<uint4*>(Vb + d) = v##U;                              \
+        } else {                                                                 \
+          const size_t d = (size_t)(rho - stage_rho0) * ROWB + col;              \
+          *reinterpret_cast<uint4*>(sk + d) = k##U;                              \
+          *reinterpret_cast<uint4*>(sv + d) = v##U;                              \
+        }                                                                        \
       }                                                                          \
     }
-    CORM_STORE_ROW(j0, k0, v0)
-    CORM_STORE_ROW(j1, k1, v1)
-    CORM_STORE_ROW(j2, k2, v2)
-    CORM_STORE_ROW(j3, k3, v3)
+    CORM_STORE_ROW(0) CORM_STORE_ROW(1) CORM_STORE_ROW(2) CORM_STORE_ROW(3)
 #undef CORM_STORE_ROW
   }
+  static_assert(NP == 4, "four named passes");
 }
 
-// One tile step of the scan.  keep: this thread's flag (0 for slots >= L).  Returns this thread's
-// rank among the tile's survivors and the tile's survivor count (via *tile_kept).
-__device__ __forceinline__ int tile_scan(bool keep, CompactShared& sh, int* tile_kept) {
+// The scan of a chunk.  keep: this thread's flag (0 for slots >= L).  Returns this thread's rank among the
+// chunk's survivors and their number (via *kept).
+__device__ __forceinline__ int chunk_scan(bool keep, CompactShared& sh, int* kept) {
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const unsigned long long bal = __ballot(keep);
   const int rank = __popcll(bal & ((1ull << lane) - 1ull));
@@ -123,12 +128,12 @@ __device__ __forceinline__ int tile_scan(bool keep, CompactShared& sh, int* tile
   __syncthreads();
   int before = 0, total = 0;
 #pragma unroll
-  for (int i = 0; i < WAVES; ++i) {
+  for (int i = 0; i < CWAVES; ++i) {
     const int c = sh.wave_count[i];
     if (i < wv) before += c;
     total += c;
   }
-  *tile_kept = total;
+  *kept = total;
   return before + rank;
 }
 
@@ -185,11 +190,11 @@ __global__ __launch_bounds__(WG) void corm_count_kernel(const CompactArgs a, int
 }
 
 template <int ROWB>
-__global__ __launch_bounds__(WG) void corm_compact_local_kernel(const CompactArgs a) {
+__global__ __launch_bounds__(CWG) void corm_compact_local_kernel(const CompactArgs a) {
   __shared__ CompactShared sh_c;
   const int split = blockIdx.x, unit = blockIdx.y;
   const int tid = threadIdx.x;
-  if (split != 0 && nothing_to_compact(a)) return;
+  if (split != 0 && nothing_to_compact(a, unit)) return;
   const int L = compact_unit_len(a, unit);
   if (split == 0 && tid == 0) a.unit_len[unit] = L;
   const int nlive = (L + CHUNK - 1) / CHUNK;
@@ -200,15 +205,14 @@ __global__ __launch_bounds__(WG) void corm_compact_local_kernel(const CompactArg
   int32_t* idxb = a.kept_idx ? a.kept_idx + (size_t)unit * a.Lcap : nullptr;
   const int cbeg = split * CHUNK;
   const int cend = min(cbeg + CHUNK, L);
+  const int i = cbeg + tid;   // this thread's slot
   if (!compact_now(a, L, T)) {   // nothing evicted, or (lazy mode) not enough dead slots yet
-    if (idxb && T == L)
-      for (int i = cbeg + tid; i < cend; i += WG) idxb[i] = i;
+    if (idxb && T == L && i < cend) idxb[i] = i;
     return;
   }
   const int my_cnt = cnt[split];
   if (R == cbeg && my_cnt == cend - cbeg) {   // no hole before or inside this chunk
-    if (idxb)
-      for (int i = cbeg + tid; i < cend; i += WG) idxb[i] = i;
+    if (idxb && i < cend) idxb[i] = i;
     return;
   }
   char* Kb = a.K + (size_t)unit * a.Lcap * ROWB;
@@ -223,39 +227,36 @@ __global__ __launch_bounds__(WG) void corm_compact_local_kernel(const CompactArg
   // a chunk whose count equals its size lost nothing: its flags are implied (and may be unwritten)
   const bool chunk_full = my_cnt == cend - cbeg;
 
-  int rho_base = R;  // survivor number of the first survivor of the current tile
-  for (int tile = cbeg; tile < cend; tile += WG) {
-    const int i = tile + tid;
-    const bool kp = i < cend && (chunk_full || ((bitsb[i >> 6] >> (i & 63)) & 1ull) != 0);
-    int my_pos = 0, my_lh = 0;
-    if (kp) {
-      my_pos = posb[i];
-      my_lh = lhb[i];
-    }
-    wait_vm_loads();
-    int tile_kept;
-    const int rank = tile_scan(kp, sh_c, &tile_kept);
-    const int rho = rho_base + rank;
-    if (kp) {
-      sh_c.src_of[rank] = i;
-      if (idxb) idxb[rho] = i;
-      if (rho >= cbeg) {
-        if (rho != i) {
-          posb[rho] = my_pos;
-          lhb[rho] = my_lh;
-        }
-      } else {
-        sm[(rho - R) * 2] = my_pos;
-        sm[(rho - R) * 2 + 1] = my_lh;
-      }
-    }
-    __syncthreads();
-    const int tile_n = min(WG, cend - tile);
-    if (!(rho_base == tile && tile_kept == tile_n))
-      move_rows<ROWB>(Kb, Vb, sk, sv, sh_c.src_of, tile_kept, rho_base, cbeg, R);
-    rho_base += tile_kept;
-    __syncthreads();
+  const bool kp = i < cend && (chunk_full || ((bitsb[i >> 6] >> (i & 63)) & 1ull) != 0);
+  int my_pos = 0, my_lh = 0;
+  if (kp) {
+    my_pos = posb[i];
+    my_lh = lhb[i];
   }
+  if (tid == 0) sh_c.first_hole = CWG;
+  wait_vm_loads();
+  int kept;
+  const int rank = chunk_scan(kp, sh_c, &kept);
+  const int rho = R + rank;   // survivor number of this thread's key
+  if (kp) {
+    sh_c.src_of[rank] = i;
+    if (idxb) idxb[rho] = i;
+    if (rho >= cbeg) {
+      if (rho != i) {
+        posb[rho] = my_pos;
+        lhb[rho] = my_lh;
+      }
+    } else {
+      sm[(rho - R) * 2] = my_pos;
+      sm[(rho - R) * 2 + 1] = my_lh;
+    }
+  } else if (i < cend) {
+    atomicMin(&sh_c.first_hole, tid);
+  }
+  __syncthreads();
+  // with no hole before the chunk, the survivors in front of its first hole already lie where they belong
+  const int fixed = R == cbeg ? min(sh_c.first_hole, kept) : 0;
+  move_rows<ROWB>(Kb, Vb, sk, sv, sh_c.src_of + fixed, kept - fixed, R + fixed, cbeg, R);
 }
 
 template <int ROWB>
@@ -263,7 +264,7 @@ __global__ __launch_bounds__(WG) void corm_compact_boundary_kernel(const Compact
   constexpr int LPR = ROWB / 16;
   const int split = blockIdx.x, unit = blockIdx.y;
   const int tid = threadIdx.x;
-  if (split != 0 && nothing_to_compact(a)) return;
+  if (split != 0 && nothing_to_compact(a, unit)) return;
   const int L = a.unit_len[unit];
   const int nlive = (L + CHUNK - 1) / CHUNK;
   if (split >= nlive && split != 0) return;

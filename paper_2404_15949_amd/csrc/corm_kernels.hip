@@ -23,6 +23,7 @@
 #include <stdint.h>
 #include <math.h>
 #include <cmath>
+#include <algorithm>
 #include <mutex>
 
 #include "corm.h"

@@ -26,8 +26,8 @@ WorkspaceLayout workspace_layout(const corm_desc& d) {
   w.counts_off = 0;
   w.kb_stride = (d.Lcap + 63) / 64;
   w.unit_len_off = align_up(units * w.nsplit * sizeof(int32_t), 256);
-  w.dirty_off = w.unit_len_off + units * sizeof(int32_t);   // one word: see Params::any_dirty
-  w.keepbits_off = align_up(w.dirty_off + sizeof(int32_t), 256);
+  w.dirty_off = w.unit_len_off + units * sizeof(int32_t);   // one word per unit: see Params::unit_dirty
+  w.keepbits_off = align_up(w.dirty_off + units * sizeof(int32_t), 256);
   w.partials_off = align_up(w.keepbits_off + units * w.kb_stride * sizeof(unsigned long long), 256);
   w.logits_off = align_up(w.partials_off + heads * w.nsplit * MAX_PARTS_PER_CHUNK * (d.d + 2) * sizeof(float), 256);
   w.stage_meta_off = align_up(w.logits_off + heads * d.Lcap * sizeof(float), 256);
@@ -114,7 +114,7 @@ int check_workspace(const corm_desc* d, void* workspace, size_t workspace_bytes,
 void bind_params(const corm_desc* d, const WorkspaceLayout& wl, void* workspace, Params& p) {
   char* ws = reinterpret_cast<char*>(workspace);
   p.counts = reinterpret_cast<int32_t*>(ws + wl.counts_off);
-  p.any_dirty = reinterpret_cast<int32_t*>(ws + wl.dirty_off);
+  p.unit_dirty = reinterpret_cast<int32_t*>(ws + wl.dirty_off);
   p.keepbits = reinterpret_cast<unsigned long long*>(ws + wl.keepbits_off);
   p.kb_stride = wl.kb_stride;
   p.partials = reinterpret_cast<float*>(ws + wl.partials_off);
@@ -291,7 +291,7 @@ struct CompactPolicy {
   int lazy = 0, dead_num = 0, dead_den = 1;
   unsigned long long* live = nullptr;   // lazy mode: the caller's live masks take the place of the keep masks
   int32_t* nlive = nullptr;             // optional output: live keys per unit
-  const int32_t* t = nullptr;           // the step's t array, if the launch before maintains the workspace's dirty word
+  const int32_t* t = nullptr;           // the step's t array, if the launch before maintains the workspace's dirty words
 };
 
 // local + boundary launches of the compaction; count_first: derive the per-split counts from the mask
@@ -315,7 +315,7 @@ int launch_compact(const corm_desc* d, const WorkspaceLayout& wl, void* workspac
   a.nsplit = wl.nsplit; a.Lcap = d->Lcap; a.do_append = do_append;
   a.lazy = pol.lazy; a.dead_num = pol.dead_num; a.dead_den = pol.dead_den;
   // (a caller who wants kept_idx gets the identity written for untouched units: every workgroup has work then)
-  a.any_dirty = pol.t && !kept_idx ? reinterpret_cast<const int32_t*>(ws + wl.dirty_off) : nullptr;
+  a.unit_dirty = pol.t && !kept_idx ? reinterpret_cast<const int32_t*>(ws + wl.dirty_off) : nullptr;
   a.t = pol.t;
   const dim3 grid(wl.nsplit, d->B * d->Hkv);
   if (count_first) {
@@ -324,15 +324,15 @@ int launch_compact(const corm_desc* d, const WorkspaceLayout& wl, void* workspac
   }
   switch (row_bytes(d)) {
     case 128:
-      hipLaunchKernelGGL((corm_compact_local_kernel<128>), grid, dim3(WG), 0, s, a);
+      hipLaunchKernelGGL((corm_compact_local_kernel<128>), grid, dim3(CWG), 0, s, a);
       hipLaunchKernelGGL((corm_compact_boundary_kernel<128>), grid, dim3(WG), 0, s, a);
       break;
     case 256:
-      hipLaunchKernelGGL((corm_compact_local_kernel<256>), grid, dim3(WG), 0, s, a);
+      hipLaunchKernelGGL((corm_compact_local_kernel<256>), grid, dim3(CWG), 0, s, a);
       hipLaunchKernelGGL((corm_compact_boundary_kernel<256>), grid, dim3(WG), 0, s, a);
       break;
     case 512:
-      hipLaunchKernelGGL((corm_compact_local_kernel<512>), grid, dim3(WG), 0, s, a);
+      hipLaunchKernelGGL((corm_compact_local_kernel<512>), grid, dim3(CWG), 0, s, a);
       hipLaunchKernelGGL((corm_compact_boundary_kernel<512>), grid, dim3(WG), 0, s, a);
       break;
     default: return CORM_EUNSUPPORTED;

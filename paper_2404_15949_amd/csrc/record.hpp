@@ -189,8 +189,8 @@ __global__ __launch_bounds__(WG) void corm_record_kernel(const Params p, const i
       for (int i = 0; i < WAVES; ++i) tot += sh_cnt[tid][i];
       const int chunk = rsplit * RECORD_CHUNKS + tid;
       p.counts[(size_t)unit * p.nsplit + chunk] = tot;
-      // exact mode: a chunk that lost a key means the compaction launches have work (see Params::any_dirty)
-      if (!p.lazy && tot != min(CHUNK, L - chunk * CHUNK)) *p.any_dirty = p.t[0];
+      // exact mode: a chunk that lost a key means the compaction launches have work (see Params::unit_dirty)
+      if (!p.lazy && tot != min(CHUNK, L - chunk * CHUNK)) p.unit_dirty[unit] = dirty_tag(p.t, p.K);
     }
   }
 }

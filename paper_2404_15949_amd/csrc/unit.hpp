@@ -357,10 +357,10 @@ __global__ __launch_bounds__(UNIT_WG) void corm_unit_kernel(const Params p, cons
     __syncthreads();
     const int ntile = (L + CHUNK - 1) / CHUNK;
     if (tid < ntile) p.counts[(size_t)unit * p.nsplit + tid] = sh_tilecnt[tid];
-    if (tid == 0) {   // tell the compaction launches, in one word, whether any unit of this launch needs them
+    if (tid == 0) {   // tell the compaction launches, in one word, whether this unit needs them
       int T = 0;
       for (int k = 0; k < ntile; ++k) T += sh_tilecnt[k];
-      if (compact_policy(LAZY, p.dead_num, p.dead_den, p.Lcap, L, T)) *p.any_dirty = p.t[0];
+      if (compact_policy(LAZY, p.dead_num, p.dead_den, p.Lcap, L, T)) p.unit_dirty[unit] = dirty_tag(p.t, p.K);
     }
   }
 }
