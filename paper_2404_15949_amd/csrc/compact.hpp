@@ -197,6 +197,9 @@ __global__ __launch_bounds__(CWG) void corm_compact_local_kernel(const CompactAr
   if (split != 0 && nothing_to_compact(a, unit)) return;
   const int L = compact_unit_len(a, unit);
   if (split == 0 && tid == 0) a.unit_len[unit] = L;
+  // (a unit that is not compacted: handing its length on was all its first workgroup had to do; lens and the unit's
+  // word are loaded together, nothing waits for the counts)
+  if (split == 0 && nothing_to_compact(a, unit)) return;
   const int nlive = (L + CHUNK - 1) / CHUNK;
   if (split >= nlive) return;
   const int32_t* cnt = a.counts + (size_t)unit * a.nsplit;
@@ -266,6 +269,10 @@ __global__ __launch_bounds__(WG) void corm_compact_boundary_kernel(const Compact
   const int tid = threadIdx.x;
   if (split != 0 && nothing_to_compact(a, unit)) return;
   const int L = a.unit_len[unit];
+  if (split == 0 && !a.nlive && nothing_to_compact(a, unit)) {   // not compacted and nobody asks for the live count
+    if (tid == 0) a.lens[unit] = L;
+    return;
+  }
   const int nlive = (L + CHUNK - 1) / CHUNK;
   if (split >= nlive && split != 0) return;
   const int32_t* cnt = a.counts + (size_t)unit * a.nsplit;
