@@ -305,7 +305,7 @@ def test_summary_only_state_equals_the_ring_state(name, mode):
 @pytest.mark.parametrize("name", ["bf16_mha", "bf16_gqa4", "structured", "sparse_layer"])
 def test_step_without_mask_outputs_equals_the_step_with_them(name, mode):
     """The calls as the benchmark makes them -- keep = kept_idx = NULL, where the compaction launches may leave
-    at once on one word of the workspace -- against the same calls with the mask outputs, whose parity with
+    at once on their unit's word of the workspace -- against the same calls with the mask outputs, whose parity with
     the oracle the other tests establish: lens, the live masks and counts, out, K, V, pos, last_hit and the
     ring must be the same bits after every step; some steps evict in some units only, some in none.  Two
     layers share one workspace, as the layers of a stack do."""
